@@ -1,0 +1,22 @@
+"""Compile the C oracle into oracle/libdessert_oracle.so with gcc."""
+from __future__ import annotations
+
+import pathlib
+import subprocess
+
+HERE = pathlib.Path(__file__).resolve().parent
+SRC = HERE / "dessert_oracle.c"
+LIB = HERE / "libdessert_oracle.so"
+
+
+def build(force: bool = True) -> pathlib.Path:
+    if not force and LIB.exists() and LIB.stat().st_mtime >= SRC.stat().st_mtime:
+        return LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+           str(SRC), "-o", str(LIB)]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,194 @@
+/*
+ * CPU oracle for hashed set-to-set scoring (DESSERT, arxiv 2210.15748).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow definition that the
+ * GPU library is compared against.  It shares no code, header, table or
+ * constant with the HIP sources and must never be called from the product
+ * path.  Every function follows one passage of the paper, cited above it, in
+ * scalar loops with no blocking, fusion or reordering.  The only parallelism
+ * is an optional OpenMP loop over documents (or vectors), which does not
+ * change any result because each iteration writes its own outputs.
+ *
+ * Integer arithmetic is exact (int32/int64).  The floating-point hash path
+ * accumulates in double.
+ *
+ * Readings of the paper taken here (the paper is silent on each):
+ *   - LSH family: signed random projections, one sign bit per projection
+ *     (Sec. 3 lists SRP for cosine; Sec. 5 "concatenation trick" joins C
+ *     hashes per table; a hash range of 128 with C = 7 in Sec. 5 / App. B
+ *     means one bit per hash).
+ *   - bit c of table t comes from projection row t*C + c and lands in bit c
+ *     of the table's code.
+ *   - sign(0): a projection that is exactly zero gives bit 1 (p >= 0).
+ *   - sigma = max, A = sum (Sec. 2, ColBERT's sum of max similarities); the
+ *     division by L in Alg. 2 and the remap of Eq. 1 are left out, so the
+ *     score is an integer in [0, |Q|*L].
+ *   - an empty document scores 0 (Alg. 2 starts every count at 0).
+ *   - top-k order: score descending, ties by ascending document id.
+ *
+ * Parity pins: see tests/test_oracle_pins.py (brute-force sum-of-max on tiny
+ * inputs, the SRP collision-probability closed form, the binomial model of
+ * the counts, invariants, the literal bucket form of Alg. 1 + Alg. 2, a
+ * hand-computed example, numpy lexsort for top-k).  What stays unpinned:
+ * recall / latency on the paper's real datasets (not available).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- projection matrix from a seed ------------------------------------
+ * Counter-based Rademacher rule shared by definition (not by code) with the
+ * library: entry (row, col) of the [P][d] matrix is +1 when the top bit of
+ * mix64(seed + GOLDEN * (row*d + col + 1)) is set, else -1, where mix64 is
+ * the finalizer of the SplitMix64 generator (Steele, Lea, Flood 2014).
+ */
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+void oracle_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t *R)
+{
+    for (uint32_t row = 0; row < P; ++row)
+        for (uint32_t col = 0; col < d; ++col) {
+            uint64_t ctr = (uint64_t)row * d + col + 1;
+            uint64_t z = mix64(seed + 0x9E3779B97F4A7C15ULL * ctr);
+            R[(size_t)row * d + col] = (z >> 63) ? 1 : -1;
+        }
+}
+
+/* ---- hashing: Sec. 3 (SRP family), Sec. 5 concatenation trick, Alg. 1 line
+ * "h = f_t(x_j)" and Alg. 2 line "h_{t,q} = f_t(q)".
+ * X [n][d] int8, R [L*C][d] int8, codes [n][L] u8.
+ * proj (optional, may be NULL) receives the raw projections [n][L*C] int32.
+ */
+void oracle_hash_i8(const int8_t *X, uint64_t n, uint32_t d, const int8_t *R,
+                    uint32_t L, uint32_t C, uint8_t *codes, int32_t *proj)
+{
+    const uint32_t P = L * C;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < (int64_t)n; ++v) {
+        const int8_t *x = X + (size_t)v * d;
+        for (uint32_t t = 0; t < L; ++t) {
+            uint32_t code = 0;
+            for (uint32_t c = 0; c < C; ++c) {
+                const int8_t *r = R + (size_t)(t * C + c) * d;
+                int32_t p = 0;
+                for (uint32_t i = 0; i < d; ++i)
+                    p += (int32_t)r[i] * (int32_t)x[i];
+                if (proj)
+                    proj[(size_t)v * P + t * C + c] = p;
+                if (p >= 0)
+                    code |= 1u << c;
+            }
+            codes[(size_t)v * L + t] = (uint8_t)code;
+        }
+    }
+}
+
+/* Same, for real-valued inputs (the values of the fp16 vectors and of the
+ * fp32 Gaussian matrix, both widened exactly to double by the caller's
+ * float arrays).  proj (optional) receives the double projections.
+ */
+void oracle_hash_fp(const float *X, uint64_t n, uint32_t d, const float *R,
+                    uint32_t L, uint32_t C, uint8_t *codes, double *proj)
+{
+    const uint32_t P = L * C;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < (int64_t)n; ++v) {
+        const float *x = X + (size_t)v * d;
+        for (uint32_t t = 0; t < L; ++t) {
+            uint32_t code = 0;
+            for (uint32_t c = 0; c < C; ++c) {
+                const float *r = R + (size_t)(t * C + c) * d;
+                double p = 0.0;
+                for (uint32_t i = 0; i < d; ++i)
+                    p += (double)r[i] * (double)x[i];
+                if (proj)
+                    proj[(size_t)v * P + t * C + c] = p;
+                if (p >= 0.0)
+                    code |= 1u << c;
+            }
+            codes[(size_t)v * L + t] = (uint8_t)code;
+        }
+    }
+}
+
+/* ---- scoring: Alg. 2, the loop over documents i, query vectors q, tables t
+ * with sigma = max over the document's vectors and A = sum over q.
+ * doc_codes [V][L], offsets [N+1] (document i owns rows offsets[i] ..
+ * offsets[i+1]-1), q_codes [mq][L].  doc_ids [n_scored] selects which
+ * documents to score (NULL: documents 0 .. n_scored-1).  scores [n_scored].
+ */
+void oracle_scores(const uint8_t *doc_codes, const int64_t *offsets, uint32_t L,
+                   const uint8_t *q_codes, uint32_t mq,
+                   const int64_t *doc_ids, uint64_t n_scored, int32_t *scores)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t s = 0; s < (int64_t)n_scored; ++s) {
+        int64_t i = doc_ids ? doc_ids[s] : s;
+        int64_t lo = offsets[i], hi = offsets[i + 1];
+        int32_t score = 0;
+        for (uint32_t q = 0; q < mq; ++q) {
+            const uint8_t *hq = q_codes + (size_t)q * L;
+            int32_t agg = 0;                       /* max over an empty set = 0 */
+            for (int64_t j = lo; j < hi; ++j) {
+                const uint8_t *hx = doc_codes + (size_t)j * L;
+                int32_t cnt = 0;
+                for (uint32_t t = 0; t < L; ++t)
+                    cnt += (hq[t] == hx[t]);
+                if (cnt > agg)
+                    agg = cnt;
+            }
+            score += agg;
+        }
+        scores[s] = score;
+    }
+}
+
+/* ---- top-k: Alg. 2 last line (argmax), widened to the k best.
+ * Order: score descending, then document id ascending.  ids may be NULL
+ * (then the id of entry s is s).  Missing slots (n < k) get id 0xFFFFFFFF,
+ * score -1.  Plain selection: k passes, each picking the best remaining.
+ */
+void oracle_topk(const int32_t *scores, const int64_t *ids, uint64_t n, uint32_t k,
+                 uint32_t *out_ids, int32_t *out_scores)
+{
+    uint8_t *taken = (uint8_t *)calloc(n ? n : 1, 1);
+    for (uint32_t r = 0; r < k; ++r) {
+        int64_t best = -1;
+        for (uint64_t s = 0; s < n; ++s) {
+            if (taken[s])
+                continue;
+            if (best < 0) {
+                best = (int64_t)s;
+                continue;
+            }
+            int64_t id_s = ids ? ids[s] : (int64_t)s;
+            int64_t id_b = ids ? ids[best] : best;
+            if (scores[s] > scores[best] || (scores[s] == scores[best] && id_s < id_b))
+                best = (int64_t)s;
+        }
+        if (best < 0) {
+            out_ids[r] = 0xFFFFFFFFu;
+            out_scores[r] = -1;
+        } else {
+            taken[best] = 1;
+            out_ids[r] = (uint32_t)(ids ? ids[best] : best);
+            out_scores[r] = scores[best];
+        }
+    }
+    free(taken);
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,111 @@
+"""ctypes front end of the C oracle, numpy arrays in and out.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module.
+Each function forwards to the C routine of the same name in dessert_oracle.c,
+which carries the citations; `search` chains them in the order of Alg. 2.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = C.CDLL(os.fspath(path))
+        _lib.oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def rademacher(seed: int, P: int, d: int) -> np.ndarray:
+    R = np.empty((P, d), dtype=np.int8)
+    lib().oracle_rademacher(C.c_uint64(seed), C.c_uint32(P), C.c_uint32(d), _p(R))
+    return R
+
+
+def hash_i8(X: np.ndarray, R: np.ndarray, L: int, Cbits: int, want_proj: bool = False):
+    X = np.ascontiguousarray(X, dtype=np.int8)
+    R = np.ascontiguousarray(R, dtype=np.int8)
+    n, d = X.shape
+    assert R.shape == (L * Cbits, d)
+    codes = np.empty((n, L), dtype=np.uint8)
+    proj = np.empty((n, L * Cbits), dtype=np.int32) if want_proj else None
+    lib().oracle_hash_i8(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits),
+                         _p(codes), _p(proj))
+    return (codes, proj) if want_proj else codes
+
+
+def hash_fp(X: np.ndarray, R: np.ndarray, L: int, Cbits: int, want_proj: bool = False):
+    """X: fp16 (or fp32) values, R: fp32 matrix; both widened exactly to double inside."""
+    X = np.ascontiguousarray(X).astype(np.float32)   # fp16 -> fp32 is exact
+    R = np.ascontiguousarray(R, dtype=np.float32)
+    n, d = X.shape
+    assert R.shape == (L * Cbits, d)
+    codes = np.empty((n, L), dtype=np.uint8)
+    proj = np.empty((n, L * Cbits), dtype=np.float64) if want_proj else None
+    lib().oracle_hash_fp(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits),
+                         _p(codes), _p(proj))
+    return (codes, proj) if want_proj else codes
+
+
+def scores(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, doc_ids=None) -> np.ndarray:
+    doc_codes = np.ascontiguousarray(doc_codes, dtype=np.uint8)
+    q_codes = np.ascontiguousarray(q_codes, dtype=np.uint8)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    L = q_codes.shape[1]
+    assert doc_codes.ndim == 2 and doc_codes.shape[1] == L
+    assert offsets[-1] <= doc_codes.shape[0]
+    n_docs = offsets.shape[0] - 1
+    if doc_ids is None:
+        n = n_docs
+        ids = None
+    else:
+        ids = np.ascontiguousarray(doc_ids, dtype=np.int64)
+        n = ids.shape[0]
+        assert n == 0 or (ids.min() >= 0 and ids.max() < n_docs)
+    out = np.empty(n, dtype=np.int32)
+    lib().oracle_scores(_p(doc_codes), _p(offsets), C.c_uint32(L), _p(q_codes), C.c_uint32(q_codes.shape[0]),
+                        _p(ids), C.c_uint64(n), _p(out))
+    return out
+
+
+def topk(score: np.ndarray, k: int, ids=None):
+    score = np.ascontiguousarray(score, dtype=np.int32)
+    ids_a = None if ids is None else np.ascontiguousarray(ids, dtype=np.int64)
+    out_ids = np.empty(k, dtype=np.uint32)
+    out_scores = np.empty(k, dtype=np.int32)
+    lib().oracle_topk(_p(score), _p(ids_a), C.c_uint64(score.shape[0]), C.c_uint32(k), _p(out_ids), _p(out_scores))
+    return out_ids, out_scores
+
+
+def search(doc_codes, offsets, q_codes_list, k, cand_ids=None):
+    """Alg. 2 for a batch: per query set, score (all docs or its candidates) then top-k.
+
+    Returns (ids [B,k] uint32, scores [B,k] int32, raw score arrays list)."""
+    B = len(q_codes_list)
+    ids_out = np.empty((B, k), dtype=np.uint32)
+    sc_out = np.empty((B, k), dtype=np.int32)
+    raw = []
+    for b in range(B):
+        cand = None if cand_ids is None else np.asarray(cand_ids[b], dtype=np.int64)
+        s = scores(doc_codes, offsets, q_codes_list[b], cand)
+        raw.append(s)
+        ids_out[b], sc_out[b] = topk(s, k, cand)
+    return ids_out, sc_out, raw
