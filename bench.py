@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the hashed set-to-set scoring hot path on one MI355X.
+
+A "step" is one batched search through the C ABI: hash the query vectors, score every
+(query set, candidate document) pair, select the top-k (rows S1-S5 of the hot path).  The index
+(rows H1-H3: hashing of all document vectors and the code layout) is built before the timed
+region, as in the paper's split between Alg. 1 and Alg. 2, and its own throughput is timed in the
+same run and reported under "index_build".
+
+Workload: the candidate-rerank preset (1M documents in HBM, lengths ~ truncated normal(70, 25),
+d=128 int8, L=32, C=7, 256 query sets x 32 vectors, 4096 candidates each, top-10), all synthetic and
+generated on the device from fixed seeds.
+
+Prints ONE JSON line; see the design doc for the meaning of every field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="preset number (3 = candidate rerank, the metric's workload)")
+    ap.add_argument("--n-docs", type=int, default=None, help="shrink the preset (for quick trials; not the metric)")
+    ap.add_argument("--n-queries", type=int, default=None)
+    ap.add_argument("--build-reps", type=int, default=5)
+    ap.add_argument("--score-algo", type=int, default=0)
+    ap.add_argument("--hash-algo", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-queries", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no sharding, no collectives); --gpus must be 1")
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2210_15748_amd as dz
+    from synth import gen
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the library has no CPU path")
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    w = gen.make(args.config, device=dev, n_docs=args.n_docs, n_queries=args.n_queries)
+    p = w.preset
+    torch.cuda.synchronize()
+    log(f"[bench] generated {p.name}: N={w.n_docs} V={w.n_vectors} B={p.n_queries} in {time.time() - t0:.1f}s")
+
+    ix = dz.create(p.d, p.L, p.C, dtype=dz.I8 if p.dtype == "i8" else dz.F16,
+                   proj_kind=dz.PROJ_RADEMACHER_I8 if p.proj_kind == "rademacher" else dz.PROJ_GAUSSIAN_F32,
+                   proj=w.proj)
+    dz.set_algo(ix, args.hash_algo, args.score_algo)
+    dz.enable_timing(ix, True)
+
+    # ---- index build (H1-H3), timed on its own
+    codes = torch.empty(w.n_vectors, p.L, dtype=torch.uint8, device=dev)
+    offsets = torch.empty(w.n_docs + 1, dtype=torch.int64, device=dev)
+    lengths = w.lengths.numpy().astype(np.uint32)
+    dz.build_index(ix, w.docs, lengths, codes, offsets)          # warm-up + the index used below
+    torch.cuda.synchronize()
+    tb = time.perf_counter()
+    for _ in range(args.build_reps):
+        dz.build_index(ix, w.docs, lengths, codes, offsets)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - tb) * 1e3 / max(1, args.build_reps)
+    hash_kernel_ms = float(np.mean([dz.get_timing(ix, i)["hash_ms"] for i in range(min(args.build_reps, 64))])) \
+        if args.build_reps else 0.0
+    log(f"[bench] build_index: {build_ms:.3f} ms/call, hash kernel {hash_kernel_ms:.3f} ms")
+
+    # ---- search (S1-S5)
+    B, k = p.n_queries, p.k
+    cand = None if w.cand_ids is None else w.cand_ids.to(torch.int32).contiguous()
+    n_scored = B * (p.n_cand if p.n_cand else w.n_docs)
+    ws = torch.empty(dz.workspace_bytes(ix, B, w.queries.shape[0], n_scored, k), dtype=torch.uint8, device=dev)
+    out_ids = torch.empty(B, k, dtype=torch.uint32, device=dev)
+    out_sc = torch.empty(B, k, dtype=torch.int32, device=dev)
+    ql = w.q_lengths.numpy().astype(np.uint32)
+    co = None if cand is None else np.arange(B + 1, dtype=np.uint64) * p.n_cand
+
+    def step():
+        dz.search(ix, w.queries, ql, k, cand_ids=cand, cand_offsets=co, workspace=ws, out_ids=out_ids, out_scores=out_sc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed * 1e3 / args.steps
+    n_t = min(args.steps, 64)
+    tim = [dz.get_timing(ix, i) for i in range(n_t)]
+    score_ms = float(np.mean([t["score_ms"] for t in tim]))
+    qhash_ms = float(np.mean([t["hash_ms"] for t in tim]))
+    topk_ms = float(np.mean([t["topk_ms"] for t in tim]))
+    value = n_scored / (ms_per_step * 1e-3)
+    log(f"[bench] search: {ms_per_step:.4f} ms/step  (hash {qhash_ms:.4f}  score {score_ms:.4f}  topk {topk_ms:.4f})")
+
+    # ---- roofline of the dominant kernel (scoring): algorithmic bytes = code bytes of every scored document
+    if cand is not None:
+        doc_len = w.lengths.to(dev)[w.cand_ids.reshape(-1)]
+        code_bytes = int(doc_len.sum().item()) * p.L
+    else:
+        code_bytes = w.n_vectors * p.L * B      # each query set reads every document's codes once
+    achieved = code_bytes / (score_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "score_masklut_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        nb = max(1, min(args.cpu_sample_queries, B))
+        R = w.proj.cpu().numpy()
+        off_all = w.offsets.numpy()
+        if cand is not None:
+            ids = w.cand_ids[:nb].cpu().numpy()
+            uniq, inv = np.unique(ids.reshape(-1), return_inverse=True)
+        else:
+            uniq = np.arange(min(w.n_docs, 8192))
+            inv = None
+        rows = np.concatenate([np.arange(off_all[i], off_all[i + 1]) for i in uniq])
+        sub_docs = w.docs[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        sub_len = (off_all[uniq + 1] - off_all[uniq])
+        sub_off = np.concatenate([[0], np.cumsum(sub_len)])
+        qv = w.queries[: nb * p.q_len].cpu().numpy()
+        th = time.perf_counter()
+        fn = orc.hash_i8 if p.dtype == "i8" else orc.hash_fp
+        dc = fn(sub_docs, R, p.L, p.C)
+        qc = fn(qv, R, p.L, p.C)
+        hash_s = time.perf_counter() - th
+        ts = time.perf_counter()
+        total = 0
+        got = dz.scores(ix, w.queries[: nb * p.q_len].contiguous(), ql[:nb],
+                        cand_ids=None if cand is None else cand[:nb].contiguous()).cpu().numpy().reshape(nb, -1)
+        ok = True
+        ts = time.perf_counter()
+        for b in range(nb):
+            sel = inv.reshape(nb, -1)[b] if inv is not None else None
+            s = orc.scores(dc, sub_off, qc[b * p.q_len:(b + 1) * p.q_len], sel)
+            total += s.shape[0]
+            ok = ok and bool(np.array_equal(s, got[b][: s.shape[0]]))
+        score_s = time.perf_counter() - ts
+        cpu = {"value": round(total / score_s, 1), "unit": "doc-set scores/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"{nb} query sets x {total // nb} documents each ({rows.shape[0]} vectors hashed by the oracle)",
+               "seconds": round(score_s, 3), "hash_vectors_per_s": round((rows.shape[0] + qv.shape[0]) / hash_s, 1),
+               "hash_seconds": round(hash_s, 3), "matches_gpu_on_sample": ok}
+        log(f"[bench] oracle: {cpu}")
+
+    line = {
+        "metric": "doc-set scores/sec (|Q|=32, m~70, L=32, C=7)",
+        "value": round(value, 1),
+        "unit": "doc-set scores/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": p.name, "n_docs": w.n_docs, "n_vectors": w.n_vectors, "d": p.d, "L": p.L, "C": p.C,
+                   "query_sets": B, "q_len": p.q_len, "candidates_per_query": p.n_cand, "k": k,
+                   "step": "dessert_search: query hashing + scoring + top-k (index built once, before the timed region)"},
+        "kernel_ms": {"query_hash": round(qhash_ms, 5), "score": round(score_ms, 5), "topk": round(topk_ms, 5)},
+        "index_build": {"metric": "index-build vectors/sec", "value": round(w.n_vectors / (build_ms * 1e-3), 1),
+                        "unit": "vectors/s", "ms_per_call": round(build_ms, 4), "hash_kernel_ms": round(hash_kernel_ms, 4),
+                        "reps": args.build_reps,
+                        "roofline": {"bound": "hbm", "kernel": "hash_mfma_i8_kernel",
+                                     "achieved": round(w.n_vectors * (p.d * (1 if p.dtype == "i8" else 2) + p.L) / (hash_kernel_ms * 1e-3) / 1e9, 2)
+                                     if hash_kernel_ms else None,
+                                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                     "frac": round(w.n_vectors * (p.d * (1 if p.dtype == "i8" else 2) + p.L) / (hash_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                     if hash_kernel_ms else None}},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

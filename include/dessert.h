@@ -1,0 +1,169 @@
+/*
+ * dessert.h -- C ABI of the MI355X (gfx950) library for hashed set-to-set
+ * scoring: vector-set search with vector-set queries (DESSERT, arxiv
+ * 2210.15748).
+ *
+ * The paper's problem statement (Sec. 1.1): given N vector sets S_1..S_N and
+ * a query set Q, return the sets with the largest F(Q,S) = A(sigma(sim(q,x))).
+ * The library implements the paper's estimator of F (Alg. 1 and Alg. 2) with
+ * signed-random-projection hashes, sigma = max and A = sum:
+ *
+ *     code_t(x)  = C sign bits of the projections t*C .. t*C+C-1   (Sec. 3, Sec. 5)
+ *     cnt(q,x)   = #{ t < L : code_t(q) == code_t(x) }              (Alg. 2, inner loops)
+ *     score(Q,S) = sum_{q in Q} max_{x in S} cnt(q,x)               (Alg. 2, sigma then A)
+ *
+ * followed by the k best documents (Alg. 2 last line, widened from argmax).
+ * The division by L in Alg. 2 and the remap of Eq. 1 are not applied: scores
+ * are integers in [0, |Q|*L].
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses on config.device, "host"
+ *     pointers are ordinary host memory.  No torch or C++ type crosses the ABI.
+ *   - Ownership: the caller allocates and frees every buffer it passes in
+ *     (vectors, codes, offsets, workspace, outputs).  The handle owns only its
+ *     host metadata and the device copy of the projection matrix it makes in
+ *     dessert_create.  Buffers given to dessert_build_index must stay alive
+ *     and unchanged while the index is searched.
+ *   - Asynchrony: all device work is enqueued on config.stream; calls return
+ *     without synchronising.  Host arrays are read before the call returns.
+ *     Outputs are valid once the caller has synchronised the stream.
+ *   - Errors: every call returns a status.  Argument errors are detected on
+ *     the host before anything is launched (DESSERT_EINVAL), HIP failures
+ *     give DESSERT_EHIP; dessert_last_error() returns a thread-local message.
+ *   - Document ids are 0-based positions in build order.
+ *   - Bit conventions: projection row t*C+c gives bit c of table t's code; a
+ *     projection that is exactly 0 gives bit 1 (p >= 0).
+ *   - Top-k order: score descending, ties by ascending document id; if fewer
+ *     than k documents were scored the remaining slots hold id 0xFFFFFFFF and
+ *     score -1.  Candidate ids are scored as given (duplicates appear twice).
+ *   - Limits: 1 <= C <= 8, L a multiple of 4 with 4 <= L <= 128, d >= 1,
+ *     (total query vectors of one set) * L <= 65535, k <= 4096.  Candidate
+ *     ids must be < n_docs (not checked on the device).
+ */
+#ifndef DESSERT_H
+#define DESSERT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dessert_index dessert_index_t;
+
+typedef enum {
+    DESSERT_OK = 0,
+    DESSERT_EINVAL = 1,   /* bad argument, nothing launched */
+    DESSERT_ENOMEM = 2,   /* host or device allocation inside the library failed */
+    DESSERT_EHIP = 3,     /* a HIP call failed; see dessert_last_error() */
+    DESSERT_ESTATE = 4    /* call order: search before build_index */
+} dessert_status_t;
+
+enum { DESSERT_I8 = 0, DESSERT_F16 = 1 };                       /* vector element type */
+enum { DESSERT_PROJ_RADEMACHER_I8 = 0, DESSERT_PROJ_GAUSSIAN_F32 = 1 };
+
+/* Kernel variants, for cross-checking and measurement (dessert_set_algo). */
+enum { DESSERT_HASH_AUTO = 0, DESSERT_HASH_SCALAR = 1, DESSERT_HASH_MFMA = 2 };
+enum { DESSERT_SCORE_AUTO = 0, DESSERT_SCORE_BYTECMP = 1, DESSERT_SCORE_MASKLUT = 2 };
+
+typedef struct {
+    uint32_t d;            /* vector dimension */
+    uint32_t L;            /* number of hash tables (Sec. 3) */
+    uint32_t C;            /* sign bits concatenated per table (Sec. 5, concatenation trick) */
+    uint32_t dtype;        /* DESSERT_I8 or DESSERT_F16 */
+    uint32_t proj_kind;    /* DESSERT_PROJ_RADEMACHER_I8: int8 entries in {-1,+1};
+                              DESSERT_PROJ_GAUSSIAN_F32: float entries */
+    int32_t  device;       /* HIP device ordinal */
+    uint64_t seed;         /* used only when proj_dev == NULL */
+    const void *proj_dev;  /* dev, [L*C][d] row-major, int8 or float by proj_kind; copied by
+                              dessert_create.  NULL: derive a Rademacher matrix from seed:
+                              entry (row,col) = +1 iff the top bit of
+                              mix64(seed + 0x9E3779B97F4A7C15*(row*d+col+1)) is set, mix64 being the
+                              SplitMix64 finalizer.  NULL with the Gaussian kind is an error. */
+    void *stream;          /* hipStream_t all work is enqueued on (NULL = default stream) */
+} dessert_config_t;
+
+/* Create a handle: validates the configuration, copies (or generates) the
+ * projection matrix into library-owned device memory.  The hash functions
+ * f_1..f_L of Sec. 3 are fixed from here on. */
+dessert_status_t dessert_create(const dessert_config_t *config, dessert_index_t **out);
+void dessert_destroy(dessert_index_t *index);
+
+/* Copy the projection matrix in use ([L*C][d], int8 or float) to proj_out_dev. */
+dessert_status_t dessert_get_projection(const dessert_index_t *index, void *proj_out_dev);
+
+/* Select kernel variants (DESSERT_HASH_*, DESSERT_SCORE_*).  A variant that
+ * does not support the configuration makes the later call return EINVAL. */
+dessert_status_t dessert_set_algo(dessert_index_t *index, int hash_algo, int score_algo);
+
+/* Bytes of the code array for n_vectors vectors: n_vectors * L (one byte per
+ * vector and table, vector-major, no padding). */
+size_t dessert_code_bytes(const dessert_index_t *index, uint64_t n_vectors);
+
+/* Hash n vectors (Alg. 1 line "h = f_t(x_j)", Alg. 2 line "h_{t,q} = f_t(q)").
+ * vectors_dev: dev, [n][d] row-major of config.dtype.  codes_dev: dev, [n][L] u8. */
+dessert_status_t dessert_hash(const dessert_index_t *index, const void *vectors_dev, uint64_t n,
+                              uint8_t *codes_dev);
+
+/* Build the index (Alg. 1): hash every vector of every document and record
+ * where each document's codes live.
+ *   vectors_dev   dev, [n_vectors][d]: the documents' vectors, concatenated in document order
+ *   lengths_host  host, [n_docs] u32: m_i = |S_i| (0 allowed); sum must equal n_vectors
+ *   codes_dev     dev, out, dessert_code_bytes(n_vectors): codes_dev[(offsets[i]+j)*L + t] = f_t(x_j of S_i)
+ *   offsets_dev   dev, out, [n_docs+1] u64: exclusive scan of lengths (in vectors)
+ * The handle remembers codes_dev / offsets_dev for later searches. */
+dessert_status_t dessert_build_index(dessert_index_t *index, const void *vectors_dev, uint64_t n_vectors,
+                                     const uint32_t *lengths_host, uint64_t n_docs,
+                                     uint8_t *codes_dev, uint64_t *offsets_dev);
+
+/* Workspace bytes needed by dessert_search / dessert_scores for a batch of
+ * n_queries query sets with total_q_vectors vectors in all, total_scored
+ * (query set, document) pairs (n_queries * n_docs when every document is
+ * scored) and k results per query set. */
+size_t dessert_search_workspace_bytes(const dessert_index_t *index, uint32_t n_queries,
+                                      uint64_t total_q_vectors, uint64_t total_scored, uint32_t k);
+
+/* Query the index (Alg. 2) for a batch of query sets.
+ *   q_vectors_dev      dev, [sum q_lengths][d]: query vectors, query sets concatenated
+ *   q_lengths_host     host, [n_queries] u32: |Q_b| >= 1
+ *   cand_ids_dev       dev, u32 document ids to score, the lists of all query sets concatenated;
+ *                      NULL = score every document for every query set
+ *   cand_offsets_host  host, [n_queries+1] u64: query set b scores cand_ids[cand_offsets[b] ..
+ *                      cand_offsets[b+1]); ignored when cand_ids_dev is NULL
+ *   workspace_dev      dev, at least dessert_search_workspace_bytes(...) bytes, 256-byte aligned
+ *   out_ids_dev        dev, out, [n_queries][k] u32
+ *   out_scores_dev     dev, out, [n_queries][k] i32
+ */
+dessert_status_t dessert_search(const dessert_index_t *index, const void *q_vectors_dev,
+                                const uint32_t *q_lengths_host, uint32_t n_queries,
+                                const uint32_t *cand_ids_dev, const uint64_t *cand_offsets_host,
+                                uint32_t k, void *workspace_dev, size_t workspace_bytes,
+                                uint32_t *out_ids_dev, int32_t *out_scores_dev);
+
+/* Same as dessert_search up to and including the outer aggregation A, without
+ * the top-k: raw integer scores.  out_scores_dev: dev, out, i32; candidate
+ * mode: [cand_offsets[n_queries]] in candidate order; otherwise
+ * [n_queries][n_docs]. */
+dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vectors_dev,
+                                const uint32_t *q_lengths_host, uint32_t n_queries,
+                                const uint32_t *cand_ids_dev, const uint64_t *cand_offsets_host,
+                                void *workspace_dev, size_t workspace_bytes, int32_t *out_scores_dev);
+
+/* Per-kernel timing of dessert_search / dessert_scores / dessert_build_index
+ * calls on this handle, measured with HIP events recorded on config.stream
+ * around each stage (off by default; enabling adds event records but no
+ * synchronisation to the calls).  The last 64 timed calls are kept.
+ * dessert_get_timing waits for the chosen call's last event and writes
+ * milliseconds: ms[0] hashing, ms[1] scoring, ms[2] top-k, ms[3] whole call;
+ * stages that did not run give 0.  calls_back = 0 is the most recent call. */
+dessert_status_t dessert_enable_timing(dessert_index_t *index, int enable);
+dessert_status_t dessert_get_timing(dessert_index_t *index, uint32_t calls_back, float ms[4]);
+
+const char *dessert_last_error(void);
+const char *dessert_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DESSERT_H */

@@ -1,0 +1,486 @@
+// C ABI of the library (declared in include/dessert.h): argument validation,
+// workspace carving and kernel sequencing.  No compute happens on the host
+// beyond the exclusive scan of the document lengths in dessert_build_index.
+#include "../../include/dessert.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace dessert;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+dessert_status_t fail(dessert_status_t st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(DESSERT_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        ok = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+struct dessert_index {
+    dessert_config_t cfg{};
+    hipStream_t stream = nullptr;
+    void* proj = nullptr;       // device, [L*C][d] int8 or float (library-owned copy)
+    void* proj_mfma = nullptr;  // device, MFMA-ordered int8 copy (or null)
+    int hash_algo = DESSERT_HASH_AUTO;
+    int score_algo = DESSERT_SCORE_AUTO;
+    // index state
+    const uint8_t* codes = nullptr;
+    const uint64_t* offsets = nullptr;
+    uint64_t n_docs = 0, n_vectors = 0;
+    bool built = false;
+    // pinned staging for the offsets upload
+    uint64_t* h_offsets = nullptr;
+    size_t h_offsets_cap = 0;
+    hipEvent_t upload_done = nullptr;  // recorded after each offsets upload
+    bool upload_pending = false;
+    // pinned staging ring for the per-batch offset arrays of a search (keeps the uploads asynchronous)
+    static constexpr unsigned kMetaSlots = 8;
+    struct MetaSlot {
+        char* host = nullptr;
+        size_t cap = 0;
+        hipEvent_t done = nullptr;
+        bool pending = false;
+    };
+    MetaSlot meta[kMetaSlots];
+    unsigned meta_next = 0;
+    // timing: a ring of event sets so that a run of calls can be timed without synchronising
+    struct TimingSlot {
+        hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        bool hash = false, score = false, topk = false, any = false;
+    };
+    static constexpr unsigned kTimingSlots = 64;
+    bool timing = false;
+    TimingSlot slots[kTimingSlots];
+    uint64_t timed_calls = 0;
+    TimingSlot& begin_timed() {
+        TimingSlot& s = slots[timed_calls % kTimingSlots];
+        s.hash = s.score = s.topk = s.any = false;
+        return s;
+    }
+};
+
+namespace {
+
+size_t proj_elem_bytes(uint32_t kind) { return kind == DESSERT_PROJ_RADEMACHER_I8 ? 1 : 4; }
+
+bool use_mfma(const dessert_index* ix) {
+    return ix->proj_mfma && ix->cfg.dtype == DESSERT_I8 && ix->cfg.proj_kind == DESSERT_PROJ_RADEMACHER_I8 &&
+           hash_mfma_supported(ix->cfg.d, ix->cfg.L, ix->cfg.C);
+}
+
+dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, uint8_t* codes) {
+    if (n == 0) return DESSERT_OK;
+    int algo = ix->hash_algo;
+    bool aligned = ((uintptr_t)X % 16 == 0) && ((uintptr_t)codes % 16 == 0);
+    if (algo == DESSERT_HASH_AUTO) algo = (use_mfma(ix) && aligned) ? DESSERT_HASH_MFMA : DESSERT_HASH_SCALAR;
+    if (algo == DESSERT_HASH_MFMA) {
+        if (!use_mfma(ix)) return fail(DESSERT_EINVAL, "MFMA hashing needs int8 vectors, +-1 projections, d in {64,128,256}, L in {16,32,64}");
+        if (!aligned) return fail(DESSERT_EINVAL, "MFMA hashing needs 16-byte aligned vectors and codes");
+        HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
+    } else if (algo == DESSERT_HASH_SCALAR) {
+        HIP_TRY(launch_hash_scalar(X, ix->cfg.dtype, n, ix->cfg.d, ix->proj, ix->cfg.proj_kind, ix->cfg.L, ix->cfg.C, codes,
+                                   ix->stream));
+    } else {
+        return fail(DESSERT_EINVAL, "unknown hash algorithm %d", algo);
+    }
+    return DESSERT_OK;
+}
+
+// Workspace layout for a search batch (all regions 256-byte aligned).
+struct Workspace {
+    size_t qcodes, q_off, cand_off, scores, partial, total;
+};
+
+Workspace carve(const dessert_index* ix, uint32_t B, uint64_t total_q, uint64_t total_scored, uint64_t max_scored, uint32_t k,
+                bool own_scores) {
+    Workspace w{};
+    size_t p = 0;
+    w.qcodes = p;   p += align_up((size_t)total_q * ix->cfg.L, 256);
+    w.q_off = p;    p += align_up(((size_t)B + 1) * 4, 256);
+    w.cand_off = p; p += align_up(((size_t)B + 1) * 8, 256);
+    w.scores = p;   if (own_scores) p += align_up((size_t)total_scored * 4, 256);
+    w.partial = p;
+    uint32_t slices = topk_slices(max_scored);
+    if (k && slices > 1) p += align_up((size_t)B * slices * k * 8, 256);
+    w.total = p;
+    return w;
+}
+
+struct Batch {
+    std::vector<uint32_t> q_off;
+    uint64_t total_q = 0, total_scored = 0, max_scored = 0;
+    uint32_t max_q_len = 0;
+};
+
+dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, const uint32_t* q_lengths, uint32_t B,
+                             const uint32_t* cand_ids, const uint64_t* cand_off, Batch* out) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!ix->built) return fail(DESSERT_ESTATE, "dessert_build_index has not been called");
+    if (B == 0) return DESSERT_OK;
+    if (B > 65535) return fail(DESSERT_EINVAL, "n_queries > 65535");
+    if (!q_vectors || !q_lengths) return fail(DESSERT_EINVAL, "q_vectors_dev / q_lengths_host is NULL");
+    out->q_off.assign(B + 1, 0);
+    for (uint32_t b = 0; b < B; ++b) {
+        if (q_lengths[b] == 0) return fail(DESSERT_EINVAL, "q_lengths_host[%u] = 0", b);
+        if ((uint64_t)q_lengths[b] * ix->cfg.L > 65535)
+            return fail(DESSERT_EINVAL, "q_lengths_host[%u] * L = %llu exceeds 65535", b,
+                        (unsigned long long)q_lengths[b] * ix->cfg.L);
+        uint64_t nxt = (uint64_t)out->q_off[b] + q_lengths[b];
+        if (nxt > 0xFFFFFFFFull) return fail(DESSERT_EINVAL, "more than 2^32-1 query vectors");
+        out->q_off[b + 1] = (uint32_t)nxt;
+        if (q_lengths[b] > out->max_q_len) out->max_q_len = q_lengths[b];
+    }
+    out->total_q = out->q_off[B];
+    if (cand_ids) {
+        if (!cand_off) return fail(DESSERT_EINVAL, "cand_offsets_host is NULL with candidate ids given");
+        if (cand_off[0] != 0) return fail(DESSERT_EINVAL, "cand_offsets_host[0] must be 0");
+        for (uint32_t b = 0; b < B; ++b) {
+            if (cand_off[b + 1] < cand_off[b]) return fail(DESSERT_EINVAL, "cand_offsets_host not non-decreasing at %u", b);
+            uint64_t c = cand_off[b + 1] - cand_off[b];
+            if (c > out->max_scored) out->max_scored = c;
+        }
+        out->total_scored = cand_off[B];
+    } else {
+        out->max_scored = ix->n_docs;
+        out->total_scored = (uint64_t)B * ix->n_docs;
+    }
+    if (out->max_scored > 0x7FFFFFFFull * 64) return fail(DESSERT_EINVAL, "too many documents per query set");
+    return DESSERT_OK;
+}
+
+// Shared body of dessert_search (k > 0) and dessert_scores (k == 0).
+dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uint32_t* q_lengths, uint32_t B,
+                             const uint32_t* cand_ids, const uint64_t* cand_off, uint32_t k, void* workspace,
+                             size_t workspace_bytes, int32_t* scores_out, uint32_t* out_ids, int32_t* out_scores) {
+    Batch bt;
+    dessert_status_t st = check_batch(ix, q_vectors, q_lengths, B, cand_ids, cand_off, &bt);
+    if (st != DESSERT_OK) return st;
+    if (B == 0) return DESSERT_OK;
+    if (!workspace) return fail(DESSERT_EINVAL, "workspace_dev is NULL");
+    if ((uintptr_t)workspace % 256) return fail(DESSERT_EINVAL, "workspace_dev must be 256-byte aligned");
+    const bool own_scores = scores_out == nullptr;
+    Workspace w = carve(ix, B, bt.total_q, bt.total_scored, bt.max_scored, k, own_scores);
+    if (workspace_bytes < w.total)
+        return fail(DESSERT_EINVAL, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, w.total);
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+
+    char* ws = (char*)workspace;
+    uint8_t* qcodes = (uint8_t*)(ws + w.qcodes);
+    uint32_t* d_q_off = (uint32_t*)(ws + w.q_off);
+    uint64_t* d_cand_off = (uint64_t*)(ws + w.cand_off);
+    int32_t* scores = own_scores ? (int32_t*)(ws + w.scores) : scores_out;
+
+    dessert_index::TimingSlot& ts = ix->begin_timed();
+    if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
+    // the offset arrays go through a pinned slot so that the uploads never block the host
+    {
+        dessert_index::MetaSlot& ms = ix->meta[ix->meta_next++ % dessert_index::kMetaSlots];
+        if (ms.pending) {
+            HIP_TRY(hipEventSynchronize(ms.done));
+            ms.pending = false;
+        }
+        const size_t qb = align_up(((size_t)B + 1) * 4, 256), cb = ((size_t)B + 1) * 8;
+        if (ms.cap < qb + cb) {
+            if (ms.host) (void)hipHostFree(ms.host);
+            ms.host = nullptr;
+            ms.cap = 0;
+            hipError_t e = hipHostMalloc((void**)&ms.host, 2 * (qb + cb), hipHostMallocDefault);
+            if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipHostMalloc(batch offsets): %s", hipGetErrorString(e));
+            ms.cap = 2 * (qb + cb);
+        }
+        if (!ms.done) HIP_TRY(hipEventCreateWithFlags(&ms.done, hipEventDisableTiming));
+        memcpy(ms.host, bt.q_off.data(), ((size_t)B + 1) * 4);
+        HIP_TRY(hipMemcpyAsync(d_q_off, ms.host, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, ix->stream));
+        if (cand_ids) {
+            memcpy(ms.host + qb, cand_off, cb);
+            HIP_TRY(hipMemcpyAsync(d_cand_off, ms.host + qb, cb, hipMemcpyHostToDevice, ix->stream));
+        }
+        HIP_TRY(hipEventRecord(ms.done, ix->stream));
+        ms.pending = true;
+    }
+
+    st = run_hash(ix, q_vectors, bt.total_q, qcodes);
+    if (st != DESSERT_OK) return st;
+    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
+
+    ScoreArgs sa{};
+    sa.codes = ix->codes; sa.offsets = ix->offsets; sa.n_docs = ix->n_docs;
+    sa.L = ix->cfg.L; sa.C = ix->cfg.C;
+    sa.qcodes = qcodes; sa.q_off = d_q_off; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
+    sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr;
+    sa.max_scored = bt.max_scored; sa.scores = scores;
+    int algo = ix->score_algo;
+    if (algo == DESSERT_SCORE_AUTO)
+        algo = score_masklut_supported(ix->cfg.L, ix->cfg.C) ? DESSERT_SCORE_MASKLUT : DESSERT_SCORE_BYTECMP;
+    if (algo == DESSERT_SCORE_MASKLUT) {
+        if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
+            return fail(DESSERT_EINVAL, "mask-table scoring needs L in {16,32,64,128}");
+        HIP_TRY(launch_score_masklut(sa, ix->stream));
+    } else if (algo == DESSERT_SCORE_BYTECMP) {
+        HIP_TRY(launch_score_bytecmp(sa, ix->stream));
+    } else {
+        return fail(DESSERT_EINVAL, "unknown scoring algorithm %d", algo);
+    }
+    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[2], ix->stream)); ts.score = true; }
+
+    if (k) {
+        TopkArgs ta{};
+        ta.scores = scores; ta.cand_ids = cand_ids; ta.cand_off = sa.cand_off; ta.n_docs = ix->n_docs;
+        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k;
+        ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
+        HIP_TRY(launch_topk(ta, ix->stream));
+        if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
+    }
+    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    return DESSERT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dessert_last_error(void) { return g_err; }
+const char* dessert_version(void) { return "dessert-gfx950 0.1"; }
+
+dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out) {
+    if (!c || !out) return fail(DESSERT_EINVAL, "config or out is NULL");
+    *out = nullptr;
+    if (c->d == 0) return fail(DESSERT_EINVAL, "d must be >= 1");
+    if (c->C < 1 || c->C > 8) return fail(DESSERT_EINVAL, "C must be in 1..8 (codes are one byte), got %u", c->C);
+    if (c->L < 4 || c->L > 128 || c->L % 4) return fail(DESSERT_EINVAL, "L must be a multiple of 4 in 4..128, got %u", c->L);
+    if (c->dtype != DESSERT_I8 && c->dtype != DESSERT_F16) return fail(DESSERT_EINVAL, "unknown dtype %u", c->dtype);
+    if (c->proj_kind != DESSERT_PROJ_RADEMACHER_I8 && c->proj_kind != DESSERT_PROJ_GAUSSIAN_F32)
+        return fail(DESSERT_EINVAL, "unknown proj_kind %u", c->proj_kind);
+    if (!c->proj_dev && c->proj_kind == DESSERT_PROJ_GAUSSIAN_F32)
+        return fail(DESSERT_EINVAL, "a Gaussian projection matrix must be passed in proj_dev");
+    if ((uint64_t)c->d * c->L * c->C > (1ull << 31)) return fail(DESSERT_EINVAL, "projection matrix too large");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
+        return fail(DESSERT_EHIP, "no HIP device available: this library has no CPU path");
+    if (c->device < 0 || c->device >= ndev) return fail(DESSERT_EINVAL, "device %d out of range (0..%d)", c->device, ndev - 1);
+
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", c->device);
+    dessert_index* ix = new (std::nothrow) dessert_index();
+    if (!ix) return fail(DESSERT_ENOMEM, "out of host memory");
+    ix->cfg = *c;
+    ix->cfg.proj_dev = nullptr;
+    ix->stream = (hipStream_t)c->stream;
+    const size_t P = (size_t)c->L * c->C;
+    const size_t pbytes = P * c->d * proj_elem_bytes(c->proj_kind);
+    hipError_t e = hipMalloc(&ix->proj, pbytes);
+    if (e != hipSuccess) {
+        delete ix;
+        return fail(DESSERT_ENOMEM, "hipMalloc(projection, %zu): %s", pbytes, hipGetErrorString(e));
+    }
+    if (c->proj_dev)
+        e = hipMemcpyAsync(ix->proj, c->proj_dev, pbytes, hipMemcpyDeviceToDevice, ix->stream);
+    else
+        e = launch_rademacher(c->seed, (uint32_t)P, c->d, (int8_t*)ix->proj, ix->stream);
+    if (e == hipSuccess && c->dtype == DESSERT_I8 && c->proj_kind == DESSERT_PROJ_RADEMACHER_I8 &&
+        hash_mfma_supported(c->d, c->L, c->C)) {
+        e = hipMalloc(&ix->proj_mfma, mfma_proj_bytes(c->d, c->L));
+        if (e == hipSuccess) e = launch_repack_proj_i8((const int8_t*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->upload_done, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        dessert_destroy(ix);
+        return fail(DESSERT_EHIP, "projection setup: %s", hipGetErrorString(e));
+    }
+    *out = ix;
+    return DESSERT_OK;
+}
+
+void dessert_destroy(dessert_index_t* ix) {
+    if (!ix) return;
+    DeviceGuard guard(ix->cfg.device);
+    (void)hipStreamSynchronize(ix->stream);
+    if (ix->upload_done) (void)hipEventDestroy(ix->upload_done);
+    if (ix->proj) (void)hipFree(ix->proj);
+    if (ix->proj_mfma) (void)hipFree(ix->proj_mfma);
+    if (ix->h_offsets) (void)hipHostFree(ix->h_offsets);
+    for (auto& slot : ix->slots)
+        for (auto& ev : slot.ev)
+            if (ev) (void)hipEventDestroy(ev);
+    for (auto& m : ix->meta) {
+        if (m.host) (void)hipHostFree(m.host);
+        if (m.done) (void)hipEventDestroy(m.done);
+    }
+    delete ix;
+}
+
+dessert_status_t dessert_get_projection(const dessert_index_t* ix, void* proj_out_dev) {
+    if (!ix || !proj_out_dev) return fail(DESSERT_EINVAL, "NULL argument");
+    DeviceGuard guard(ix->cfg.device);
+    size_t bytes = (size_t)ix->cfg.L * ix->cfg.C * ix->cfg.d * proj_elem_bytes(ix->cfg.proj_kind);
+    HIP_TRY(hipMemcpyAsync(proj_out_dev, ix->proj, bytes, hipMemcpyDeviceToDevice, ix->stream));
+    return DESSERT_OK;
+}
+
+dessert_status_t dessert_set_algo(dessert_index_t* ix, int hash_algo, int score_algo) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (hash_algo < 0 || hash_algo > DESSERT_HASH_MFMA) return fail(DESSERT_EINVAL, "unknown hash algorithm %d", hash_algo);
+    if (score_algo < 0 || score_algo > DESSERT_SCORE_MASKLUT)
+        return fail(DESSERT_EINVAL, "unknown scoring algorithm %d", score_algo);
+    ix->hash_algo = hash_algo;
+    ix->score_algo = score_algo;
+    return DESSERT_OK;
+}
+
+size_t dessert_code_bytes(const dessert_index_t* ix, uint64_t n_vectors) {
+    return ix ? (size_t)n_vectors * ix->cfg.L : 0;
+}
+
+dessert_status_t dessert_hash(const dessert_index_t* ix, const void* vectors_dev, uint64_t n, uint8_t* codes_dev) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (n == 0) return DESSERT_OK;
+    if (!vectors_dev || !codes_dev) return fail(DESSERT_EINVAL, "vectors_dev / codes_dev is NULL");
+    if (n > (1ull << 40)) return fail(DESSERT_EINVAL, "n too large");
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    return run_hash(ix, vectors_dev, n, codes_dev);
+}
+
+dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_dev, uint64_t n_vectors,
+                                     const uint32_t* lengths_host, uint64_t n_docs, uint8_t* codes_dev,
+                                     uint64_t* offsets_dev) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!offsets_dev) return fail(DESSERT_EINVAL, "offsets_dev is NULL");
+    if (n_docs && !lengths_host) return fail(DESSERT_EINVAL, "lengths_host is NULL");
+    if (n_vectors && (!vectors_dev || !codes_dev)) return fail(DESSERT_EINVAL, "vectors_dev / codes_dev is NULL");
+    if (n_docs > 0xFFFFFFFEull) return fail(DESSERT_EINVAL, "document ids are 32-bit: n_docs too large");
+    uint64_t sum = 0;
+    for (uint64_t i = 0; i < n_docs; ++i) sum += lengths_host[i];
+    if (sum != n_vectors)
+        return fail(DESSERT_EINVAL, "sum of lengths_host (%llu) != n_vectors (%llu)", (unsigned long long)sum,
+                    (unsigned long long)n_vectors);
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    ix->built = false;
+    dessert_index::TimingSlot& ts = ix->begin_timed();
+    if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
+    // The code layout does not depend on document boundaries, so hashing starts first and the
+    // host scans the lengths while the GPU works.
+    dessert_status_t st = run_hash(ix, vectors_dev, n_vectors, codes_dev);
+    if (st != DESSERT_OK) return st;
+    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
+    // the staging buffer may still feed the previous build's upload (enqueued before this hash launch)
+    if (ix->upload_pending) {
+        HIP_TRY(hipEventSynchronize(ix->upload_done));
+        ix->upload_pending = false;
+    }
+    if (ix->h_offsets_cap < n_docs + 1) {
+        if (ix->h_offsets) (void)hipHostFree(ix->h_offsets);
+        ix->h_offsets = nullptr;
+        ix->h_offsets_cap = 0;
+        hipError_t e = hipHostMalloc((void**)&ix->h_offsets, (n_docs + 1) * 8, hipHostMallocDefault);
+        if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipHostMalloc(offsets): %s", hipGetErrorString(e));
+        ix->h_offsets_cap = n_docs + 1;
+    }
+    uint64_t run = 0;
+    for (uint64_t i = 0; i < n_docs; ++i) {
+        ix->h_offsets[i] = run;
+        run += lengths_host[i];
+    }
+    ix->h_offsets[n_docs] = run;
+    HIP_TRY(hipMemcpyAsync(offsets_dev, ix->h_offsets, (n_docs + 1) * 8, hipMemcpyHostToDevice, ix->stream));
+    HIP_TRY(hipEventRecord(ix->upload_done, ix->stream));
+    ix->upload_pending = true;
+    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    ix->codes = codes_dev;
+    ix->offsets = offsets_dev;
+    ix->n_docs = n_docs;
+    ix->n_vectors = n_vectors;
+    ix->built = true;
+    return DESSERT_OK;
+}
+
+size_t dessert_search_workspace_bytes(const dessert_index_t* ix, uint32_t n_queries, uint64_t total_q_vectors,
+                                      uint64_t total_scored, uint32_t k) {
+    if (!ix) return 0;
+    // the slice count depends on the longest list; total_scored bounds it from above
+    Workspace w = carve(ix, n_queries, total_q_vectors, total_scored, total_scored, k, true);
+    return w.total;
+}
+
+dessert_status_t dessert_search(const dessert_index_t* ix, const void* q_vectors_dev, const uint32_t* q_lengths_host,
+                                uint32_t n_queries, const uint32_t* cand_ids_dev, const uint64_t* cand_offsets_host,
+                                uint32_t k, void* workspace_dev, size_t workspace_bytes, uint32_t* out_ids_dev,
+                                int32_t* out_scores_dev) {
+    if (k == 0 || k > 4096) return fail(DESSERT_EINVAL, "k must be in 1..4096, got %u", k);
+    if (n_queries && (!out_ids_dev || !out_scores_dev)) return fail(DESSERT_EINVAL, "output pointer is NULL");
+    return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
+                       cand_offsets_host, k, workspace_dev, workspace_bytes, nullptr, out_ids_dev, out_scores_dev);
+}
+
+dessert_status_t dessert_scores(const dessert_index_t* ix, const void* q_vectors_dev, const uint32_t* q_lengths_host,
+                                uint32_t n_queries, const uint32_t* cand_ids_dev, const uint64_t* cand_offsets_host,
+                                void* workspace_dev, size_t workspace_bytes, int32_t* out_scores_dev) {
+    if (n_queries && !out_scores_dev) return fail(DESSERT_EINVAL, "out_scores_dev is NULL");
+    return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
+                       cand_offsets_host, 0, workspace_dev, workspace_bytes, out_scores_dev, nullptr, nullptr);
+}
+
+dessert_status_t dessert_enable_timing(dessert_index_t* ix, int enable) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    DeviceGuard guard(ix->cfg.device);
+    if (enable && !ix->slots[0].ev[0])
+        for (auto& slot : ix->slots)
+            for (auto& ev : slot.ev) HIP_TRY(hipEventCreate(&ev));
+    ix->timing = enable != 0;
+    ix->timed_calls = 0;
+    for (auto& slot : ix->slots) slot.any = false;
+    return DESSERT_OK;
+}
+
+dessert_status_t dessert_get_timing(dessert_index_t* ix, uint32_t calls_back, float ms[4]) {
+    if (!ix || !ms) return fail(DESSERT_EINVAL, "NULL argument");
+    ms[0] = ms[1] = ms[2] = ms[3] = 0.f;
+    if (calls_back >= dessert_index::kTimingSlots || calls_back >= ix->timed_calls)
+        return fail(DESSERT_ESTATE, "no timed call recorded %u calls back", calls_back);
+    const dessert_index::TimingSlot& ts = ix->slots[(ix->timed_calls - 1 - calls_back) % dessert_index::kTimingSlots];
+    if (!ts.any) return fail(DESSERT_ESTATE, "no timed call recorded %u calls back", calls_back);
+    DeviceGuard guard(ix->cfg.device);
+    HIP_TRY(hipEventSynchronize(ts.ev[4]));
+    if (ts.hash) HIP_TRY(hipEventElapsedTime(&ms[0], ts.ev[0], ts.ev[1]));
+    if (ts.score) HIP_TRY(hipEventElapsedTime(&ms[1], ts.ev[1], ts.ev[2]));
+    if (ts.topk) HIP_TRY(hipEventElapsedTime(&ms[2], ts.ev[2], ts.ev[3]));
+    HIP_TRY(hipEventElapsedTime(&ms[3], ts.ev[0], ts.ev[4]));
+    return DESSERT_OK;
+}
+
+}  // extern "C"

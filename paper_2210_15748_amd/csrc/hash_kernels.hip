@@ -1,0 +1,277 @@
+// SRP hashing kernels for gfx950.
+//
+// A vector's code for table t is C sign bits, bit c = [ r_{t*C+c} . x >= 0 ]
+// (Sec. 3: signed random projections; Sec. 5: C hashes concatenated per
+// table; Alg. 1 "h = f_t(x_j)", Alg. 2 "h_{t,q} = f_t(q)").  Codes are written
+// vector-major, one byte per table: codes[v*L + t].
+#include "kernels.hpp"
+
+#include <type_traits>
+
+namespace dessert {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------
+// Seed-derived Rademacher matrix: entry (row, col) = +1 iff the top bit of
+// mix64(seed + GOLDEN*(row*d+col+1)) is set (SplitMix64 output function).
+__device__ inline uint64_t splitmix_out(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ void rademacher_kernel(uint64_t seed, uint64_t total, int8_t* R) {
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    uint64_t z = splitmix_out(seed + 0x9E3779B97F4A7C15ull * (i + 1));
+    R[i] = (z >> 63) ? 1 : -1;
+}
+
+hipError_t launch_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t* R, hipStream_t stream) {
+    uint64_t total = (uint64_t)P * d;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(rademacher_kernel, dim3(blocks), dim3(256), 0, stream, seed, total, R);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Generic kernel: one thread per (vector, table).  int8 x int8 accumulates in
+// int32 (exact), everything else in fp32 with fused multiply-add in index
+// order.
+template <typename XT, typename RT, typename AccT>
+__global__ __launch_bounds__(256) void hash_scalar_kernel(const XT* __restrict__ X, uint64_t n, uint32_t d,
+                                                          const RT* __restrict__ R, uint32_t L, uint32_t C,
+                                                          uint8_t* __restrict__ codes) {
+    uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n * L) return;
+    uint64_t v = idx / L;
+    uint32_t t = (uint32_t)(idx - v * L);
+    const XT* x = X + v * d;
+    uint32_t code = 0;
+    for (uint32_t c = 0; c < C; ++c) {
+        const RT* r = R + (size_t)(t * C + c) * d;
+        AccT acc = 0;
+        for (uint32_t i = 0; i < d; ++i) {
+            if constexpr (std::is_same<AccT, float>::value)
+                acc = __builtin_fmaf((float)r[i], (float)x[i], acc);
+            else
+                acc += (AccT)r[i] * (AccT)x[i];
+        }
+        code |= (acc >= (AccT)0 ? 1u : 0u) << c;
+    }
+    codes[idx] = (uint8_t)code;
+}
+
+hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
+                              uint32_t L, uint32_t C, uint8_t* codes, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    uint64_t total = n * L;
+    uint64_t blocks64 = (total + 255) / 256;
+    if (blocks64 > 0x7fffffffull) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks64), block(256);
+    if (dtype == 0 && proj_kind == 0)
+        hipLaunchKernelGGL((hash_scalar_kernel<int8_t, int8_t, int32_t>), grid, block, 0, stream, (const int8_t*)X, n, d,
+                           (const int8_t*)R, L, C, codes);
+    else if (dtype == 0 && proj_kind == 1)
+        hipLaunchKernelGGL((hash_scalar_kernel<int8_t, float, float>), grid, block, 0, stream, (const int8_t*)X, n, d,
+                           (const float*)R, L, C, codes);
+    else if (dtype == 1 && proj_kind == 0)
+        hipLaunchKernelGGL((hash_scalar_kernel<_Float16, int8_t, float>), grid, block, 0, stream, (const _Float16*)X, n,
+                           d, (const int8_t*)R, L, C, codes);
+    else
+        hipLaunchKernelGGL((hash_scalar_kernel<_Float16, float, float>), grid, block, 0, stream, (const _Float16*)X, n,
+                           d, (const float*)R, L, C, codes);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// int8 MFMA kernel.  Computes P^T = R * X^T with v_mfma_i32_32x32x32_i8: the M
+// dimension runs over projection rows, the N dimension over vectors, so a
+// lane's 16 accumulators belong to ONE vector and the sign bits are packed in
+// registers without any cross-lane traffic.
+//
+// Accumulator layout of the 32x32 tile: lane l, register r holds
+//   row i = 8*(r/4) + 4*(l/32) + (r%4),   column j = l%32.
+// The rows of R are re-ordered (launch_repack_proj_i8) so that within M-tile mt
+// register r of lane-half g = l/32 is  table t = g*(L/2) + 2*mt + r/8,  bit r%8.
+// Bits c >= C are zero rows and are masked off.  A lane therefore owns L/2
+// consecutive code bytes of its vector: lanes 0..31 bytes [0, L/2), lanes
+// 32..63 bytes [L/2, L), and the wave's stores cover whole 32*L-byte runs.
+//
+// Operand layout: lane l supplies row (l%32) of its operand and the 16
+// consecutive k-indices 32*ks + 16*(l/32) .. +15; A and B use the same rule,
+// so whatever order the instruction walks k in, matching elements meet.
+//
+// The re-ordered matrix ([LT][KS][64 lanes][16 B], LT = L/4 M-tiles, KS = d/32
+// k-steps) is staged in LDS once per workgroup; each wave then loops over
+// tiles of 32*NT vectors, reading every A fragment once per NT MFMAs.
+template <int KS, int LT, int NT>
+__global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restrict__ X, uint64_t n,
+                                                           const v4i* __restrict__ Rp, uint32_t cmask,
+                                                           uint8_t* __restrict__ codes) {
+    constexpr int D = KS * 32;
+    constexpr int L = LT * 4;
+    constexpr int OW = LT / 2;  // output dwords per lane (L/2 bytes)
+    extern __shared__ v4i sR[];
+    for (int i = threadIdx.x; i < LT * KS * 64; i += 256) sR[i] = Rp[i];
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31;
+    const int g = lane >> 5;
+    const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
+
+    for (uint64_t tile = (uint64_t)blockIdx.x * 4 + wave; tile < n_tiles; tile += (uint64_t)gridDim.x * 4) {
+        const uint64_t v0 = tile * (32 * NT);
+        v4i b[NT][KS];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            uint64_t v = v0 + nt * 32 + col;
+            if (v >= n) v = n - 1;
+            const v4i* src = (const v4i*)(X + v * D + g * 16);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) b[nt][ks] = src[ks * 2];
+        }
+        uint32_t outw[NT][OW];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int w = 0; w < OW; ++w) outw[nt][w] = 0;
+
+        // One iteration = two M-tiles = one output dword per lane.  The loop is kept rolled so
+        // that only one pair of tiles' accumulators is live; finished dwords shift through outw.
+#pragma unroll 1
+        for (int mp = 0; mp < OW; ++mp) {
+            uint32_t word[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) word[nt] = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int mt = mp * 2 + h;
+                v16i acc[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[nt][r] = 0;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    v4i a = sR[(mt * KS + ks) * 64 + lane];
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[nt][ks], acc[nt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        // shift in the sign bits, most significant code bit first: neg = sum_c [p_c < 0] << c
+                        uint32_t neg = 0;
+#pragma unroll
+                        for (int c = 7; c >= 0; --c)
+                            neg = __builtin_amdgcn_alignbit(neg, (uint32_t)acc[nt][8 * s + c], 31);
+                        uint32_t code = ~neg & cmask;  // bit = [p >= 0]
+                        word[nt] |= code << (8 * (2 * h + s));
+                    }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+                for (int w = 0; w + 1 < OW; ++w) outw[nt][w] = outw[nt][w + 1];
+                outw[nt][OW - 1] = word[nt];
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            uint64_t v = v0 + nt * 32 + col;
+            if (v < n) {
+                uint32_t* dst = (uint32_t*)(codes + v * L + g * (L / 2));
+                if constexpr (OW % 4 == 0) {
+#pragma unroll
+                    for (int w = 0; w < OW; w += 4) {
+                        v4i o = {(int)outw[nt][w], (int)outw[nt][w + 1], (int)outw[nt][w + 2], (int)outw[nt][w + 3]};
+                        *(v4i*)(dst + w) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int w = 0; w < OW; ++w) dst[w] = outw[nt][w];
+                }
+            }
+        }
+    }
+}
+
+__global__ void repack_proj_i8_kernel(const int8_t* __restrict__ R, uint32_t d, uint32_t L, uint32_t C,
+                                      int8_t* __restrict__ Rp, uint32_t total) {
+    uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t KS = d / 32;
+    uint32_t e = idx & 15;          // byte within the lane's 16
+    uint32_t l = (idx >> 4) & 63;   // lane
+    uint32_t ks = (idx >> 10) % KS;
+    uint32_t mt = (idx >> 10) / KS;
+    uint32_t i = l & 31;            // row of the M-tile
+    uint32_t kk = ks * 32 + 16 * (l >> 5) + e;
+    uint32_t g = (i >> 2) & 1;
+    uint32_t s = i >> 4;
+    uint32_t c = 4 * ((i >> 3) & 1) + (i & 3);
+    uint32_t t = g * (L / 2) + 2 * mt + s;
+    Rp[idx] = (c < C) ? R[(size_t)(t * C + c) * d + kk] : (int8_t)0;
+}
+
+static bool mfma_shape(uint32_t d, uint32_t L) {
+    return (d == 64 || d == 128 || d == 256) && (L == 16 || L == 32 || L == 64);
+}
+
+size_t mfma_proj_bytes(uint32_t d, uint32_t L) {
+    if (!mfma_shape(d, L)) return 0;
+    return (size_t)(L / 4) * (d / 32) * 64 * 16;
+}
+
+bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C) {
+    return mfma_shape(d, L) && C >= 1 && C <= 8 && mfma_proj_bytes(d, L) <= 64 * 1024;
+}
+
+hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
+    uint32_t total = (uint32_t)mfma_proj_bytes(d, L);
+    if (!total) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(repack_proj_i8_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, R, d, L, C, (int8_t*)Rp,
+                       total);
+    return hipGetLastError();
+}
+
+template <int KS, int LT>
+static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
+                                hipStream_t stream) {
+    constexpr int NT = 2;
+    const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
+    uint64_t blocks = (n_tiles + 3) / 4;
+    if (blocks > 1024) blocks = 1024;  // persistent waves: 256 CUs x 4 workgroups
+    size_t lds = (size_t)LT * KS * 64 * 16;
+    auto kern = hash_mfma_i8_kernel<KS, LT, NT>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
+                       codes);
+    return hipGetLastError();
+}
+
+hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
+                               uint8_t* codes, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
+#define DESSERT_MFMA_CASE(KS_, LT_) \
+    if (d == KS_ * 32 && L == LT_ * 4) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, stream);
+    DESSERT_MFMA_CASE(2, 4)
+    DESSERT_MFMA_CASE(2, 8)
+    DESSERT_MFMA_CASE(2, 16)
+    DESSERT_MFMA_CASE(4, 4)
+    DESSERT_MFMA_CASE(4, 8)
+    DESSERT_MFMA_CASE(4, 16)
+    DESSERT_MFMA_CASE(8, 4)
+    DESSERT_MFMA_CASE(8, 8)
+#undef DESSERT_MFMA_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dessert

@@ -1,0 +1,60 @@
+// Internal launch interface between the C ABI (api.hip) and the gfx950 kernels.
+// Nothing here is exported; every function enqueues work on `stream` and
+// returns the launch status without synchronising.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dessert {
+
+// ---- hashing (Sec. 3 SRP family, Sec. 5 concatenation trick) ----------------
+// Fill R [P][d] with the seed-derived Rademacher matrix.
+hipError_t launch_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t* R, hipStream_t stream);
+
+// Bytes of the MFMA-ordered copy of an int8 projection matrix, 0 if (d, L) has no MFMA kernel.
+size_t mfma_proj_bytes(uint32_t d, uint32_t L);
+hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream);
+bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C);
+hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
+                               uint8_t* codes, hipStream_t stream);
+
+// One thread per (vector, table); any d, L, C.  dtype/proj_kind as in dessert.h.
+hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
+                              uint32_t L, uint32_t C, uint8_t* codes, hipStream_t stream);
+
+// ---- scoring (Alg. 2: collision counts, sigma = max, A = sum) ---------------
+struct ScoreArgs {
+    const uint8_t* codes;       // [V][L]
+    const uint64_t* offsets;    // [n_docs+1]
+    uint64_t n_docs;
+    uint32_t L, C;
+    const uint8_t* qcodes;      // [total_q][L]
+    const uint32_t* q_off;      // dev [B+1]
+    uint32_t n_queries;
+    uint32_t max_q_len;
+    const uint32_t* cand_ids;   // dev or nullptr
+    const uint64_t* cand_off;   // dev [B+1] (candidate mode)
+    uint64_t max_scored;        // largest number of documents scored by one query set
+    int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
+};
+hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
+bool score_masklut_supported(uint32_t L, uint32_t C);
+hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
+
+// ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
+struct TopkArgs {
+    const int32_t* scores;      // as written by the scoring kernels
+    const uint32_t* cand_ids;   // dev or nullptr
+    const uint64_t* cand_off;   // dev [B+1] or nullptr
+    uint64_t n_docs;
+    uint32_t n_queries;
+    uint64_t max_scored;
+    uint32_t k;
+    uint64_t* partial;          // workspace for the two-level path: [B][slices][k] keys
+    uint32_t* out_ids;          // [B][k]
+    int32_t* out_scores;        // [B][k]
+};
+uint32_t topk_slices(uint64_t max_scored);
+hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
+
+}  // namespace dessert

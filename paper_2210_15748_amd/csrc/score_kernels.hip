@@ -1,0 +1,292 @@
+// Scoring kernels for gfx950: Alg. 2's loop over documents, query vectors and
+// tables with sigma = max and A = sum,
+//     score(Q,S) = sum_{q in Q} max_{x in S} #{ t : code_t(q) == code_t(x) }.
+// Scores are raw integer counts (no division by L, no remap of Eq. 1).
+#include "kernels.hpp"
+
+namespace dessert {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Where query set b's documents and outputs live.
+struct Span {
+    uint64_t base;   // first output slot (and first candidate entry)
+    uint64_t count;  // documents scored by this query set
+};
+
+__device__ inline Span query_span(const ScoreArgs& a, uint32_t b) {
+    Span s;
+    if (a.cand_ids) {
+        s.base = a.cand_off[b];
+        s.count = a.cand_off[b + 1] - s.base;
+    } else {
+        s.base = (uint64_t)b * a.n_docs;
+        s.count = a.n_docs;
+    }
+    return s;
+}
+
+// ---------------------------------------------------------------------------
+// Byte-compare kernel (plain form, any L multiple of 4, any C <= 8).
+// One wave per scored document; lanes stride over the document's vectors.  For
+// each query vector the lane counts equal bytes four at a time: z = q ^ x has a
+// zero byte exactly where the codes agree, and
+//     nz = (((z & 0x7f7f7f7f) + 0x7f7f7f7f) | z) & 0x80808080
+// has bit 7 of a byte set exactly where z's byte is non-zero.
+__global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
+    extern __shared__ uint32_t sq[];  // query set's codes, [mq][L/4]
+    const uint32_t b = blockIdx.y;
+    const Span sp = query_span(a, b);
+    const uint32_t q_lo = a.q_off[b], mq = a.q_off[b + 1] - q_lo;
+    const uint32_t LW = a.L / 4;
+    const uint32_t* qsrc = (const uint32_t*)(a.qcodes + (size_t)q_lo * a.L);
+    for (uint32_t i = threadIdx.x; i < mq * LW; i += blockDim.x) sq[i] = qsrc[i];
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint64_t pos = (uint64_t)blockIdx.x * 4 + wave; pos < sp.count; pos += (uint64_t)gridDim.x * 4) {
+        const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+        const uint64_t lo = a.offsets[id], hi = a.offsets[id + 1];
+        int32_t score = 0;
+        for (uint32_t q = 0; q < mq; ++q) {
+            int32_t best = 0;
+            for (uint64_t j = lo + lane; j < hi; j += 64) {
+                const uint32_t* x = (const uint32_t*)(a.codes + j * a.L);
+                int32_t cnt = 0;
+                for (uint32_t w = 0; w < LW; ++w) {
+                    uint32_t z = x[w] ^ sq[q * LW + w];
+                    uint32_t nz = (((z & 0x7f7f7f7fu) + 0x7f7f7f7fu) | z) & 0x80808080u;
+                    cnt += 4 - __builtin_popcount(nz);
+                }
+                best = cnt > best ? cnt : best;
+            }
+            for (int off = 32; off >= 1; off >>= 1) {
+                int32_t o = __shfl_xor(best, off, 64);
+                best = o > best ? o : best;
+            }
+            score += best;
+        }
+        if (lane == 0) a.scores[sp.base + pos] = score;
+    }
+}
+
+hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
+    if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
+    size_t lds = (size_t)a.max_q_len * a.L;
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    uint64_t bx = (a.max_scored + 3) / 4;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(score_bytecmp_kernel, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Mask-table kernel: bit-parallel over the query vectors.
+//
+// For a chunk of up to 32 query vectors the workgroup builds, in LDS,
+//     M[t][h] = { q : code_t(q) == h }   as a 32-bit mask,
+// so one LDS read M[t][code_t(x)] answers "which q collide with x in table t"
+// for all 32 q at once.  A lane owns one document vector x at a time: it reads
+// the L masks of x, adds them with a carry-save adder tree into a bit-sliced
+// counter (plane p holds bit p of cnt(q,x) for the 32 q), and folds that into
+// a bit-sliced running maximum.  Sixteen lanes share a document; at its end
+// their maxima are merged with DPP row rotations and the score is
+//     sum_q max_x cnt(q,x) = sum_p 2^p * popcount(plane_p).
+// Everything is integer and exact.  Query sets longer than 32 vectors are
+// processed in chunks of 32 whose partial sums add (the score is a sum over q).
+
+// three-input boolean functions through v_bitop3_b32; the immediate is the
+// function's truth table evaluated on a=0xF0, b=0xCC, c=0xAA
+#define DESSERT_BITOP3(a, b, c, tt) __builtin_amdgcn_bitop3_b32((a), (b), (c), (tt))
+__device__ inline uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) { return DESSERT_BITOP3(a, b, c, 0x96); }
+__device__ inline uint32_t maj3(uint32_t a, uint32_t b, uint32_t c) { return DESSERT_BITOP3(a, b, c, 0xE8); }
+// borrow out of a - b with borrow-in c: maj(~a, b, c)
+__device__ inline uint32_t borrow3(uint32_t a, uint32_t b, uint32_t c) { return DESSERT_BITOP3(a, b, c, 0x8E); }
+// sel ? x : y, bitwise
+__device__ inline uint32_t select3(uint32_t sel, uint32_t x, uint32_t y) { return DESSERT_BITOP3(sel, x, y, 0xCA); }
+
+// Sum N one-bit-per-position inputs into bit planes: planes[p] = bit p of the
+// per-position count.  Inputs of one weight are consumed three at a time by
+// full adders (sum stays at the weight and re-enters the queue, carry moves to
+// the next weight); an even count ends with one half adder.
+template <int N>
+__device__ inline void csa_planes(const uint32_t* in, uint32_t* planes) {
+    if constexpr (N == 1) {
+        planes[0] = in[0];
+    } else {
+        constexpr int F = (N - 1) / 2;  // full adders at this weight
+        uint32_t w[N + F];
+        uint32_t next[N / 2];
+#pragma unroll
+        for (int i = 0; i < N; ++i) w[i] = in[i];
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+            uint32_t x = w[3 * f], y = w[3 * f + 1], z = w[3 * f + 2];
+            w[N + f] = xor3(x, y, z);
+            next[f] = maj3(x, y, z);
+        }
+        if constexpr (N % 2 == 0) {
+            uint32_t x = w[N + F - 2], y = w[N + F - 1];
+            planes[0] = x ^ y;
+            next[N / 2 - 1] = x & y;
+        } else {
+            planes[0] = w[N + F - 1];
+        }
+        csa_planes<N / 2>(next, planes + 1);
+    }
+}
+
+template <int P>
+__device__ inline void planes_max(uint32_t* mx, const uint32_t* c) {
+    // lt = (mx < c) per bit position, from the borrow chain of mx - c
+    uint32_t lt = 0;
+#pragma unroll
+    for (int p = 0; p < P; ++p) lt = borrow3(mx[p], c[p], lt);
+#pragma unroll
+    for (int p = 0; p < P; ++p) mx[p] = select3(lt, c[p], mx[p]);
+}
+
+template <int CTRL>
+__device__ inline uint32_t dpp_row(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2); }
+
+template <int LW, int CB>
+__global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block) {
+    constexpr int L = LW * 4;
+    constexpr int STRIDE = 1 << CB;
+    constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
+    extern __shared__ uint32_t lut[];     // [L][STRIDE]
+
+    const uint32_t b = blockIdx.y;
+    const Span sp = query_span(a, b);
+    const uint64_t first = (uint64_t)blockIdx.x * docs_per_block;
+    if (first >= sp.count) return;
+    const uint64_t last = (first + docs_per_block < sp.count) ? first + docs_per_block : sp.count;
+    const uint32_t q_lo = a.q_off[b], q_hi = a.q_off[b + 1];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t sub = lane & 15;                 // lane within the document's group
+    const uint32_t group = wave * 4 + (lane >> 4);  // 16 groups per workgroup
+
+    for (uint32_t qc = q_lo; qc < q_hi; qc += 32) {
+        const uint32_t nq = (q_hi - qc < 32) ? q_hi - qc : 32;
+        if (qc != q_lo) __syncthreads();
+        for (uint32_t i = threadIdx.x; i < L * STRIDE; i += 256) lut[i] = 0;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
+            uint32_t q = i / L, t = i % L;
+            uint32_t h = a.qcodes[(size_t)(qc + q) * L + t];
+            atomicOr(&lut[t * STRIDE + h], 1u << q);
+        }
+        __syncthreads();
+
+        for (uint64_t p0 = first; p0 < last; p0 += 16) {
+            const uint64_t pos = p0 + group;
+            const bool valid = pos < last;
+            uint64_t lo = 0;
+            uint32_t m = 0;
+            if (valid) {
+                const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+                lo = a.offsets[id];
+                m = (uint32_t)(a.offsets[id + 1] - lo);
+            }
+            uint32_t mx[P];
+#pragma unroll
+            for (int p = 0; p < P; ++p) mx[p] = 0;
+
+            for (uint32_t j0 = 0; __any(j0 < m); j0 += 16) {
+                const uint32_t j = j0 + sub;
+                const bool act = j < m;
+                uint32_t dw[LW];
+                if (act) {
+                    const v4i* src = (const v4i*)(a.codes + (lo + j) * L);
+#pragma unroll
+                    for (int w = 0; w < LW; w += 4) {
+                        v4i v = src[w / 4];
+                        dw[w] = v.x; dw[w + 1] = v.y; dw[w + 2] = v.z; dw[w + 3] = v.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int w = 0; w < LW; ++w) dw[w] = 0;
+                }
+                uint32_t msk[L];
+#pragma unroll
+                for (int t = 0; t < L; ++t) {
+                    uint32_t h = (dw[t / 4] >> (8 * (t % 4))) & 0xFFu;
+                    msk[t] = lut[t * STRIDE + h];
+                }
+                uint32_t cnt[P];
+                csa_planes<L>(msk, cnt);
+                if (!act) {
+#pragma unroll
+                    for (int p = 0; p < P; ++p) cnt[p] = 0;
+                }
+                planes_max<P>(mx, cnt);
+            }
+            // merge the 16 lanes of the document: all-reduce by row rotations 8, 4, 2, 1
+            uint32_t o[P];
+#pragma unroll
+            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x128>(mx[p]);
+            planes_max<P>(mx, o);
+#pragma unroll
+            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x124>(mx[p]);
+            planes_max<P>(mx, o);
+#pragma unroll
+            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x122>(mx[p]);
+            planes_max<P>(mx, o);
+#pragma unroll
+            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x121>(mx[p]);
+            planes_max<P>(mx, o);
+            int32_t score = 0;
+#pragma unroll
+            for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[p]);
+            if (valid && sub == 0) {
+                if (qc == q_lo)
+                    a.scores[sp.base + pos] = score;
+                else
+                    a.scores[sp.base + pos] += score;
+            }
+        }
+    }
+}
+
+bool score_masklut_supported(uint32_t L, uint32_t C) {
+    return (L == 16 || L == 32 || L == 64 || L == 128) && C >= 1 && C <= 8;
+}
+
+template <int LW, int CB>
+static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
+    constexpr size_t lds = (size_t)LW * 4 * (1u << CB) * 4;
+    auto kern = score_masklut_kernel<LW, CB>;
+    if (lds > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)lds);
+        if (attr != hipSuccess) return attr;
+    }
+    // documents per workgroup: enough workgroups to fill 256 CUs several times over, at least 64
+    // documents each so the table build is amortised
+    uint32_t dpb = 256;
+    while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * a.n_queries < 4096) dpb /= 2;
+    uint64_t bx = (a.max_scored + dpb - 1) / dpb;
+    if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a, dpb);
+    return hipGetLastError();
+}
+
+hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream) {
+    if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
+    if (!score_masklut_supported(a.L, a.C)) return hipErrorInvalidValue;
+    const uint32_t cb = a.C <= 6 ? 6 : a.C;
+#define DESSERT_LUT_CASE(LW_, CB_) \
+    if (a.L == LW_ * 4 && cb == CB_) return launch_masklut_t<LW_, CB_>(a, stream);
+    DESSERT_LUT_CASE(4, 6) DESSERT_LUT_CASE(4, 7) DESSERT_LUT_CASE(4, 8)
+    DESSERT_LUT_CASE(8, 6) DESSERT_LUT_CASE(8, 7) DESSERT_LUT_CASE(8, 8)
+    DESSERT_LUT_CASE(16, 6) DESSERT_LUT_CASE(16, 7) DESSERT_LUT_CASE(16, 8)
+    DESSERT_LUT_CASE(32, 6) DESSERT_LUT_CASE(32, 7) DESSERT_LUT_CASE(32, 8)
+#undef DESSERT_LUT_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dessert

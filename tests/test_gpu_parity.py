@@ -1,0 +1,292 @@
+"""GPU parity: every call goes through the C ABI (via the thin binding) and is compared
+element by element with the CPU oracle on the same seeded inputs.  Integer paths are bit-exact."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2210_15748_amd as dz
+from oracle import oracle as orc
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case]", msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_codes(w):
+    p = w.preset
+    R = w.proj.cpu().numpy()
+    fn = orc.hash_i8 if p.dtype == "i8" else orc.hash_fp
+    return fn(w.docs.cpu().numpy(), R, p.L, p.C), fn(w.queries.cpu().numpy(), R, p.L, p.C)
+
+
+def make_index(w, hash_algo=dz.HASH_AUTO, score_algo=dz.SCORE_AUTO):
+    p = w.preset
+    ix = dz.create(p.d, p.L, p.C, dtype=dz.I8 if p.dtype == "i8" else dz.F16,
+                   proj_kind=dz.PROJ_RADEMACHER_I8 if p.proj_kind == "rademacher" else dz.PROJ_GAUSSIAN_F32,
+                   proj=w.proj.to(DEV))
+    dz.set_algo(ix, hash_algo, score_algo)
+    codes, offsets = dz.build_index(ix, w.docs.to(DEV), w.lengths)
+    return ix, codes, offsets
+
+
+# ------------------------------------------------------------------ hashing
+@pytest.mark.parametrize("algo", [dz.HASH_SCALAR, dz.HASH_MFMA])
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 63, 64, 65, 127, 129, 1000, 4099])
+def test_hash_i8_bit_exact_ragged_sizes(algo, n):
+    say(f"hash algo={algo} n={n} d=128 L=32 C=7")
+    rng = np.random.default_rng(n)
+    X = rng.integers(-127, 128, (n, 128)).astype(np.int8)
+    X[0] = 0                                   # all projections exactly zero -> every bit 1
+    R = (rng.integers(0, 2, (224, 128)) * 2 - 1).astype(np.int8)
+    ix = dz.create(128, 32, 7, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, algo, dz.SCORE_AUTO)
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    want = orc.hash_i8(X, R, 32, 7)
+    assert np.array_equal(got, want)
+    assert np.all(got[0] == 127)
+
+
+@pytest.mark.parametrize("d,L,Cb", [(128, 16, 6), (64, 16, 1), (256, 32, 8), (128, 64, 5), (64, 64, 8), (256, 16, 4)])
+def test_hash_mfma_shapes(d, L, Cb):
+    say(f"hash mfma d={d} L={L} C={Cb}")
+    rng = np.random.default_rng(d + L + Cb)
+    n = 777
+    # small magnitudes make exact-zero projections frequent: exercises the sign(0) rule
+    X = rng.integers(-2, 3, (n, d)).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_MFMA, dz.SCORE_AUTO)
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    codes, proj = orc.hash_i8(X, R, L, Cb, want_proj=True)
+    assert (proj == 0).mean() > 0.01
+    assert np.array_equal(got, codes)
+
+
+def test_hash_scalar_odd_shapes_and_seed_rule():
+    say("hash scalar d=50 L=12 C=3 seed-derived projection")
+    rng = np.random.default_rng(1)
+    d, L, Cb, n = 50, 12, 3, 301
+    X = rng.integers(-127, 128, (n, d)).astype(np.int8)
+    ix = dz.create(d, L, Cb, seed=987654321)
+    R = dz.get_projection(ix).cpu().numpy()
+    assert np.array_equal(R, orc.rademacher(987654321, L * Cb, d))
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    assert np.array_equal(got, orc.hash_i8(X, R, L, Cb))
+
+
+def test_hash_fp16_gaussian_within_tolerance():
+    say("hash f16 x gaussian f32, d=256 L=64 C=8")
+    w = gen.make(5, n_docs=40, n_queries=1)
+    p = w.preset
+    X = w.docs.numpy()
+    R = w.proj.numpy()
+    ix = dz.create(p.d, p.L, p.C, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=w.proj.to(DEV))
+    got = dz.hash(ix, w.docs.to(DEV)).cpu().numpy()
+    want, proj = orc.hash_fp(X, R, p.L, p.C, want_proj=True)
+    bits_got = np.unpackbits(got[..., None], axis=2, bitorder="little")
+    bits_want = np.unpackbits(want[..., None], axis=2, bitorder="little")
+    diff = bits_got != bits_want
+    assert diff.mean() <= 1e-4
+    norms = np.linalg.norm(X.astype(np.float64), axis=1)
+    margins = np.abs(proj.reshape(X.shape[0], p.L, p.C))
+    assert np.all(margins[diff] < 1e-3 * np.broadcast_to(norms[:, None, None], margins.shape)[diff])
+
+
+# ------------------------------------------------------------------ index build
+def test_build_index_codes_and_offsets_cfg1():
+    say("build_index cfg1")
+    w = gen.make(1)
+    ix, codes, offsets = make_index(w)
+    dc, _ = oracle_codes(w)
+    assert np.array_equal(codes.cpu().numpy(), dc)
+    assert np.array_equal(offsets.cpu().numpy(), w.offsets.numpy())
+
+
+# ------------------------------------------------------------------ scoring
+def check_scores(w, score_algo, tag):
+    p = w.preset
+    say(f"scores {tag} algo={score_algo} N={w.n_docs} B={p.n_queries} |Q|={p.q_len} L={p.L} C={p.C} cand={p.n_cand}")
+    ix, codes, _ = make_index(w, score_algo=score_algo)
+    dc, qc = oracle_codes(w)
+    assert np.array_equal(codes.cpu().numpy(), dc)
+    got = dz.scores(ix, w.queries.to(DEV), w.q_lengths, cand_ids=None if w.cand_ids is None else w.cand_ids.to(DEV))
+    got = got.cpu().numpy().reshape(p.n_queries, -1)
+    off = w.offsets.numpy()
+    qo = np.concatenate([[0], np.cumsum(w.q_lengths.numpy())])
+    for b in range(p.n_queries):
+        cand = None if w.cand_ids is None else w.cand_ids[b].cpu().numpy()
+        want = orc.scores(dc, off, qc[qo[b]:qo[b + 1]], cand)
+        assert np.array_equal(got[b], want), (tag, b)
+    return ix, dc, qc
+
+
+@pytest.mark.parametrize("algo", [dz.SCORE_BYTECMP, dz.SCORE_MASKLUT])
+def test_scores_cfg1_full(algo):
+    check_scores(gen.make(1), algo, "cfg1")
+
+
+@pytest.mark.parametrize("algo", [dz.SCORE_BYTECMP, dz.SCORE_MASKLUT])
+def test_scores_cfg2_reduced(algo):
+    check_scores(gen.make(2, n_docs=3001, n_queries=5), algo, "cfg2-reduced")
+
+
+@pytest.mark.parametrize("algo", [dz.SCORE_BYTECMP, dz.SCORE_MASKLUT])
+def test_scores_cfg3_reduced_candidates(algo):
+    check_scores(gen.make(3, n_docs=20000, n_queries=6, n_cand=777), algo, "cfg3-reduced")
+
+
+@pytest.mark.parametrize("algo", [dz.SCORE_BYTECMP, dz.SCORE_MASKLUT])
+def test_scores_edge_lengths_and_ragged_queries(algo):
+    say(f"scores edge cases algo={algo}")
+    rng = np.random.default_rng(77)
+    d, L, Cb = 128, 32, 7
+    lens = np.array([0, 1, 15, 16, 17, 180, 0, 31, 33, 64, 65, 2, 0], dtype=np.int64)
+    V = int(lens.sum())
+    # few distinct vectors so that collisions (and ties) are common
+    pool = rng.integers(-127, 128, (12, d)).astype(np.int8)
+    X = pool[rng.integers(0, 12, V)]
+    fresh = rng.random(V) < 0.3
+    X[fresh] = rng.integers(-127, 128, (int(fresh.sum()), d)).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    q_lens = np.array([1, 32, 33, 40, 7, 64], dtype=np.int64)
+    Q = pool[rng.integers(0, 12, int(q_lens.sum()))]
+    noise = rng.integers(-20, 21, Q.shape)
+    Q = np.clip(Q.astype(np.int64) + noise, -127, 127).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_AUTO, algo)
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    # exhaustive
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens).cpu().numpy()
+    for b in range(len(q_lens)):
+        assert np.array_equal(got[b], orc.scores(dc, off, qc[qo[b]:qo[b + 1]])), b
+    # ragged candidate lists with duplicates and an empty list
+    cands = [np.array([5, 5, 0, 12, 3]), np.array([], dtype=np.int64), np.arange(13), np.array([9]),
+             rng.integers(0, 13, 300), np.array([6, 0])]
+    co = np.concatenate([[0], np.cumsum([len(c) for c in cands])])
+    flat = torch.from_numpy(np.concatenate(cands).astype(np.int32)).to(DEV)
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens, cand_ids=flat, cand_offsets=co).cpu().numpy()
+    for b, c in enumerate(cands):
+        assert np.array_equal(got[co[b]:co[b + 1]], orc.scores(dc, off, qc[qo[b]:qo[b + 1]], c)), b
+
+
+@pytest.mark.parametrize("L,Cb", [(16, 6), (64, 8), (128, 5), (16, 8)])
+def test_scores_masklut_other_shapes(L, Cb):
+    say(f"scores masklut L={L} C={Cb}")
+    rng = np.random.default_rng(L * 10 + Cb)
+    d = 64
+    lens = rng.integers(1, 40, 300)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (40, d))
+    X = np.clip(pool[rng.integers(0, 40, V)] + rng.integers(-30, 31, (V, d)), -127, 127).astype(np.int8)
+    Q = np.clip(pool[rng.integers(0, 40, 50)] + rng.integers(-30, 31, (50, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_AUTO, dz.SCORE_MASKLUT)
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), [20, 30]).cpu().numpy()
+    assert np.array_equal(got[0], orc.scores(dc, off, qc[:20]))
+    assert np.array_equal(got[1], orc.scores(dc, off, qc[20:]))
+
+
+# ------------------------------------------------------------------ top-k and whole search
+def check_search(w, tag, score_algo=dz.SCORE_AUTO):
+    p = w.preset
+    say(f"search {tag} N={w.n_docs} B={p.n_queries} k={p.k} cand={p.n_cand}")
+    ix, codes, _ = make_index(w, score_algo=score_algo)
+    dc, qc = oracle_codes(w)
+    cand = None if w.cand_ids is None else w.cand_ids.to(DEV)
+    ids, sc = dz.search(ix, w.queries.to(DEV), w.q_lengths, p.k, cand_ids=cand)
+    qo = np.concatenate([[0], np.cumsum(w.q_lengths.numpy())])
+    qs = [qc[qo[b]:qo[b + 1]] for b in range(p.n_queries)]
+    want_ids, want_sc, _ = orc.search(dc, w.offsets.numpy(), qs, p.k,
+                                      None if w.cand_ids is None else w.cand_ids.cpu().numpy())
+    assert np.array_equal(sc.cpu().numpy(), want_sc), tag
+    assert np.array_equal(ids.cpu().numpy(), want_ids), tag
+    return ids.cpu().numpy()
+
+
+def test_search_cfg1_full():
+    w = gen.make(1)
+    ids = check_search(w, "cfg1")
+    assert np.array_equal(ids[:, 0], w.planted[:, 0].numpy())
+
+
+def test_search_cfg2_reduced():
+    check_search(gen.make(2, n_docs=5000, n_queries=4), "cfg2-reduced")
+
+
+def test_search_cfg3_reduced():
+    w = gen.make(3, n_docs=30000, n_queries=5, n_cand=1024)
+    ids = check_search(w, "cfg3-reduced")
+    # each planted document contributed only 4 of the 32 query vectors; most still reach the top-10
+    for b in range(5):
+        assert len(set(w.planted[b].tolist()) & set(ids[b].tolist())) >= 4
+
+
+def test_search_k_larger_than_scored_and_all_ties():
+    say("search: k > n, all-equal scores, duplicate candidates")
+    d, L, Cb = 128, 32, 7
+    rng = np.random.default_rng(5)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    x = rng.integers(-127, 128, (1, d)).astype(np.int8)
+    lens = np.full(50, 3)
+    X = np.repeat(x, 150, axis=0)                        # every document identical: all scores tie
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    Q = np.repeat(x, 4, axis=0)
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), [4], 64)
+    ids, sc = ids.cpu().numpy()[0], sc.cpu().numpy()[0]
+    assert ids[:50].tolist() == list(range(50)) and np.all(sc[:50] == 4 * L)
+    assert np.all(ids[50:] == 0xFFFFFFFF) and np.all(sc[50:] == -1)
+    cand = torch.tensor([7, 3, 7, 49, 3, 0], dtype=torch.int32, device=DEV)
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), [4], 4, cand_ids=cand, cand_offsets=[0, 6])
+    assert ids.cpu().numpy()[0].tolist() == [0, 3, 3, 7]
+
+
+def test_search_two_level_topk_many_short_documents():
+    say("search: 300000 one-to-three-vector documents, sliced top-k")
+    rng = np.random.default_rng(21)
+    d, L, Cb, N = 64, 16, 4, 300_000
+    lens = rng.integers(1, 4, N)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (64, d))
+    X = np.clip(pool[rng.integers(0, 64, V)] + rng.integers(-60, 61, (V, d)), -127, 127).astype(np.int8)
+    Q = np.clip(pool[rng.integers(0, 64, 6)] + rng.integers(-60, 61, (6, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), [2, 4], 100)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    want_ids, want_sc, _ = orc.search(dc, off, [qc[:2], qc[2:]], 100)
+    assert np.array_equal(sc.cpu().numpy(), want_sc)
+    assert np.array_equal(ids.cpu().numpy(), want_ids)
+
+
+def test_determinism_same_inputs_twice():
+    say("determinism cfg3-reduced")
+    w = gen.make(3, n_docs=20000, n_queries=4, n_cand=512)
+    ix, _, _ = make_index(w)
+    a = dz.search(ix, w.queries.to(DEV), w.q_lengths, 10, cand_ids=w.cand_ids.to(DEV))
+    b = dz.search(ix, w.queries.to(DEV), w.q_lengths, 10, cand_ids=w.cand_ids.to(DEV))
+    assert torch.equal(a[0].cpu(), b[0].cpu()) and torch.equal(a[1], b[1])
+
+
+def test_search_before_build_is_a_state_error():
+    ix = dz.create(128, 32, 7, seed=3)
+    q = torch.zeros(4, 128, dtype=torch.int8, device=DEV)
+    with pytest.raises(dz.DessertError) as e:
+        dz.search(ix, q, [4], 3)
+    assert e.value.status == dz.ESTATE
