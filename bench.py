@@ -44,7 +44,9 @@ def main() -> int:
     ap.add_argument("--score-algo", type=int, default=0)
     ap.add_argument("--hash-algo", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-queries", type=int, default=2)
+    ap.add_argument("--cpu-sample-queries", type=int, default=32)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no sharding, no collectives); --gpus must be 1")
@@ -117,6 +119,14 @@ def main() -> int:
     topk_ms = float(np.mean([t["topk_ms"] for t in tim]))
     value = n_scored / (ms_per_step * 1e-3)
     log(f"[bench] search: {ms_per_step:.4f} ms/step  (hash {qhash_ms:.4f}  score {score_ms:.4f}  topk {topk_ms:.4f})")
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- roofline of the dominant kernel (scoring): algorithmic bytes = code bytes of every scored document
     if cand is not None:

@@ -244,8 +244,10 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr;
     sa.max_scored = bt.max_scored; sa.scores = scores;
     int algo = ix->score_algo;
-    if (algo == DESSERT_SCORE_AUTO)
-        algo = score_masklut_supported(ix->cfg.L, ix->cfg.C) ? DESSERT_SCORE_MASKLUT : DESSERT_SCORE_BYTECMP;
+    // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
+    if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
+        algo = (score_masklut_supported(ix->cfg.L, ix->cfg.C) && ix->n_vectors) ? DESSERT_SCORE_MASKLUT
+                                                                                : DESSERT_SCORE_BYTECMP;
     if (algo == DESSERT_SCORE_MASKLUT) {
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
             return fail(DESSERT_EINVAL, "mask-table scoring needs L in {16,32,64,128}");

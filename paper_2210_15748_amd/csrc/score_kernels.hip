@@ -89,8 +89,8 @@ hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
 // for all 32 q at once.  A lane owns one document vector x at a time: it reads
 // the L masks of x, adds them with a carry-save adder tree into a bit-sliced
 // counter (plane p holds bit p of cnt(q,x) for the 32 q), and folds that into
-// a bit-sliced running maximum.  Sixteen lanes share a document; at its end
-// their maxima are merged with DPP row rotations and the score is
+// a bit-sliced running maximum.  Eight lanes share a document; at its end
+// their maxima are merged with DPP lane exchanges and the score is
 //     sum_q max_x cnt(q,x) = sum_p 2^p * popcount(plane_p).
 // Everything is integer and exact.  Query sets longer than 32 vectors are
 // processed in chunks of 32 whose partial sums add (the score is a sum over q).
@@ -147,33 +147,103 @@ __device__ inline void planes_max(uint32_t* mx, const uint32_t* c) {
 }
 
 template <int CTRL>
-__device__ inline uint32_t dpp_row(uint32_t v) {
+__device__ inline uint32_t dpp_mov(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// byte K of dw, times 4 (the LDS byte offset of a 32-bit table entry), in one SDWA shift
+template <int K>
+__device__ inline uint32_t byte_x4(uint32_t dw, uint32_t two) {
+    uint32_t r;
+    if constexpr (K == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0"
+            : "=v"(r) : "v"(two), "v"(dw));
+    else if constexpr (K == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
+            : "=v"(r) : "v"(two), "v"(dw));
+    else if constexpr (K == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2"
+            : "=v"(r) : "v"(two), "v"(dw));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3"
+            : "=v"(r) : "v"(two), "v"(dw));
+    return r;
 }
 
 constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2); }
 
+constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
+constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
+
+// Per-workgroup bookkeeping placed after the mask table in dynamic LDS.
+struct LutBlockMeta {
+    uint64_t lo[LUT_DOCS];      // first code row of each document of the block
+    uint32_t m[LUT_DOCS];       // its length
+    uint16_t order[LUT_DOCS];   // documents ordered longest class first
+    uint32_t bin[LUT_BINS];     // counting sort by length class
+    uint32_t next;              // next unclaimed position in `order`
+};
+
+// G = lanes per document (8): a wave works on 64/G documents at a time, each lane looping over
+// every G-th vector of its document.  Documents of a block are ordered by length class
+// ceil(m/G) (counting sort in LDS) and waves claim runs of 64/G consecutive documents from that
+// order, so the documents sharing a wave need the same number of rounds and few lanes idle.
 template <int LW, int CB>
 __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block) {
     constexpr int L = LW * 4;
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
-    extern __shared__ uint32_t lut[];     // [L][STRIDE]
+    constexpr int G = 8;
+    constexpr int DOCS_PER_WAVE = 64 / G;
+    // static LDS: the table sits at a link-time constant address, so t*STRIDE*4 folds into the
+    // immediate offset of each ds_read and the only per-read address arithmetic is one shift
+    __shared__ uint32_t lut[L * STRIDE];
+    __shared__ LutBlockMeta meta;
 
     const uint32_t b = blockIdx.y;
     const Span sp = query_span(a, b);
     const uint64_t first = (uint64_t)blockIdx.x * docs_per_block;
     if (first >= sp.count) return;
-    const uint64_t last = (first + docs_per_block < sp.count) ? first + docs_per_block : sp.count;
+    const uint32_t ndocs = (uint32_t)((first + docs_per_block < sp.count) ? docs_per_block : sp.count - first);
     const uint32_t q_lo = a.q_off[b], q_hi = a.q_off[b + 1];
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t sub = lane & 15;                 // lane within the document's group
-    const uint32_t group = wave * 4 + (lane >> 4);  // 16 groups per workgroup
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t sub = lane & (G - 1);  // lane within the document's group
+    const uint32_t grp = lane / G;        // group within the wave
 
+    // ---- where each document lives, and the length-class ordering
+    for (uint32_t i = threadIdx.x; i < LUT_BINS; i += 256) meta.bin[i] = 0;
+    __syncthreads();
+    uint32_t my_class = 0;
+    if (threadIdx.x < ndocs) {
+        const uint64_t pos = first + threadIdx.x;
+        const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+        const uint64_t lo = a.offsets[id];
+        const uint32_t m = (uint32_t)(a.offsets[id + 1] - lo);
+        meta.lo[threadIdx.x] = lo;
+        meta.m[threadIdx.x] = m;
+        uint32_t rounds = (m + G - 1) / G;
+        my_class = rounds < LUT_BINS ? LUT_BINS - 1 - rounds : 0;  // class 0 = longest
+        atomicAdd(&meta.bin[my_class], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {  // exclusive scan of the 64 class counts by one wave
+        uint32_t c = meta.bin[lane], incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t o = __shfl_up(incl, off, 64);
+            if ((int)lane >= off) incl += o;
+        }
+        meta.bin[lane] = incl - c;
+    }
+    __syncthreads();
+    if (threadIdx.x < ndocs) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
+
+    const uint32_t two = 2;
     for (uint32_t qc = q_lo; qc < q_hi; qc += 32) {
         const uint32_t nq = (q_hi - qc < 32) ? q_hi - qc : 32;
-        if (qc != q_lo) __syncthreads();
+        __syncthreads();  // previous chunk's readers are done (and `order` is complete)
         for (uint32_t i = threadIdx.x; i < L * STRIDE; i += 256) lut[i] = 0;
+        if (threadIdx.x == 0) meta.next = 0;
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
             uint32_t q = i / L, t = i % L;
@@ -182,71 +252,81 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
         }
         __syncthreads();
 
-        for (uint64_t p0 = first; p0 < last; p0 += 16) {
-            const uint64_t pos = p0 + group;
-            const bool valid = pos < last;
-            uint64_t lo = 0;
-            uint32_t m = 0;
-            if (valid) {
-                const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
-                lo = a.offsets[id];
-                m = (uint32_t)(a.offsets[id + 1] - lo);
-            }
+        for (;;) {
+            uint32_t claim = 0;
+            if (lane == 0) claim = atomicAdd(&meta.next, (uint32_t)DOCS_PER_WAVE);
+            claim = __builtin_amdgcn_readfirstlane(claim);
+            if (claim >= ndocs) break;
+            const uint32_t slot = claim + grp;
+            const bool valid = slot < ndocs;
+            const uint32_t doc = valid ? meta.order[slot] : 0;
+            const uint32_t m = valid ? meta.m[doc] : 0;
+            // groups with nothing to do read row 0 (the caller guarantees the index holds a vector)
+            const uint64_t lo = m ? meta.lo[doc] : 0;
+            const uint32_t last_j = m ? m - 1 : 0;
+
             uint32_t mx[P];
 #pragma unroll
             for (int p = 0; p < P; ++p) mx[p] = 0;
 
-            for (uint32_t j0 = 0; __any(j0 < m); j0 += 16) {
-                const uint32_t j = j0 + sub;
-                const bool act = j < m;
-                uint32_t dw[LW];
-                if (act) {
-                    const v4i* src = (const v4i*)(a.codes + (lo + j) * L);
+            // lanes past the end re-read the document's last vector (a repeated vector cannot
+            // change the maximum); the next round's codes are requested before this round's
+            // table reads so that HBM latency overlaps the bit-sliced arithmetic
+            auto load_codes = [&](uint32_t j0, uint32_t (&dst)[LW]) {
+                uint32_t j = j0 + sub;
+                j = j < last_j ? j : last_j;
+                const v4i* src = (const v4i*)(a.codes + (lo + j) * L);
 #pragma unroll
-                    for (int w = 0; w < LW; w += 4) {
-                        v4i v = src[w / 4];
-                        dw[w] = v.x; dw[w + 1] = v.y; dw[w + 2] = v.z; dw[w + 3] = v.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int w = 0; w < LW; ++w) dw[w] = 0;
+                for (int w = 0; w < LW; w += 4) {
+                    v4i v = src[w / 4];
+                    dst[w] = v.x; dst[w + 1] = v.y; dst[w + 2] = v.z; dst[w + 3] = v.w;
                 }
+            };
+            uint32_t nxt[LW];
+            load_codes(0, nxt);
+            for (uint32_t j0 = 0; __any(j0 < m); j0 += G) {
+                uint32_t dw[LW];
+#pragma unroll
+                for (int w = 0; w < LW; ++w) dw[w] = nxt[w];
+                load_codes(j0 + G, nxt);
+                const char* lut_bytes = reinterpret_cast<const char*>(lut);
                 uint32_t msk[L];
 #pragma unroll
-                for (int t = 0; t < L; ++t) {
-                    uint32_t h = (dw[t / 4] >> (8 * (t % 4))) & 0xFFu;
-                    msk[t] = lut[t * STRIDE + h];
+                for (int w = 0; w < LW; ++w) {
+                    msk[4 * w + 0] = *(const uint32_t*)(lut_bytes + (4 * w + 0) * STRIDE * 4 + byte_x4<0>(dw[w], two));
+                    msk[4 * w + 1] = *(const uint32_t*)(lut_bytes + (4 * w + 1) * STRIDE * 4 + byte_x4<1>(dw[w], two));
+                    msk[4 * w + 2] = *(const uint32_t*)(lut_bytes + (4 * w + 2) * STRIDE * 4 + byte_x4<2>(dw[w], two));
+                    msk[4 * w + 3] = *(const uint32_t*)(lut_bytes + (4 * w + 3) * STRIDE * 4 + byte_x4<3>(dw[w], two));
                 }
                 uint32_t cnt[P];
                 csa_planes<L>(msk, cnt);
-                if (!act) {
-#pragma unroll
-                    for (int p = 0; p < P; ++p) cnt[p] = 0;
-                }
                 planes_max<P>(mx, cnt);
             }
-            // merge the 16 lanes of the document: all-reduce by row rotations 8, 4, 2, 1
+            if (m == 0) {  // empty document: the maximum over nothing is 0
+#pragma unroll
+                for (int p = 0; p < P; ++p) mx[p] = 0;
+            }
+            // merge the G = 8 lanes of a document: mirror within the half row, then the two
+            // quad exchanges
             uint32_t o[P];
 #pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x128>(mx[p]);
+            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[p]);  // row_half_mirror
             planes_max<P>(mx, o);
 #pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x124>(mx[p]);
+            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[p]);   // quad_perm [1,0,3,2]
             planes_max<P>(mx, o);
 #pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x122>(mx[p]);
-            planes_max<P>(mx, o);
-#pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_row<0x121>(mx[p]);
+            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[p]);   // quad_perm [2,3,0,1]
             planes_max<P>(mx, o);
             int32_t score = 0;
 #pragma unroll
             for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[p]);
             if (valid && sub == 0) {
+                int32_t* dst = a.scores + sp.base + first + doc;
                 if (qc == q_lo)
-                    a.scores[sp.base + pos] = score;
+                    *dst = score;
                 else
-                    a.scores[sp.base + pos] += score;
+                    *dst += score;
             }
         }
     }
@@ -258,20 +338,14 @@ bool score_masklut_supported(uint32_t L, uint32_t C) {
 
 template <int LW, int CB>
 static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
-    constexpr size_t lds = (size_t)LW * 4 * (1u << CB) * 4;
     auto kern = score_masklut_kernel<LW, CB>;
-    if (lds > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                     (int)lds);
-        if (attr != hipSuccess) return attr;
-    }
-    // documents per workgroup: enough workgroups to fill 256 CUs several times over, at least 64
-    // documents each so the table build is amortised
-    uint32_t dpb = 256;
+    // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
+    // workgroups, but at least 64 so the table build stays amortised
+    uint32_t dpb = LUT_DOCS;
     while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * a.n_queries < 4096) dpb /= 2;
     uint64_t bx = (a.max_scored + dpb - 1) / dpb;
     if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a, dpb);
+    hipLaunchKernelGGL(kern, dim3((unsigned)bx, a.n_queries), dim3(256), 0, stream, a, dpb);
     return hipGetLastError();
 }
 
