@@ -1,0 +1,107 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot score every pair of the large presets in reasonable time, so these tests check
+  - hash codes of sampled documents (every vector of each sampled document) bit for bit,
+  - raw scores of sampled (query set, document) pairs and of every document the GPU ranks, bit for bit,
+  - the top-k of every query set re-derived by the oracle's selection from the GPU's full score dump
+    (exact, including the tie rule), and
+  - properties that hold at any size (score range, planted documents rank first / in the top-k).
+Inputs are generated on the device from fixed seeds and handed to the oracle as bytes.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2210_15748_amd as dz
+from oracle import oracle as orc
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case]", msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_codes_of_docs(w, doc_ids):
+    """Oracle hash of every vector of the given documents -> (codes, offsets over the subset)."""
+    off = w.offsets.numpy()
+    rows = np.concatenate([np.arange(off[i], off[i + 1]) for i in doc_ids]) if len(doc_ids) else np.zeros(0, np.int64)
+    sub = w.docs[torch.from_numpy(rows).to(w.docs.device)].cpu().numpy()
+    codes = orc.hash_i8(sub, w.proj.cpu().numpy(), w.preset.L, w.preset.C)
+    sub_off = np.concatenate([[0], np.cumsum(off[np.asarray(doc_ids) + 1] - off[np.asarray(doc_ids)])])
+    return rows, codes, sub_off
+
+
+def test_cfg3_full_candidate_rerank():
+    say("cfg3 full: 1M docs, 256 query sets x 4096 candidates, k=10")
+    w = gen.make(3, device=DEV)
+    p = w.preset
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj)
+    codes, offsets = dz.build_index(ix, w.docs, w.lengths)
+    assert torch.equal(offsets.cpu(), w.offsets)
+    cand = w.cand_ids.to(torch.int32).contiguous()
+    ids, sc = dz.search(ix, w.queries, w.q_lengths, p.k, cand_ids=cand)
+    raw = dz.scores(ix, w.queries, w.q_lengths, cand_ids=cand).cpu().numpy().reshape(p.n_queries, p.n_cand)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    cand_np = w.cand_ids.cpu().numpy()
+    qc = orc.hash_i8(w.queries.cpu().numpy(), w.proj.cpu().numpy(), p.L, p.C)
+
+    # (1) top-k of every query set from the dumped scores, by the oracle's selection
+    for b in range(p.n_queries):
+        want_ids, want_sc = orc.topk(raw[b], p.k, cand_np[b])
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+    assert raw.min() >= 0 and raw.max() <= p.q_len * p.L
+
+    # (2) sampled pairs: 3 whole query sets + 3000 random pairs + every ranked document
+    rng = np.random.default_rng(3)
+    pairs = [(b, c) for b in (0, 101, 255) for c in range(p.n_cand)]
+    pairs += list(zip(rng.integers(0, p.n_queries, 3000).tolist(), rng.integers(0, p.n_cand, 3000).tolist()))
+    pos_of = {}
+    for b in range(p.n_queries):
+        order = np.argsort(cand_np[b], kind="stable")
+        where = np.searchsorted(cand_np[b][order], ids[b].astype(np.int64))
+        pairs += [(b, int(order[x])) for x in where]
+    pb = np.array([x[0] for x in pairs]); pc = np.array([x[1] for x in pairs])
+    docs_needed = np.unique(cand_np[pb, pc])
+    rows, dcodes, sub_off = oracle_codes_of_docs(w, docs_needed)
+    # (3) hash parity on every vector of the sampled documents
+    assert np.array_equal(codes[torch.from_numpy(rows).to(DEV)].cpu().numpy(), dcodes)
+    local = np.searchsorted(docs_needed, cand_np[pb, pc])
+    for b in np.unique(pb):
+        sel = pb == b
+        want = orc.scores(dcodes, sub_off, qc[b * p.q_len:(b + 1) * p.q_len], local[sel])
+        assert np.array_equal(raw[b, pc[sel]], want), b
+    # (4) most planted documents reach the top-10 (each supplied only 4 of the 32 query vectors)
+    hits = [len(set(w.planted[b].tolist()) & set(ids[b].tolist())) for b in range(p.n_queries)]
+    assert np.mean(hits) >= 5.0
+
+
+def test_cfg2_full_exhaustive():
+    say("cfg2 full: 100k docs x 64 query sets exhaustive, k=100")
+    w = gen.make(2, device=DEV)
+    p = w.preset
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj)
+    codes, offsets = dz.build_index(ix, w.docs, w.lengths)
+    ids, sc = dz.search(ix, w.queries, w.q_lengths, p.k)
+    raw = dz.scores(ix, w.queries, w.q_lengths).cpu().numpy()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    R = w.proj.cpu().numpy()
+    dcodes = orc.hash_i8(w.docs.cpu().numpy(), R, p.L, p.C)          # all 7.2M vectors
+    assert np.array_equal(codes.cpu().numpy(), dcodes)
+    qc = orc.hash_i8(w.queries.cpu().numpy(), R, p.L, p.C)
+    off = w.offsets.numpy()
+    for b in range(p.n_queries):
+        want_ids, want_sc = orc.topk(raw[b], p.k)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+        assert ids[b, 0] == int(w.planted[b, 0])
+    rng = np.random.default_rng(2)
+    for b in (0, 17, 63):                                           # three query sets against every document
+        assert np.array_equal(raw[b], orc.scores(dcodes, off, qc[b * p.q_len:(b + 1) * p.q_len])), b
+    for b in range(p.n_queries):                                    # everywhere: ranked docs + a random sample
+        sel = np.unique(np.concatenate([ids[b].astype(np.int64), rng.integers(0, w.n_docs, 500)]))
+        assert np.array_equal(raw[b, sel], orc.scores(dcodes, off, qc[b * p.q_len:(b + 1) * p.q_len], sel)), b
