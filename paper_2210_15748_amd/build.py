@@ -10,6 +10,9 @@ LIB = HERE / "libdessert_hip.so"
 SOURCES = ["api.hip", "hash_kernels.hip", "score_kernels.hip", "topk_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA accumulators in ordinary VGPRs: the sign packing reads them with VALU ops, which
+         # cannot address AGPRs (saves one v_accvgpr_read per accumulator)
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
