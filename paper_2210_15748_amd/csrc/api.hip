@@ -143,6 +143,8 @@ struct Batch {
     std::vector<uint32_t> q_off;
     uint64_t total_q = 0, total_scored = 0, max_scored = 0;
     uint32_t max_q_len = 0;
+    uint32_t q_uniform = 0;      // common query-set length, 0 if they differ
+    uint64_t cand_uniform = 0;   // common candidate-list length, 0 if they differ (or no candidates)
 };
 
 dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, const uint32_t* q_lengths, uint32_t B,
@@ -164,6 +166,9 @@ dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, con
         if (q_lengths[b] > out->max_q_len) out->max_q_len = q_lengths[b];
     }
     out->total_q = out->q_off[B];
+    out->q_uniform = q_lengths[0];
+    for (uint32_t b = 1; b < B; ++b)
+        if (q_lengths[b] != q_lengths[0]) out->q_uniform = 0;
     if (cand_ids) {
         if (!cand_off) return fail(DESSERT_EINVAL, "cand_offsets_host is NULL with candidate ids given");
         if (cand_off[0] != 0) return fail(DESSERT_EINVAL, "cand_offsets_host[0] must be 0");
@@ -173,6 +178,9 @@ dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, con
             if (c > out->max_scored) out->max_scored = c;
         }
         out->total_scored = cand_off[B];
+        out->cand_uniform = cand_off[1];
+        for (uint32_t b = 1; b < B; ++b)
+            if (cand_off[b + 1] - cand_off[b] != cand_off[1]) out->cand_uniform = 0;
     } else {
         out->max_scored = ix->n_docs;
         out->total_scored = (uint64_t)B * ix->n_docs;
@@ -206,8 +214,10 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
 
     dessert_index::TimingSlot& ts = ix->begin_timed();
     if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
-    // the offset arrays go through a pinned slot so that the uploads never block the host
-    {
+    // Offset arrays are uploaded only when the lengths differ (equal lengths travel as kernel
+    // arguments); they go through a pinned slot so that the uploads never block the host.
+    const bool need_q = bt.q_uniform == 0, need_c = cand_ids && bt.cand_uniform == 0;
+    if (need_q || need_c) {
         dessert_index::MetaSlot& ms = ix->meta[ix->meta_next++ % dessert_index::kMetaSlots];
         if (ms.pending) {
             HIP_TRY(hipEventSynchronize(ms.done));
@@ -223,9 +233,11 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
             ms.cap = 2 * (qb + cb);
         }
         if (!ms.done) HIP_TRY(hipEventCreateWithFlags(&ms.done, hipEventDisableTiming));
-        memcpy(ms.host, bt.q_off.data(), ((size_t)B + 1) * 4);
-        HIP_TRY(hipMemcpyAsync(d_q_off, ms.host, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, ix->stream));
-        if (cand_ids) {
+        if (need_q) {
+            memcpy(ms.host, bt.q_off.data(), ((size_t)B + 1) * 4);
+            HIP_TRY(hipMemcpyAsync(d_q_off, ms.host, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, ix->stream));
+        }
+        if (need_c) {
             memcpy(ms.host + qb, cand_off, cb);
             HIP_TRY(hipMemcpyAsync(d_cand_off, ms.host + qb, cb, hipMemcpyHostToDevice, ix->stream));
         }
@@ -240,8 +252,8 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     ScoreArgs sa{};
     sa.codes = ix->codes; sa.offsets = ix->offsets; sa.n_docs = ix->n_docs;
     sa.L = ix->cfg.L; sa.C = ix->cfg.C;
-    sa.qcodes = qcodes; sa.q_off = d_q_off; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
-    sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr;
+    sa.qcodes = qcodes; sa.q_off = d_q_off; sa.q_uniform = bt.q_uniform; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
+    sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr; sa.cand_uniform = cand_ids ? bt.cand_uniform : 0;
     sa.max_scored = bt.max_scored; sa.scores = scores;
     int algo = ix->score_algo;
     // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
@@ -261,8 +273,8 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
 
     if (k) {
         TopkArgs ta{};
-        ta.scores = scores; ta.cand_ids = cand_ids; ta.cand_off = sa.cand_off; ta.n_docs = ix->n_docs;
-        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k;
+        ta.scores = scores; ta.cand_ids = cand_ids; ta.cand_off = sa.cand_off; ta.cand_uniform = sa.cand_uniform; ta.n_docs = ix->n_docs;
+        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = bt.max_q_len * ix->cfg.L;
         ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
         HIP_TRY(launch_topk(ta, ix->stream));
         if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }

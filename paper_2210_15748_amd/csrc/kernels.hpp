@@ -29,14 +29,21 @@ struct ScoreArgs {
     uint64_t n_docs;
     uint32_t L, C;
     const uint8_t* qcodes;      // [total_q][L]
-    const uint32_t* q_off;      // dev [B+1]
+    const uint32_t* q_off;      // dev [B+1]; unused when q_uniform != 0
+    uint32_t q_uniform;         // != 0: every query set has this many vectors (q_off[b] = b * q_uniform)
     uint32_t n_queries;
     uint32_t max_q_len;
     const uint32_t* cand_ids;   // dev or nullptr
-    const uint64_t* cand_off;   // dev [B+1] (candidate mode)
+    const uint64_t* cand_off;   // dev [B+1] (candidate mode); unused when cand_uniform != 0
+    uint64_t cand_uniform;      // != 0: every candidate list has this many ids
     uint64_t max_scored;        // largest number of documents scored by one query set
     int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
 };
+// first query vector / first candidate slot of query set b (b may be n_queries: one past the end)
+__device__ inline uint32_t q_begin(const ScoreArgs& a, uint32_t b) { return a.q_uniform ? b * a.q_uniform : a.q_off[b]; }
+__device__ inline uint64_t cand_begin(const ScoreArgs& a, uint32_t b) {
+    return a.cand_uniform ? (uint64_t)b * a.cand_uniform : a.cand_off[b];
+}
 hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
 bool score_masklut_supported(uint32_t L, uint32_t C);
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
@@ -46,10 +53,12 @@ struct TopkArgs {
     const int32_t* scores;      // as written by the scoring kernels
     const uint32_t* cand_ids;   // dev or nullptr
     const uint64_t* cand_off;   // dev [B+1] or nullptr
+    uint64_t cand_uniform;      // != 0: every candidate list has this many ids (cand_off unused)
     uint64_t n_docs;
     uint32_t n_queries;
     uint64_t max_scored;
     uint32_t k;
+    uint32_t max_score;         // largest possible score (longest query set * L)
     uint64_t* partial;          // workspace for the two-level path: [B][slices][k] keys
     uint32_t* out_ids;          // [B][k]
     int32_t* out_scores;        // [B][k]

@@ -17,8 +17,8 @@ struct Span {
 __device__ inline Span query_span(const ScoreArgs& a, uint32_t b) {
     Span s;
     if (a.cand_ids) {
-        s.base = a.cand_off[b];
-        s.count = a.cand_off[b + 1] - s.base;
+        s.base = cand_begin(a, b);
+        s.count = cand_begin(a, b + 1) - s.base;
     } else {
         s.base = (uint64_t)b * a.n_docs;
         s.count = a.n_docs;
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
     extern __shared__ uint32_t sq[];  // query set's codes, [mq][L/4]
     const uint32_t b = blockIdx.y;
     const Span sp = query_span(a, b);
-    const uint32_t q_lo = a.q_off[b], mq = a.q_off[b + 1] - q_lo;
+    const uint32_t q_lo = q_begin(a, b), mq = q_begin(a, b + 1) - q_lo;
     const uint32_t LW = a.L / 4;
     const uint32_t* qsrc = (const uint32_t*)(a.qcodes + (size_t)q_lo * a.L);
     for (uint32_t i = threadIdx.x; i < mq * LW; i += blockDim.x) sq[i] = qsrc[i];
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     const uint64_t first = (uint64_t)blockIdx.x * docs_per_block;
     if (first >= sp.count) return;
     const uint32_t ndocs = (uint32_t)((first + docs_per_block < sp.count) ? docs_per_block : sp.count - first);
-    const uint32_t q_lo = a.q_off[b], q_hi = a.q_off[b + 1];
+    const uint32_t q_lo = q_begin(a, b), q_hi = q_begin(a, b + 1);
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t sub = lane & (G - 1);  // lane within the document's group
     const uint32_t grp = lane / G;        // group within the wave

@@ -1,0 +1,187 @@
+// Exact block-level top-k selection for gfx950 (device code shared by the stand-alone
+// top-k kernels and by the scoring kernel's fused finish).
+//
+// Alg. 2's last line returns the argmax; here the k best are returned, ordered by score
+// descending and, among equal scores, by ascending document id.  Every scored document
+// becomes one dense integer key
+//     key = (score + 1) << id_bits | (2^id_bits - 1 - id)
+// so "larger key" is exactly "ranks earlier" and key 0 never occurs (it pads).  A workgroup
+// fixes the k-th largest key by most-significant-digit radix selection (digits of up to 11
+// bits, one histogram pass each, the digit chosen by a parallel suffix scan of the
+// histogram), emits the keys above it plus as many copies of it as are still needed, and
+// sorts those k keys in LDS with a bitonic network.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dessert {
+
+constexpr uint32_t TOPK_KMAX = 4096;
+constexpr uint32_t TOPK_DIGIT_BITS = 11;
+constexpr uint32_t TOPK_HIST = 1u << TOPK_DIGIT_BITS;
+
+struct KeyPlan {
+    uint8_t id_bits;     // bits that hold 2^id_bits-1-id
+    uint8_t n_digits;    // radix passes, most significant digit first
+    uint8_t shift[6];
+    uint8_t width[6];
+};
+
+inline uint32_t bits_for(uint64_t max_value) {
+    uint32_t b = 1;
+    while (b < 64 && (max_value >> b)) ++b;
+    return b;
+}
+
+// max_score: largest possible score; max_id: largest document id that can occur
+inline KeyPlan make_key_plan(uint32_t max_score, uint64_t max_id) {
+    KeyPlan p{};
+    p.id_bits = (uint8_t)bits_for(max_id);
+    uint32_t total = p.id_bits + bits_for((uint64_t)max_score + 1);
+    uint32_t n = (total + TOPK_DIGIT_BITS - 1) / TOPK_DIGIT_BITS;
+    p.n_digits = (uint8_t)n;
+    uint32_t hi = total;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t w = (hi + (n - i) - 1) / (n - i);  // spread the bits evenly over the remaining digits
+        p.width[i] = (uint8_t)w;
+        p.shift[i] = (uint8_t)(hi - w);
+        hi -= w;
+    }
+    return p;
+}
+
+__device__ inline uint64_t make_key(int32_t score, uint32_t id, uint32_t id_bits) {
+    const uint64_t idmask = (1ull << id_bits) - 1;
+    return ((uint64_t)(uint32_t)(score + 1) << id_bits) | (idmask - (uint64_t)id);
+}
+
+__device__ inline void write_result(uint64_t key, uint32_t id_bits, uint32_t* id, int32_t* score) {
+    if (key == 0) {
+        *id = 0xFFFFFFFFu;
+        *score = -1;
+    } else {
+        const uint64_t idmask = (1ull << id_bits) - 1;
+        *id = (uint32_t)(idmask - (key & idmask));
+        *score = (int32_t)(key >> id_bits) - 1;
+    }
+}
+
+struct SelectShared {
+    uint32_t hist[TOPK_HIST];
+    uint32_t wave_sum[16];
+    uint64_t prefix;
+    uint32_t need;
+    uint32_t count;
+    uint32_t eq_taken;
+};
+
+// Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
+// T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
+// sorted: kpad = next power of two >= max(k, 2) entries of LDS.
+template <int T, typename Keys>
+__device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
+                             SelectShared& sh, const KeyPlan& plan) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    constexpr int WAVES = T / 64;
+    for (uint32_t i = tid; i < kpad; i += T) sorted[i] = 0;
+    if (tid == 0) {
+        sh.count = 0;
+        sh.prefix = 0;
+        sh.need = k;
+        sh.eq_taken = 0;
+    }
+    __syncthreads();
+    if (n <= k) {
+        for (uint64_t i = tid; i < n; i += T) sorted[i] = keys(i);
+    } else {
+        for (uint32_t d = 0; d < plan.n_digits; ++d) {
+            const uint32_t shift = plan.shift[d], width = plan.width[d];
+            const uint32_t nbins = 1u << width, dmask = nbins - 1;
+            for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = 0;
+            __syncthreads();
+            const uint64_t prefix = sh.prefix;
+            const uint32_t need = sh.need;
+            for (uint64_t i = tid; i < n; i += T) {
+                uint64_t key = keys(i);
+                if ((key >> (shift + width)) == prefix) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & dmask], 1u);
+            }
+            __syncthreads();
+            // digit D with  count(digits > D) < need <= count(digits >= D):
+            // thread t owns bins [t*per, (t+1)*per); suffix sums over threads, then a short scan
+            const uint32_t per = (nbins + T - 1) / T;
+            const uint32_t b0 = tid * per;
+            uint32_t mine = 0;
+            for (uint32_t j = 0; j < per; ++j)
+                if (b0 + j < nbins) mine += sh.hist[b0 + j];
+            uint32_t incl = mine;  // inclusive suffix sum within the wave (lanes above contribute)
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_down(incl, off, 64);
+                if ((int)lane + off < 64) incl += o;
+            }
+            if (lane == 0) sh.wave_sum[wave] = incl;
+            __syncthreads();
+            uint32_t above = incl - mine;  // bins owned by higher threads
+            for (int w2 = (int)wave + 1; w2 < WAVES; ++w2) above += sh.wave_sum[w2];
+            if (above < need && need <= above + mine) {  // exactly one thread
+                for (int j = (int)per - 1; j >= 0; --j) {
+                    if (b0 + j >= nbins) continue;
+                    uint32_t c = sh.hist[b0 + j];
+                    if (above + c >= need) {
+                        sh.need = need - above;
+                        sh.prefix = (prefix << width) | (uint64_t)(b0 + j);
+                        break;
+                    }
+                    above += c;
+                }
+            }
+            __syncthreads();
+        }
+        const uint64_t kth = sh.prefix;   // the k-th largest key
+        const uint32_t need_eq = sh.need;  // copies of it that belong to the result
+        for (uint64_t i = tid; i < n; i += T) {
+            uint64_t key = keys(i);
+            if (key > kth) {
+                sorted[atomicAdd(&sh.count, 1u)] = key;
+            } else if (key == kth) {
+                if (atomicAdd(&sh.eq_taken, 1u) < need_eq) sorted[atomicAdd(&sh.count, 1u)] = key;
+            }
+        }
+    }
+    __syncthreads();
+    // bitonic sort, descending
+    for (uint32_t size = 2; size <= kpad; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t i = tid; i < kpad / 2; i += T) {
+                uint32_t lo = 2 * i - (i & (stride - 1));
+                uint32_t hi = lo + stride;
+                bool desc = ((lo & size) == 0);
+                uint64_t x = sorted[lo], y = sorted[hi];
+                if ((x < y) == desc) {
+                    sorted[lo] = y;
+                    sorted[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+struct ScoreKeys {  // keys computed from a score array (+ optional candidate ids)
+    const int32_t* scores;
+    const uint32_t* ids;  // nullptr: id = first_id + i
+    uint64_t first_id;
+    uint32_t id_bits;
+    __device__ uint64_t operator()(uint64_t i) const {
+        uint32_t id = ids ? ids[i] : (uint32_t)(first_id + i);
+        return make_key(scores[i], id, id_bits);
+    }
+};
+
+struct StoredKeys {
+    const uint64_t* keys;
+    __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
+};
+
+}  // namespace dessert
