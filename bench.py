@@ -150,7 +150,10 @@ def main() -> int:
             ids = w.cand_ids[:nb].cpu().numpy()
             uniq, inv = np.unique(ids.reshape(-1), return_inverse=True)
         else:
-            uniq = np.arange(min(w.n_docs, 8192))
+            # bound the oracle's hashing work (about 2e10 multiply-adds)
+            mean_len = max(1.0, w.n_vectors / max(1, w.n_docs))
+            cap = int(2e10 / (mean_len * p.L * p.C * p.d))
+            uniq = np.arange(min(w.n_docs, 8192, max(64, cap)))
             inv = None
         rows = np.concatenate([np.arange(off_all[i], off_all[i + 1]) for i in uniq])
         sub_docs = w.docs[torch.from_numpy(rows).to(dev)].cpu().numpy()
@@ -164,8 +167,13 @@ def main() -> int:
         hash_s = time.perf_counter() - th
         ts = time.perf_counter()
         total = 0
-        got = dz.scores(ix, w.queries[: nb * p.q_len].contiguous(), ql[:nb],
-                        cand_ids=None if cand is None else cand[:nb].contiguous()).cpu().numpy().reshape(nb, -1)
+        if cand is not None:
+            got = dz.scores(ix, w.queries[: nb * p.q_len].contiguous(), ql[:nb],
+                            cand_ids=cand[:nb].contiguous()).cpu().numpy().reshape(nb, -1)
+        else:   # exhaustive: score the sampled documents as an explicit candidate list
+            sel_ids = torch.from_numpy(np.tile(uniq, nb).astype(np.int32)).to(dev)
+            got = dz.scores(ix, w.queries[: nb * p.q_len].contiguous(), ql[:nb], cand_ids=sel_ids,
+                            cand_offsets=np.arange(nb + 1, dtype=np.uint64) * len(uniq)).cpu().numpy().reshape(nb, -1)
         ok = True
         ts = time.perf_counter()
         for b in range(nb):

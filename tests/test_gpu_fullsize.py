@@ -105,3 +105,55 @@ def test_cfg2_full_exhaustive():
     for b in range(p.n_queries):                                    # everywhere: ranked docs + a random sample
         sel = np.unique(np.concatenate([ids[b].astype(np.int64), rng.integers(0, w.n_docs, 500)]))
         assert np.array_equal(raw[b, sel], orc.scores(dcodes, off, qc[b * p.q_len:(b + 1) * p.q_len], sel)), b
+
+
+def test_cfg5_fp16_gaussian_tolerance_path():
+    """fp16 vectors x fp32 Gaussian projections, L=64, C=8, |Q|=128 (four mask-table chunks per query set).
+
+    Tolerances of this configuration: code-bit mismatch rate <= 1e-4, every mismatch at a projection with
+    |p| < 1e-3*||x||, top-10 overlap with the oracle >= 0.99.  The scoring of GPU codes is itself exact, which
+    is checked by scoring the GPU's own codes with the oracle."""
+    say("cfg5 reduced to 20k docs: fp16 / Gaussian, L=64 C=8, 16 query sets x 128 vectors, exhaustive, k=10")
+    w = gen.make(5, device=DEV, n_docs=20000, n_queries=16)
+    p = w.preset
+    ix = dz.create(p.d, p.L, p.C, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=w.proj)
+    codes, _ = dz.build_index(ix, w.docs, w.lengths)
+    ids, sc = dz.search(ix, w.queries, w.q_lengths, p.k)
+    raw = dz.scores(ix, w.queries, w.q_lengths).cpu().numpy()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    R = w.proj.cpu().numpy()
+    off = w.offsets.numpy()
+
+    # hashing: sampled documents, all their vectors
+    rng = np.random.default_rng(5)
+    sample = np.unique(np.concatenate([rng.integers(0, w.n_docs, 1500), w.planted[:, 0].numpy()]))
+    rows = np.concatenate([np.arange(off[i], off[i + 1]) for i in sample])
+    X = w.docs[torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    want, proj = orc.hash_fp(X, R, p.L, p.C, want_proj=True)
+    got = codes[torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    diff = np.unpackbits(got[..., None], axis=2, bitorder="little") != np.unpackbits(want[..., None], axis=2, bitorder="little")
+    assert diff.mean() <= 1e-4, diff.mean()
+    norms = np.linalg.norm(X.astype(np.float64), axis=1)
+    margins = np.abs(proj.reshape(X.shape[0], p.L, p.C))
+    assert np.all(margins[diff] < 1e-3 * np.broadcast_to(norms[:, None, None], margins.shape)[diff])
+
+    # scoring and top-k are exact given the GPU's own codes
+    gcodes = codes.cpu().numpy()
+    qcodes_gpu = dz.hash(ix, w.queries).cpu().numpy()
+    for b in (0, 7, 15):
+        q = qcodes_gpu[b * p.q_len:(b + 1) * p.q_len]
+        assert np.array_equal(raw[b], orc.scores(gcodes, off, q)), b
+    for b in range(p.n_queries):
+        want_ids, want_sc = orc.topk(raw[b], p.k)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+
+    # end to end against the oracle's own codes: top-10 overlap
+    ocodes = orc.hash_fp(w.docs.cpu().numpy(), R, p.L, p.C)
+    oq = orc.hash_fp(w.queries.cpu().numpy(), R, p.L, p.C)
+    overlap = []
+    for b in range(p.n_queries):
+        s = orc.scores(ocodes, off, oq[b * p.q_len:(b + 1) * p.q_len])
+        o_ids, _ = orc.topk(s, p.k)
+        overlap.append(len(set(o_ids.tolist()) & set(ids[b].tolist())) / p.k)
+        assert ids[b, 0] == int(w.planted[b, 0])
+    assert np.mean(overlap) >= 0.99, overlap
