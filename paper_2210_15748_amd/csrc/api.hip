@@ -96,10 +96,13 @@ namespace {
 
 size_t proj_elem_bytes(uint32_t kind) { return kind == DESSERT_PROJ_RADEMACHER_I8 ? 1 : 4; }
 
-bool use_mfma(const dessert_index* ix) {
-    return ix->proj_mfma && ix->cfg.dtype == DESSERT_I8 && ix->cfg.proj_kind == DESSERT_PROJ_RADEMACHER_I8 &&
-           hash_mfma_supported(ix->cfg.d, ix->cfg.L, ix->cfg.C);
+bool is_i8_mfma(const dessert_config_t& c) {
+    return c.dtype == DESSERT_I8 && c.proj_kind == DESSERT_PROJ_RADEMACHER_I8 && hash_mfma_supported(c.d, c.L, c.C);
 }
+bool is_f16_mfma(const dessert_config_t& c) {
+    return c.dtype == DESSERT_F16 && c.proj_kind == DESSERT_PROJ_GAUSSIAN_F32 && hash_mfma_f16_supported(c.d, c.L, c.C);
+}
+bool use_mfma(const dessert_index* ix) { return ix->proj_mfma && (is_i8_mfma(ix->cfg) || is_f16_mfma(ix->cfg)); }
 
 dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, uint8_t* codes) {
     if (n == 0) return DESSERT_OK;
@@ -107,9 +110,14 @@ dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, ui
     bool aligned = ((uintptr_t)X % 16 == 0) && ((uintptr_t)codes % 16 == 0);
     if (algo == DESSERT_HASH_AUTO) algo = (use_mfma(ix) && aligned) ? DESSERT_HASH_MFMA : DESSERT_HASH_SCALAR;
     if (algo == DESSERT_HASH_MFMA) {
-        if (!use_mfma(ix)) return fail(DESSERT_EINVAL, "MFMA hashing needs int8 vectors, +-1 projections, d in {64,128,256}, L in {16,32,64}");
+        if (!use_mfma(ix))
+            return fail(DESSERT_EINVAL, "MFMA hashing needs int8 vectors with +-1 projections or fp16 vectors with "
+                                        "Gaussian projections, d in {64,128,256}, L in {16,32,64}");
         if (!aligned) return fail(DESSERT_EINVAL, "MFMA hashing needs 16-byte aligned vectors and codes");
-        HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
+        if (ix->cfg.dtype == DESSERT_I8)
+            HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
+        else
+            HIP_TRY(launch_hash_mfma_f16(X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
     } else if (algo == DESSERT_HASH_SCALAR) {
         HIP_TRY(launch_hash_scalar(X, ix->cfg.dtype, n, ix->cfg.d, ix->proj, ix->cfg.proj_kind, ix->cfg.L, ix->cfg.C, codes,
                                    ix->stream));
@@ -325,10 +333,12 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
         e = hipMemcpyAsync(ix->proj, c->proj_dev, pbytes, hipMemcpyDeviceToDevice, ix->stream);
     else
         e = launch_rademacher(c->seed, (uint32_t)P, c->d, (int8_t*)ix->proj, ix->stream);
-    if (e == hipSuccess && c->dtype == DESSERT_I8 && c->proj_kind == DESSERT_PROJ_RADEMACHER_I8 &&
-        hash_mfma_supported(c->d, c->L, c->C)) {
+    if (e == hipSuccess && is_i8_mfma(*c)) {
         e = hipMalloc(&ix->proj_mfma, mfma_proj_bytes(c->d, c->L));
         if (e == hipSuccess) e = launch_repack_proj_i8((const int8_t*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
+    } else if (e == hipSuccess && is_f16_mfma(*c)) {
+        e = hipMalloc(&ix->proj_mfma, mfma_f16_proj_bytes(c->d, c->L));
+        if (e == hipSuccess) e = launch_repack_proj_f16((const float*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->upload_done, hipEventDisableTiming);
     if (e != hipSuccess) {

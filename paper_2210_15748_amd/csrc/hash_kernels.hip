@@ -274,4 +274,187 @@ hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t
     return hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------
+// fp16 vectors x fp32 Gaussian projections on v_mfma_f32_32x32x16_f16.
+//
+// An fp16 copy of R alone would perturb r.x by about 3e-4*|x| and flip more sign bits than the
+// 1e-4 budget allows, so R is split as  R = hi + lo/2048  with hi = fp16(R) and
+// lo = fp16((R - hi) * 2048): both parts are normal fp16 numbers, every product is exact in
+// fp32, and the two parts accumulate in separate fp32 accumulators that are joined as
+// p = accL/2048 + accH.  What is left is fp32 accumulation error (about 1e-6*|x|).
+//
+// Tiling and sign packing follow the int8 kernel (same accumulator layout, same row order of
+// R).  R does not fit LDS here (512 KB at L=64, d=256), so the workgroup stages one M-tile of
+// R (hi and lo, 2*d*64 bytes) in LDS at a time; its four waves multiply it with their own
+// vectors, which stay in registers for all M-tiles.
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int KS, int LT, int NT>  // KS = d/16 k-steps, LT = L/4 M-tiles, NT n-tiles of 32 vectors per wave
+__global__ __launch_bounds__(256) void hash_mfma_f16_kernel(const _Float16* __restrict__ X, uint64_t n,
+                                                            const v8h* __restrict__ Rp, uint32_t cmask,
+                                                            uint8_t* __restrict__ codes) {
+    constexpr int D = KS * 16;
+    constexpr int L = LT * 4;
+    constexpr int OW = LT / 2;
+    constexpr int TILE_FRAGS = 2 * KS * 64;  // 16-byte fragments of one M-tile (hi then lo)
+    __shared__ v8h sA[TILE_FRAGS];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31;
+    const int g = lane >> 5;
+    const uint64_t block_vecs = 4 * 32 * NT;
+    const uint64_t n_blocks = (n + block_vecs - 1) / block_vecs;
+
+    for (uint64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        const uint64_t v0 = blk * block_vecs + (uint64_t)wave * 32 * NT;
+        v8h b[NT][KS];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            uint64_t v = v0 + nt * 32 + col;
+            if (v >= n) v = n - 1;
+            const v8h* src = (const v8h*)(X + v * D + g * 8);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) b[nt][ks] = src[ks * 2];
+        }
+        uint32_t outw[NT][OW];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int w = 0; w < OW; ++w) outw[nt][w] = 0;
+
+#pragma unroll 1
+        for (int mp = 0; mp < OW; ++mp) {
+            uint32_t word[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) word[nt] = 0;
+#pragma unroll 1
+            for (int h = 0; h < 2; ++h) {
+                const int mt = mp * 2 + h;
+                __syncthreads();  // every wave is done with the previous tile of R
+                for (int i = threadIdx.x; i < TILE_FRAGS; i += 256) sA[i] = Rp[(size_t)mt * TILE_FRAGS + i];
+                __syncthreads();
+                v16f accH[NT], accL[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        accH[nt][r] = 0.f;
+                        accL[nt][r] = 0.f;
+                    }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    v8h ah = sA[ks * 64 + lane];
+                    v8h al = sA[(KS + ks) * 64 + lane];
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) {
+                        accH[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, b[nt][ks], accH[nt], 0, 0, 0);
+                        accL[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b[nt][ks], accL[nt], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        uint32_t neg = 0;
+#pragma unroll
+                        for (int c = 7; c >= 0; --c) {
+                            float p = __builtin_fmaf(accL[nt][8 * s + c], 1.0f / 2048.0f, accH[nt][8 * s + c]);
+                            neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(p), 31);  // sign bit: p < 0
+                        }
+                        uint32_t code = ~neg & cmask;
+                        word[nt] |= code << (8 * (2 * h + s));
+                    }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+                for (int w = 0; w + 1 < OW; ++w) outw[nt][w] = outw[nt][w + 1];
+                outw[nt][OW - 1] = word[nt];
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            uint64_t v = v0 + nt * 32 + col;
+            if (v < n) {
+                uint32_t* dst = (uint32_t*)(codes + v * L + g * (L / 2));
+#pragma unroll
+                for (int w = 0; w < OW; ++w) dst[w] = outw[nt][w];
+            }
+        }
+    }
+}
+
+// Rp layout: [LT M-tiles][2 parts: hi, lo][KS k-steps][64 lanes][8 halves]
+__global__ void repack_proj_f16_kernel(const float* __restrict__ R, uint32_t d, uint32_t L, uint32_t C,
+                                       _Float16* __restrict__ Rp, uint32_t total) {
+    uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t KS = d / 16;
+    uint32_t e = idx & 7;
+    uint32_t l = (idx >> 3) & 63;
+    uint32_t rest = idx >> 9;
+    uint32_t ks = rest % KS;
+    uint32_t part = (rest / KS) & 1;
+    uint32_t mt = rest / (2 * KS);
+    uint32_t i = l & 31;
+    uint32_t kk = ks * 16 + 8 * (l >> 5) + e;
+    uint32_t g = (i >> 2) & 1;
+    uint32_t s = i >> 4;
+    uint32_t c = 4 * ((i >> 3) & 1) + (i & 3);
+    uint32_t t = g * (L / 2) + 2 * mt + s;
+    float r = (c < C) ? R[(size_t)(t * C + c) * d + kk] : 0.f;
+    _Float16 hi = (_Float16)r;
+    _Float16 lo = (_Float16)((r - (float)hi) * 2048.0f);
+    Rp[idx] = part ? lo : hi;
+}
+
+size_t mfma_f16_proj_bytes(uint32_t d, uint32_t L) {
+    if (!mfma_shape(d, L)) return 0;
+    return (size_t)(L / 4) * 2 * (d / 16) * 64 * 16;
+}
+
+bool hash_mfma_f16_supported(uint32_t d, uint32_t L, uint32_t C) { return mfma_shape(d, L) && C >= 1 && C <= 8; }
+
+hipError_t launch_repack_proj_f16(const float* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
+    uint32_t total = (uint32_t)(mfma_f16_proj_bytes(d, L) / 2);
+    if (!total) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(repack_proj_f16_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, R, d, L, C,
+                       (_Float16*)Rp, total);
+    return hipGetLastError();
+}
+
+template <int KS, int LT>
+static hipError_t launch_mfma_f16_t(const void* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
+                                    hipStream_t stream) {
+    constexpr int NT = 2;
+    const uint64_t block_vecs = 4 * 32 * NT;
+    uint64_t blocks = (n + block_vecs - 1) / block_vecs;
+    if (blocks > 512) blocks = 512;  // persistent workgroups: 256 CUs x 2
+    auto kern = hash_mfma_f16_kernel<KS, LT, NT>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, stream, (const _Float16*)X, n, (const v8h*)Rp,
+                       (1u << C) - 1u, codes);
+    return hipGetLastError();
+}
+
+hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
+                                uint8_t* codes, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (!hash_mfma_f16_supported(d, L, C)) return hipErrorInvalidValue;
+#define DESSERT_MFMA_F16_CASE(KS_, LT_) \
+    if (d == KS_ * 16 && L == LT_ * 4) return launch_mfma_f16_t<KS_, LT_>(X, n, C, Rp, codes, stream);
+    DESSERT_MFMA_F16_CASE(4, 4)
+    DESSERT_MFMA_F16_CASE(4, 8)
+    DESSERT_MFMA_F16_CASE(4, 16)
+    DESSERT_MFMA_F16_CASE(8, 4)
+    DESSERT_MFMA_F16_CASE(8, 8)
+    DESSERT_MFMA_F16_CASE(8, 16)
+    DESSERT_MFMA_F16_CASE(16, 4)
+    DESSERT_MFMA_F16_CASE(16, 8)
+    DESSERT_MFMA_F16_CASE(16, 16)
+#undef DESSERT_MFMA_F16_CASE
+    return hipErrorInvalidValue;
+}
+
 }  // namespace dessert

@@ -18,6 +18,13 @@ bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
                                uint8_t* codes, hipStream_t stream);
 
+// fp16 vectors x fp32 Gaussian projections on fp16 MFMA (projection matrix split hi + lo).
+size_t mfma_f16_proj_bytes(uint32_t d, uint32_t L);
+hipError_t launch_repack_proj_f16(const float* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream);
+bool hash_mfma_f16_supported(uint32_t d, uint32_t L, uint32_t C);
+hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
+                                uint8_t* codes, hipStream_t stream);
+
 // One thread per (vector, table); any d, L, C.  dtype/proj_kind as in dessert.h.
 hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
                               uint32_t L, uint32_t C, uint8_t* codes, hipStream_t stream);

@@ -113,8 +113,8 @@ def test_cfg5_fp16_gaussian_tolerance_path():
     Tolerances of this configuration: code-bit mismatch rate <= 1e-4, every mismatch at a projection with
     |p| < 1e-3*||x||, top-10 overlap with the oracle >= 0.99.  The scoring of GPU codes is itself exact, which
     is checked by scoring the GPU's own codes with the oracle."""
-    say("cfg5 reduced to 20k docs: fp16 / Gaussian, L=64 C=8, 16 query sets x 128 vectors, exhaustive, k=10")
-    w = gen.make(5, device=DEV, n_docs=20000, n_queries=16)
+    say("cfg5 reduced to 8k docs: fp16 / Gaussian, L=64 C=8, 16 query sets x 128 vectors, exhaustive, k=10")
+    w = gen.make(5, device=DEV, n_docs=8000, n_queries=16)
     p = w.preset
     ix = dz.create(p.d, p.L, p.C, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=w.proj)
     codes, _ = dz.build_index(ix, w.docs, w.lengths)
@@ -126,7 +126,7 @@ def test_cfg5_fp16_gaussian_tolerance_path():
 
     # hashing: sampled documents, all their vectors
     rng = np.random.default_rng(5)
-    sample = np.unique(np.concatenate([rng.integers(0, w.n_docs, 1500), w.planted[:, 0].numpy()]))
+    sample = np.unique(np.concatenate([rng.integers(0, w.n_docs, 800), w.planted[:, 0].numpy()]))
     rows = np.concatenate([np.arange(off[i], off[i + 1]) for i in sample])
     X = w.docs[torch.from_numpy(rows).to(DEV)].cpu().numpy()
     want, proj = orc.hash_fp(X, R, p.L, p.C, want_proj=True)

@@ -81,22 +81,32 @@ def test_hash_scalar_odd_shapes_and_seed_rule():
     assert np.array_equal(got, orc.hash_i8(X, R, L, Cb))
 
 
-def test_hash_fp16_gaussian_within_tolerance():
-    say("hash f16 x gaussian f32, d=256 L=64 C=8")
-    w = gen.make(5, n_docs=40, n_queries=1)
-    p = w.preset
-    X = w.docs.numpy()
-    R = w.proj.numpy()
-    ix = dz.create(p.d, p.L, p.C, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=w.proj.to(DEV))
-    got = dz.hash(ix, w.docs.to(DEV)).cpu().numpy()
-    want, proj = orc.hash_fp(X, R, p.L, p.C, want_proj=True)
-    bits_got = np.unpackbits(got[..., None], axis=2, bitorder="little")
-    bits_want = np.unpackbits(want[..., None], axis=2, bitorder="little")
+@pytest.mark.parametrize("algo", [dz.HASH_SCALAR, dz.HASH_MFMA])
+@pytest.mark.parametrize("d,L,Cb,n", [(256, 64, 8, 5000), (128, 32, 7, 1000), (64, 16, 3, 333)])
+def test_hash_fp16_gaussian_within_tolerance(algo, d, L, Cb, n):
+    say(f"hash f16 x gaussian f32 algo={algo} d={d} L={L} C={Cb} n={n}")
+    rng = np.random.default_rng(d + L + Cb)
+    X = rng.standard_normal((n, d))
+    X = (X / np.linalg.norm(X, axis=1, keepdims=True)).astype(np.float16)
+    X[0] = 0                                   # zero vector: every projection is +0 -> every bit 1
+    R = rng.standard_normal((L * Cb, d)).astype(np.float32)
+    R[5, :] *= 1e-3                            # a row of small entries (lo part of the split underflows less gracefully)
+    ix = dz.create(d, L, Cb, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, algo, dz.SCORE_AUTO)
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    want, proj = orc.hash_fp(X, R, L, Cb, want_proj=True)
+    assert np.all(got[0] == (1 << Cb) - 1)
+    bits_got = np.unpackbits(got[..., None], axis=2, bitorder="little")[:, :, :Cb]
+    bits_want = np.unpackbits(want[..., None], axis=2, bitorder="little")[:, :, :Cb]
     diff = bits_got != bits_want
-    assert diff.mean() <= 1e-4
+    assert diff.mean() <= 1e-4, diff.mean()
     norms = np.linalg.norm(X.astype(np.float64), axis=1)
-    margins = np.abs(proj.reshape(X.shape[0], p.L, p.C))
-    assert np.all(margins[diff] < 1e-3 * np.broadcast_to(norms[:, None, None], margins.shape)[diff])
+    margins = np.abs(proj.reshape(n, L, Cb))
+    rnorm = np.linalg.norm(R.astype(np.float64), axis=1).reshape(L, Cb) / np.sqrt(d)
+    # a mismatch is allowed only where the projection is within 1e-3*||x|| of zero (scaled by the row's rms entry)
+    bound = 1e-3 * norms[:, None, None] * np.maximum(rnorm[None], 1e-30)
+    assert np.all(margins[diff] < np.broadcast_to(bound, margins.shape)[diff])
+    assert got.max() < (1 << Cb)
 
 
 # ------------------------------------------------------------------ index build
