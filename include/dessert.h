@@ -97,6 +97,20 @@ dessert_status_t dessert_get_projection(const dessert_index_t *index, void *proj
  * does not support the configuration makes the later call return EINVAL. */
 dessert_status_t dessert_set_algo(dessert_index_t *index, int hash_algo, int score_algo);
 
+/* Score transform.
+ *   DESSERT_SCORE_RAW_COUNTS (default): score = sum_q max_x cnt(q,x), an integer in [0, |Q|*L].
+ *   DESSERT_SCORE_EQ1_Q16: the paper's practical pipeline (Sec. 5, concatenation trick, Eq. 1): each
+ *     per-query-vector maximum count c is first turned into a similarity estimate
+ *         sim(c) = exp(ln(c / L) / C)   (sim(0) = 0),
+ *     tabulated once for the L+1 possible counts as the fixed-point integer
+ *     round(65536 * sim(c)) (round half away from zero), and the score is the sum of these
+ *     integers over the query vectors.  score / (65536 * |Q|) is the paper's "average of max
+ *     similarities" (Sec. 6, experiment setup).  Integer sums keep the result independent of
+ *     summation order.  Needs |Q| <= 16383.
+ * Applies to later dessert_search / dessert_scores calls. */
+enum { DESSERT_SCORE_RAW_COUNTS = 0, DESSERT_SCORE_EQ1_Q16 = 1 };
+dessert_status_t dessert_set_score_transform(dessert_index_t *index, int transform);
+
 /* Bytes of the code array for n_vectors vectors: n_vectors * L (one byte per
  * vector and table, vector-major, no padding). */
 size_t dessert_code_bytes(const dessert_index_t *index, uint64_t n_vectors);

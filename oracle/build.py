@@ -13,7 +13,7 @@ def build(force: bool = True) -> pathlib.Path:
     if not force and LIB.exists() and LIB.stat().st_mtime >= SRC.stat().st_mtime:
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-           str(SRC), "-o", str(LIB)]
+           str(SRC), "-o", str(LIB), "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -20,9 +20,10 @@
  *   - bit c of table t comes from projection row t*C + c and lands in bit c
  *     of the table's code.
  *   - sign(0): a projection that is exactly zero gives bit 1 (p >= 0).
- *   - sigma = max, A = sum (Sec. 2, ColBERT's sum of max similarities); the
- *     division by L in Alg. 2 and the remap of Eq. 1 are left out, so the
- *     score is an integer in [0, |Q|*L].
+ *   - sigma = max, A = sum (Sec. 2, ColBERT's sum of max similarities); in
+ *     oracle_scores the division by L in Alg. 2 and the remap of Eq. 1 are left
+ *     out, so the score is an integer in [0, |Q|*L]; oracle_scores_eq1 applies
+ *     both.
  *   - an empty document scores 0 (Alg. 2 starts every count at 0).
  *   - top-k order: score descending, ties by ascending document id.
  *
@@ -32,6 +33,7 @@
  * hand-computed example, numpy lexsort for top-k).  What stays unpinned:
  * recall / latency on the paper's real datasets (not available).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -146,6 +148,50 @@ void oracle_scores(const uint8_t *doc_codes, const int64_t *offsets, uint32_t L,
         }
         scores[s] = score;
     }
+}
+
+/* ---- scoring with the similarity remap of Sec. 5 ("concatenation trick", Eq. 1):
+ * Alg. 2 as the paper's implementation runs it: count / L  ->  Eq. 1  ->  sigma = max  ->  A.
+ * Eq. 1: sim = exp(ln(p_hat) / C) with p_hat = count / L; a count of 0 gives similarity 0
+ * (the limit of Eq. 1).  The L+1 possible values are tabulated once, as the paper says its
+ * implementation does.  Reading taken here (the paper does not fix a number format): each
+ * per-query-vector maximum enters the sum as the fixed-point integer round(65536 * sim)
+ * (llround: half away from zero), so the result does not depend on summation order;
+ * score / (65536 * mq) is the paper's average of max similarities.  sim_table (optional,
+ * [L+1] doubles) receives the table.
+ */
+void oracle_scores_eq1(const uint8_t *doc_codes, const int64_t *offsets, uint32_t L, uint32_t C,
+                       const uint8_t *q_codes, uint32_t mq,
+                       const int64_t *doc_ids, uint64_t n_scored, int32_t *scores, double *sim_table)
+{
+    double *sim = (double *)malloc((L + 1) * sizeof(double));
+    for (uint32_t c = 0; c <= L; ++c) {
+        double p_hat = (double)c / (double)L;                       /* Alg. 2: s_hat / L */
+        sim[c] = (c == 0) ? 0.0 : exp(log(p_hat) / (double)C);      /* Eq. 1 */
+        if (sim_table)
+            sim_table[c] = sim[c];
+    }
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t s = 0; s < (int64_t)n_scored; ++s) {
+        int64_t i = doc_ids ? doc_ids[s] : s;
+        int64_t lo = offsets[i], hi = offsets[i + 1];
+        int64_t score = 0;
+        for (uint32_t q = 0; q < mq; ++q) {
+            const uint8_t *hq = q_codes + (size_t)q * L;
+            double agg = 0.0;                                       /* sigma = max, empty set -> 0 */
+            for (int64_t j = lo; j < hi; ++j) {
+                const uint8_t *hx = doc_codes + (size_t)j * L;
+                int32_t cnt = 0;
+                for (uint32_t t = 0; t < L; ++t)
+                    cnt += (hq[t] == hx[t]);
+                if (sim[cnt] > agg)
+                    agg = sim[cnt];
+            }
+            score += llround(65536.0 * agg);                        /* A = sum, in Q16 */
+        }
+        scores[s] = (int32_t)score;
+    }
+    free(sim);
 }
 
 /* ---- top-k: Alg. 2 last line (argmax), widened to the k best.

@@ -86,6 +86,28 @@ def scores(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, doc_
     return out
 
 
+def scores_eq1(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, Cbits: int, doc_ids=None,
+               want_table: bool = False):
+    """Scores with the Eq. 1 similarity remap, Q16 fixed point (see oracle_scores_eq1)."""
+    doc_codes = np.ascontiguousarray(doc_codes, dtype=np.uint8)
+    q_codes = np.ascontiguousarray(q_codes, dtype=np.uint8)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    L = q_codes.shape[1]
+    assert doc_codes.ndim == 2 and doc_codes.shape[1] == L and offsets[-1] <= doc_codes.shape[0]
+    n_docs = offsets.shape[0] - 1
+    if doc_ids is None:
+        n, ids = n_docs, None
+    else:
+        ids = np.ascontiguousarray(doc_ids, dtype=np.int64)
+        n = ids.shape[0]
+        assert n == 0 or (ids.min() >= 0 and ids.max() < n_docs)
+    out = np.empty(n, dtype=np.int32)
+    table = np.empty(L + 1, dtype=np.float64) if want_table else None
+    lib().oracle_scores_eq1(_p(doc_codes), _p(offsets), C.c_uint32(L), C.c_uint32(Cbits), _p(q_codes),
+                            C.c_uint32(q_codes.shape[0]), _p(ids), C.c_uint64(n), _p(out), _p(table))
+    return (out, table) if want_table else out
+
+
 def topk(score: np.ndarray, k: int, ids=None):
     score = np.ascontiguousarray(score, dtype=np.int32)
     ids_a = None if ids is None else np.ascontiguousarray(ids, dtype=np.int64)

@@ -7,7 +7,7 @@ built (run ``python -m paper_2210_15748_amd.build`` or ``__graft_entry__.build()
 
 Function names mirror the C entry points without the ``dessert_`` prefix:
 ``create`` / ``destroy`` / ``hash`` / ``build_index`` / ``search`` / ``scores`` /
-``set_algo`` / ``get_projection`` / ``enable_timing`` / ``get_timing``.
+``set_algo`` / ``set_score_transform`` / ``get_projection`` / ``enable_timing`` / ``get_timing``.
 """
 from __future__ import annotations
 
@@ -28,8 +28,11 @@ PROJ_RADEMACHER_I8, PROJ_GAUSSIAN_F32 = 0, 1
 HASH_AUTO, HASH_SCALAR, HASH_MFMA = 0, 1, 2
 SCORE_AUTO, SCORE_BYTECMP, SCORE_MASKLUT = 0, 1, 2
 
+SCORE_RAW_COUNTS, SCORE_EQ1_Q16 = 0, 1
+
 EXPORTS = [
-    "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_code_bytes",
+    "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_set_score_transform",
+    "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
     "dessert_enable_timing", "dessert_get_timing", "dessert_last_error", "dessert_version",
 ]
@@ -65,6 +68,7 @@ def lib() -> C.CDLL:
     l.dessert_destroy.restype = None
     l.dessert_get_projection.argtypes = [vp, vp]
     l.dessert_set_algo.argtypes = [vp, C.c_int, C.c_int]
+    l.dessert_set_score_transform.argtypes = [vp, C.c_int]
     l.dessert_code_bytes.argtypes = [vp, u64]
     l.dessert_code_bytes.restype = sz
     l.dessert_hash.argtypes = [vp, vp, u64, vp]
@@ -154,6 +158,10 @@ def destroy(ix: Index) -> None:
 
 def set_algo(ix: Index, hash_algo: int = HASH_AUTO, score_algo: int = SCORE_AUTO) -> None:
     _check(lib().dessert_set_algo(ix.handle, hash_algo, score_algo))
+
+
+def set_score_transform(ix: Index, transform: int) -> None:
+    _check(lib().dessert_set_score_transform(ix.handle, transform))
 
 
 def get_projection(ix: Index) -> torch.Tensor:

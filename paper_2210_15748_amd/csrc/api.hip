@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -54,6 +55,8 @@ struct dessert_index {
     hipStream_t stream = nullptr;
     void* proj = nullptr;       // device, [L*C][d] int8 or float (library-owned copy)
     void* proj_mfma = nullptr;  // device, MFMA-ordered int8 copy (or null)
+    uint32_t* remap = nullptr;  // device, [L+1] Eq. 1 table in Q16 (library-owned)
+    int transform = DESSERT_SCORE_RAW_COUNTS;
     int hash_algo = DESSERT_HASH_AUTO;
     int score_algo = DESSERT_SCORE_AUTO;
     // index state
@@ -205,6 +208,8 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     dessert_status_t st = check_batch(ix, q_vectors, q_lengths, B, cand_ids, cand_off, &bt);
     if (st != DESSERT_OK) return st;
     if (B == 0) return DESSERT_OK;
+    if (ix->transform == DESSERT_SCORE_EQ1_Q16 && bt.max_q_len > 16383)
+        return fail(DESSERT_EINVAL, "the Eq. 1 score transform needs query sets of at most 16383 vectors");
     if (!workspace) return fail(DESSERT_EINVAL, "workspace_dev is NULL");
     if ((uintptr_t)workspace % 256) return fail(DESSERT_EINVAL, "workspace_dev must be 256-byte aligned");
     const bool own_scores = scores_out == nullptr;
@@ -263,6 +268,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     sa.qcodes = qcodes; sa.q_off = d_q_off; sa.q_uniform = bt.q_uniform; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
     sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr; sa.cand_uniform = cand_ids ? bt.cand_uniform : 0;
     sa.max_scored = bt.max_scored; sa.scores = scores;
+    sa.remap = ix->transform == DESSERT_SCORE_EQ1_Q16 ? ix->remap : nullptr;
     int algo = ix->score_algo;
     // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
     if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
@@ -282,7 +288,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     if (k) {
         TopkArgs ta{};
         ta.scores = scores; ta.cand_ids = cand_ids; ta.cand_off = sa.cand_off; ta.cand_uniform = sa.cand_uniform; ta.n_docs = ix->n_docs;
-        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = bt.max_q_len * ix->cfg.L;
+        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = sa.remap ? bt.max_q_len * 65536u : bt.max_q_len * ix->cfg.L;
         ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
         HIP_TRY(launch_topk(ta, ix->stream));
         if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
@@ -356,6 +362,7 @@ void dessert_destroy(dessert_index_t* ix) {
     if (ix->upload_done) (void)hipEventDestroy(ix->upload_done);
     if (ix->proj) (void)hipFree(ix->proj);
     if (ix->proj_mfma) (void)hipFree(ix->proj_mfma);
+    if (ix->remap) (void)hipFree(ix->remap);
     if (ix->h_offsets) (void)hipHostFree(ix->h_offsets);
     for (auto& slot : ix->slots)
         for (auto& ev : slot.ev)
@@ -382,6 +389,24 @@ dessert_status_t dessert_set_algo(dessert_index_t* ix, int hash_algo, int score_
         return fail(DESSERT_EINVAL, "unknown scoring algorithm %d", score_algo);
     ix->hash_algo = hash_algo;
     ix->score_algo = score_algo;
+    return DESSERT_OK;
+}
+
+dessert_status_t dessert_set_score_transform(dessert_index_t* ix, int transform) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (transform != DESSERT_SCORE_RAW_COUNTS && transform != DESSERT_SCORE_EQ1_Q16)
+        return fail(DESSERT_EINVAL, "unknown score transform %d", transform);
+    if (transform == DESSERT_SCORE_EQ1_Q16 && !ix->remap) {
+        // Eq. 1 for the L+1 possible collision counts: sim(c) = exp(ln(c/L)/C), sim(0) = 0, in Q16
+        DeviceGuard guard(ix->cfg.device);
+        const uint32_t L = ix->cfg.L, C = ix->cfg.C;
+        std::vector<uint32_t> tab(L + 1, 0);
+        for (uint32_t c = 1; c <= L; ++c)
+            tab[c] = (uint32_t)std::llround(65536.0 * std::exp(std::log((double)c / (double)L) / (double)C));
+        HIP_TRY(hipMalloc((void**)&ix->remap, (L + 1) * sizeof(uint32_t)));
+        HIP_TRY(hipMemcpy(ix->remap, tab.data(), (L + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+    }
+    ix->transform = transform;
     return DESSERT_OK;
 }
 

@@ -45,6 +45,7 @@ struct ScoreArgs {
     uint64_t cand_uniform;      // != 0: every candidate list has this many ids
     uint64_t max_scored;        // largest number of documents scored by one query set
     int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
+    const uint32_t* remap;      // dev [L+1] fixed-point similarity per collision count (Eq. 1), or nullptr: raw counts
 };
 // first query vector / first candidate slot of query set b (b may be n_queries: one past the end)
 __device__ inline uint32_t q_begin(const ScoreArgs& a, uint32_t b) { return a.q_uniform ? b * a.q_uniform : a.q_off[b]; }

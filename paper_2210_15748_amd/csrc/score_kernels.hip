@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
                 int32_t o = __shfl_xor(best, off, 64);
                 best = o > best ? o : best;
             }
-            score += best;
+            score += a.remap ? (int32_t)a.remap[best] : best;
         }
         if (lane == 0) a.scores[sp.base + pos] = score;
     }
@@ -188,7 +188,8 @@ struct LutBlockMeta {
 // every G-th vector of its document.  Documents of a block are ordered by length class
 // ceil(m/G) (counting sort in LDS) and waves claim runs of 64/G consecutive documents from that
 // order, so the documents sharing a wave need the same number of rounds and few lanes idle.
-template <int LW, int CB>
+// REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
+template <int LW, int CB, bool REMAP>
 __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block) {
     constexpr int L = LW * 4;
     constexpr int STRIDE = 1 << CB;
@@ -319,8 +320,28 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
             for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[p]);   // quad_perm [2,3,0,1]
             planes_max<P>(mx, o);
             int32_t score = 0;
+            if constexpr (!REMAP) {
 #pragma unroll
-            for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[p]);
+                for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[p]);
+            } else {
+                // similarity remap (Eq. 1 as a table of L+1 fixed-point values): every lane of the
+                // group holds the merged maxima; lane `sub` un-slices query vectors sub, sub+8,
+                // sub+16, sub+24, looks their maxima up, and the eight partial sums are added
+                // (integers, so the order does not matter)
+                uint32_t part = 0;
+#pragma unroll
+                for (int jq = 0; jq < 32 / G; ++jq) {
+                    const uint32_t q = sub + G * jq;
+                    uint32_t v = 0;
+#pragma unroll
+                    for (int p = P - 1; p >= 0; --p) v = 2 * v + ((mx[p] >> q) & 1u);
+                    part += a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
+                }
+                part += dpp_mov<0x141>(part);  // row_half_mirror
+                part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
+                part += dpp_mov<0x4E>(part);   // quad_perm [2,3,0,1]
+                score = (int32_t)part;
+            }
             if (valid && sub == 0) {
                 int32_t* dst = a.scores + sp.base + first + doc;
                 if (qc == q_lo)
@@ -338,7 +359,7 @@ bool score_masklut_supported(uint32_t L, uint32_t C) {
 
 template <int LW, int CB>
 static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
-    auto kern = score_masklut_kernel<LW, CB>;
+    auto kern = a.remap ? score_masklut_kernel<LW, CB, true> : score_masklut_kernel<LW, CB, false>;
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
     // workgroups, but at least 64 so the table build stays amortised
     uint32_t dpb = LUT_DOCS;

@@ -300,3 +300,56 @@ def test_search_before_build_is_a_state_error():
     with pytest.raises(dz.DessertError) as e:
         dz.search(ix, q, [4], 3)
     assert e.value.status == dz.ESTATE
+
+
+# ------------------------------------------------------------------ Eq. 1 score transform (Sec. 5)
+@pytest.mark.parametrize("algo", [dz.SCORE_BYTECMP, dz.SCORE_MASKLUT])
+@pytest.mark.parametrize("L,Cb,q_lens", [(32, 7, [32, 5, 33]), (64, 8, [40, 64]), (16, 1, [8, 8])])
+def test_scores_eq1_transform_bit_exact(algo, L, Cb, q_lens):
+    say(f"scores Eq.1 transform algo={algo} L={L} C={Cb} q_lens={q_lens}")
+    rng = np.random.default_rng(L + Cb)
+    d = 64
+    lens = rng.integers(0, 50, 400)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (30, d))
+    X = np.clip(pool[rng.integers(0, 30, V)] + rng.integers(-25, 26, (V, d)), -127, 127).astype(np.int8)
+    nq = int(sum(q_lens))
+    Q = np.clip(pool[rng.integers(0, 30, nq)] + rng.integers(-25, 26, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_AUTO, algo)
+    dz.set_score_transform(ix, dz.SCORE_EQ1_Q16)
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens).cpu().numpy()
+    for b in range(len(q_lens)):
+        assert np.array_equal(got[b], orc.scores_eq1(dc, off, qc[qo[b]:qo[b + 1]], Cb)), b
+    # top-k on the transformed scores, candidate mode with duplicates
+    cand = rng.integers(0, 400, (len(q_lens), 150))
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, 20, cand_ids=torch.from_numpy(cand).to(DEV))
+    for b in range(len(q_lens)):
+        s = orc.scores_eq1(dc, off, qc[qo[b]:qo[b + 1]], Cb, cand[b])
+        want_ids, want_sc = orc.topk(s, 20, cand[b])
+        assert np.array_equal(ids[b].cpu().numpy(), want_ids) and np.array_equal(sc[b].cpu().numpy(), want_sc), b
+    # back to raw counts
+    dz.set_score_transform(ix, dz.SCORE_RAW_COUNTS)
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens).cpu().numpy()
+    assert np.array_equal(got[0], orc.scores(dc, off, qc[qo[0]:qo[1]]))
+
+
+def test_search_eq1_cfg3_reduced_changes_ranking_but_matches_oracle():
+    w = gen.make(3, n_docs=30000, n_queries=6, n_cand=2048)
+    p = w.preset
+    say("search Eq.1 cfg3-reduced")
+    ix, codes, _ = make_index(w)
+    dz.set_score_transform(ix, dz.SCORE_EQ1_Q16)
+    cand = w.cand_ids.to(DEV)
+    ids, sc = dz.search(ix, w.queries.to(DEV), w.q_lengths, p.k, cand_ids=cand)
+    dc, qc = oracle_codes(w)
+    for b in range(p.n_queries):
+        c = w.cand_ids[b].numpy()
+        s = orc.scores_eq1(dc, w.offsets.numpy(), qc[b * p.q_len:(b + 1) * p.q_len], p.C, c)
+        want_ids, want_sc = orc.topk(s, p.k, c)
+        assert np.array_equal(ids[b].cpu().numpy(), want_ids) and np.array_equal(sc[b].cpu().numpy(), want_sc), b

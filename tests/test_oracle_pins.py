@@ -34,7 +34,7 @@ def pair_at_angle(rng, d, theta):
 
 # ---------------------------------------------------------------- P7 hand example
 def load_hand():
-    R, X, P, Cd, S = [], [], [], [], []
+    R, X, P, Cd, S, E = [], [], [], [], [], []
     for line in open(os.path.join(GOLDEN, "hand_example.txt")):
         line = line.strip()
         if not line or line.startswith("#"):
@@ -47,11 +47,13 @@ def load_hand():
             X.append(parts[0]); P.append(parts[1]); Cd.append(parts[2])
         elif tag == "S":
             S.append((parts[0], parts[1], parts[2][0]))
-    return (np.array(R, np.int8), np.array(X, np.int8), np.array(P, np.int32), np.array(Cd, np.uint8), S)
+        elif tag == "E":
+            E.append((parts[0], parts[1], parts[2][0]))
+    return (np.array(R, np.int8), np.array(X, np.int8), np.array(P, np.int32), np.array(Cd, np.uint8), S, E)
 
 
 def test_p7_hand_example_codes_and_scores():
-    R, X, P, Cd, S = load_hand()
+    R, X, P, Cd, S, E = load_hand()
     codes, proj = orc.hash_i8(X, R, 2, 2, want_proj=True)
     assert np.array_equal(proj, P)
     assert np.array_equal(codes, Cd)
@@ -61,6 +63,9 @@ def test_p7_hand_example_codes_and_scores():
     for q_idx, s_idx, want in S:
         doc = codes[s_idx]
         got = orc.scores(doc, np.array([0, len(s_idx)]), codes[q_idx])
+        assert got.tolist() == [want]
+    for q_idx, s_idx, want in E:
+        got = orc.scores_eq1(codes[s_idx], np.array([0, len(s_idx)]), codes[q_idx], 2)
         assert got.tolist() == [want]
 
 
@@ -316,3 +321,43 @@ def test_search_chain_top1_is_planted_on_cfg1():
     assert np.array_equal(ids[:, 0], w.planted[:, 0].numpy().astype(np.uint32))
     assert np.all(np.diff(sc.astype(np.int64), axis=1) <= 0)
     assert sc.max() <= p.q_len * p.L
+
+
+# ---------------------------------------------------------------- Eq. 1 remap (Sec. 5)
+def test_eq1_table_endpoints_monotone_and_identity_for_one_bit_tables():
+    rng = np.random.default_rng(31)
+    L, d = 32, 16
+    X = rng.integers(-127, 128, (60, d)).astype(np.int8)
+    off = np.arange(0, 61, 5)
+    for Cbits in (1, 4, 7):
+        R = (rng.integers(0, 2, (L * Cbits, d)) * 2 - 1).astype(np.int8)
+        codes = orc.hash_i8(X, R, L, Cbits)
+        s, table = orc.scores_eq1(codes, off, codes[:9], Cbits, want_table=True)
+        assert table[0] == 0.0 and table[L] == 1.0 and np.all(np.diff(table) > 0)
+        raw = orc.scores(codes, off, codes[:9])
+        assert np.all(s >= 0) and np.all(s <= 9 * 65536)
+        if Cbits == 1:
+            # C = 1: Eq. 1 is the identity on count/L, and 65536/L is an integer for L = 32
+            assert np.array_equal(s, raw * (65536 // L))
+        else:
+            # the remap is concave: per-vector similarities are at least count/L
+            assert np.all(s >= raw * (65536 // L))
+        # a document containing every query vector reaches similarity 1 for each of them
+        assert orc.scores_eq1(codes[:9], np.array([0, 9]), codes[:9], Cbits)[0] == 9 * 65536
+
+
+@pytest.mark.parametrize("Cbits", [2, 5])
+@pytest.mark.parametrize("theta", [0.3, 1.0])
+def test_eq1_recovers_the_angular_similarity(Cbits, theta):
+    # Sec. 5: concatenating C hashes turns the collision probability into sim^C; Eq. 1 undoes it.
+    rng = np.random.default_rng(200 + Cbits)
+    d, L = 24, 40000
+    a, b = pair_at_angle(rng, d, theta)
+    R = rng.standard_normal((L * Cbits, d)).astype(np.float32)
+    codes = orc.hash_fp(np.stack([a, b]).astype(np.float32), R, L, Cbits)
+    est = orc.scores_eq1(codes[1:2], np.array([0, 1]), codes[0:1], Cbits)[0] / 65536.0
+    sim = 1 - theta / math.pi
+    p = sim ** Cbits
+    # delta method: sd(p_hat^(1/C)) = sd(p_hat) * p^(1/C - 1) / C
+    sd = math.sqrt(p * (1 - p) / L) * p ** (1.0 / Cbits - 1) / Cbits
+    assert abs(est - sim) < 4.5 * sd + 2e-5, (est, sim, sd)
