@@ -32,6 +32,29 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def traffic_from_profile(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel calibration factors 2.0 and 1.0 stated there).
+    Valid for the full candidate-rerank preset only; None if the summary is missing."""
+    path = os.path.join(ROOT, "profiles", "cfg3_search_and_build_kernels.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    vals = {}
+    section = None
+    for line in text.splitlines():
+        if line.startswith("## --pmc FETCH_SIZE"):
+            section = "fetch"
+        elif line.startswith("## --pmc WRITE_SIZE"):
+            section = "write"
+        elif section and kernel in line and "mean=" in line:
+            vals.setdefault(section, float(line.split("mean=")[1]))
+    if "fetch" not in vals or "write" not in vals:
+        return None
+    return int((vals["fetch"] * 2.0 + vals["write"] * 1.0) * 1024)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,7 +159,9 @@ def main() -> int:
         code_bytes = w.n_vectors * p.L * B      # each query set reads every document's codes once
     achieved = code_bytes / (score_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "score_masklut_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic_from_profile("score_masklut_kernel")
+                if (args.config == 3 and args.n_docs is None and args.n_queries is None) else None,
                 "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5)}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
