@@ -353,3 +353,56 @@ def test_search_eq1_cfg3_reduced_changes_ranking_but_matches_oracle():
         s = orc.scores_eq1(dc, w.offsets.numpy(), qc[b * p.q_len:(b + 1) * p.q_len], p.C, c)
         want_ids, want_sc = orc.topk(s, p.k, c)
         assert np.array_equal(ids[b].cpu().numpy(), want_ids) and np.array_equal(sc[b].cpu().numpy(), want_sc), b
+
+
+# ------------------------------------------------------------------ randomized sweep over configurations
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_end_to_end(seed):
+    """Random (d, L, C, lengths, query lengths, candidates, k, transform) through the default kernel choice."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([8, 24, 50, 64, 96, 128, 200, 256]))
+    L = int(rng.choice([4, 8, 12, 16, 20, 32, 48, 64, 128]))
+    Cb = int(rng.integers(1, 9))
+    n_docs = int(rng.integers(1, 700))
+    lens = rng.integers(0, int(rng.choice([3, 20, 90])), n_docs)
+    if lens.sum() == 0:
+        lens[0] = 2
+    V = int(lens.sum())
+    B = int(rng.integers(1, 5))
+    q_lens = rng.integers(1, int(rng.choice([4, 33, 70])), B)
+    k = int(rng.choice([1, 3, 10, 64, 300]))
+    eq1 = bool(rng.integers(0, 2))
+    use_cand = bool(rng.integers(0, 2))
+    say(f"random cfg seed={seed} d={d} L={L} C={Cb} N={n_docs} V={V} q_lens={q_lens.tolist()} k={k} eq1={eq1} cand={use_cand}")
+    pool = rng.integers(-127, 128, (25, d))
+    X = np.clip(pool[rng.integers(0, 25, V)] + rng.integers(-30, 31, (V, d)), -127, 127).astype(np.int8)
+    nq = int(q_lens.sum())
+    Q = np.clip(pool[rng.integers(0, 25, nq)] + rng.integers(-30, 31, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    if eq1:
+        dz.set_score_transform(ix, dz.SCORE_EQ1_Q16)
+    codes, offsets = dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    assert np.array_equal(codes.cpu().numpy(), dc)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    assert np.array_equal(offsets.cpu().numpy(), off)
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    if use_cand:
+        cands = [rng.integers(0, n_docs, int(rng.integers(0, 400))) for _ in range(B)]
+        co = np.concatenate([[0], np.cumsum([len(c) for c in cands])])
+        flat = torch.from_numpy(np.concatenate(cands).astype(np.int32)).to(DEV) if co[-1] else \
+            torch.zeros(1, dtype=torch.int32, device=DEV)[:0]
+        if co[-1] == 0:
+            return
+        ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, k, cand_ids=flat, cand_offsets=co)
+    else:
+        cands = [None] * B
+        ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, k)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    for b in range(B):
+        q = qc[qo[b]:qo[b + 1]]
+        s = orc.scores_eq1(dc, off, q, Cb, cands[b]) if eq1 else orc.scores(dc, off, q, cands[b])
+        want_ids, want_sc = orc.topk(s, k, cands[b])
+        assert np.array_equal(sc[b], want_sc), b
+        assert np.array_equal(ids[b], want_ids), b
