@@ -151,6 +151,12 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what a kernel that only reads gets out of HBM on this GPU (context for the roofline fraction)
+    probe = torch.empty(1 << 30, dtype=torch.int32, device=dev).zero_()     # 4 GiB
+    read_gbs = dz.probe_read_bandwidth(probe, reps=10)
+    del probe
+    log(f"[bench] plain streaming read: {read_gbs:.0f} GB/s")
+
     # ---- roofline of the dominant kernel (scoring): algorithmic bytes = code bytes of every scored document
     if cand is not None:
         doc_len = w.lengths.to(dev)[w.cand_ids.reshape(-1)]
@@ -162,7 +168,8 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic_from_profile("score_masklut_kernel")
                 if (args.config == 3 and args.n_docs is None and args.n_queries is None) else None,
-                "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5)}
+                "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5),
+                "measured_stream_read_GBs": round(read_gbs, 1), "frac_of_measured_stream": round(achieved / read_gbs, 4)}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     cpu = None

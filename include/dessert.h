@@ -174,6 +174,13 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
 dessert_status_t dessert_enable_timing(dessert_index_t *index, int enable);
 dessert_status_t dessert_get_timing(dessert_index_t *index, uint32_t calls_back, float ms[4]);
 
+/* Measurement aid, not part of the method: time `reps` passes of a kernel that only reads
+ * [buf_dev, buf_dev + bytes) with 16-byte loads (HIP events on `stream`; synchronises).  Gives
+ * the streaming-read rate this GPU actually delivers, to set beside the nameplate 8 TB/s.
+ * buf_dev: dev, 16-byte aligned, bytes >= 16; ms_per_pass: host, out. */
+dessert_status_t dessert_probe_read_bandwidth(const void *buf_dev, size_t bytes, int device, void *stream, int reps,
+                                              float *ms_per_pass);
+
 const char *dessert_last_error(void);
 const char *dessert_version(void);
 

@@ -34,7 +34,8 @@ EXPORTS = [
     "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_set_score_transform",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
-    "dessert_enable_timing", "dessert_get_timing", "dessert_last_error", "dessert_version",
+    "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
+    "dessert_version",
 ]
 
 
@@ -79,6 +80,7 @@ def lib() -> C.CDLL:
     l.dessert_scores.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
     l.dessert_enable_timing.argtypes = [vp, C.c_int]
     l.dessert_get_timing.argtypes = [vp, u32, C.POINTER(C.c_float)]
+    l.dessert_probe_read_bandwidth.argtypes = [vp, sz, C.c_int, vp, C.c_int, C.POINTER(C.c_float)]
     l.dessert_last_error.restype = C.c_char_p
     l.dessert_version.restype = C.c_char_p
     _lib = l
@@ -271,3 +273,12 @@ def get_timing(ix: Index, calls_back: int = 0):
     ms = (C.c_float * 4)()
     _check(lib().dessert_get_timing(ix.handle, calls_back, ms))
     return {"hash_ms": ms[0], "score_ms": ms[1], "topk_ms": ms[2], "total_ms": ms[3]}
+
+
+def probe_read_bandwidth(buf: torch.Tensor, reps: int = 10) -> float:
+    """dessert_probe_read_bandwidth: GB/s of a plain streaming read over `buf` (measurement aid)."""
+    ms = C.c_float()
+    nbytes = buf.numel() * buf.element_size()
+    stream = torch.cuda.current_stream(buf.device).cuda_stream
+    _check(lib().dessert_probe_read_bandwidth(buf.data_ptr(), nbytes, buf.device.index or 0, stream, reps, C.byref(ms)))
+    return nbytes / (ms.value * 1e-3) / 1e9

@@ -302,6 +302,30 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
 extern "C" {
 
 const char* dessert_last_error(void) { return g_err; }
+
+dessert_status_t dessert_probe_read_bandwidth(const void* buf_dev, size_t bytes, int device, void* stream, int reps,
+                                              float* ms_per_pass) {
+    if (!buf_dev || !ms_per_pass || bytes < 16 || reps < 1) return fail(DESSERT_EINVAL, "bad probe arguments");
+    if ((uintptr_t)buf_dev % 16) return fail(DESSERT_EINVAL, "probe buffer must be 16-byte aligned");
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", device);
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_read_probe(buf_dev, bytes, st);  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, st);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_read_probe(buf_dev, bytes, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(DESSERT_EHIP, "read probe: %s", hipGetErrorString(e));
+    *ms_per_pass = ms / (float)reps;
+    return DESSERT_OK;
+}
 const char* dessert_version(void) { return "dessert-gfx950 0.1"; }
 
 dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out) {

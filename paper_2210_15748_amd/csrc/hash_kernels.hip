@@ -457,4 +457,25 @@ hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t 
     return hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------
+// Plain streaming read (measurement aid): what HBM delivers to a kernel that does nothing but
+// read, for comparison with the 8 TB/s nameplate and with the scoring kernel's rate.
+__global__ __launch_bounds__(256) void read_probe_kernel(const v4i* __restrict__ p, size_t n16, int* sink) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    v4i acc = {0, 0, 0, 0};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        v4i a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc += a; acc += b; acc += c; acc += d;
+    }
+    for (; i < n16; i += stride) acc += p[i];
+    // a store that practically never happens keeps the loads alive
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5ee1c0de && sink) *sink = 1;
+}
+
+hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t stream) {
+    hipLaunchKernelGGL(read_probe_kernel, dim3(65536), dim3(256), 0, stream, (const v4i*)buf, bytes / 16, (int*)nullptr);
+    return hipGetLastError();
+}
+
 }  // namespace dessert

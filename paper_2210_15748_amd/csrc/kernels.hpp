@@ -29,6 +29,9 @@ hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t 
 hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
                               uint32_t L, uint32_t C, uint8_t* codes, hipStream_t stream);
 
+// ---- measurement aid: one pass of a plain streaming read over [buf, buf+bytes) ------------
+hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t stream);
+
 // ---- scoring (Alg. 2: collision counts, sigma = max, A = sum) ---------------
 struct ScoreArgs {
     const uint8_t* codes;       // [V][L]

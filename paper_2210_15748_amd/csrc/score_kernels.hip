@@ -151,22 +151,23 @@ __device__ inline uint32_t dpp_mov(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
 }
 
-// byte K of dw, times 4 (the LDS byte offset of a 32-bit table entry), in one SDWA shift
+// byte K of dw shifted left by `sh` (the LDS byte offset of a table entry of 1 << sh bytes), in one
+// SDWA shift; sh lives in a VGPR because SDWA takes no literal operand
 template <int K>
-__device__ inline uint32_t byte_x4(uint32_t dw, uint32_t two) {
+__device__ inline uint32_t byte_shl(uint32_t dw, uint32_t sh) {
     uint32_t r;
     if constexpr (K == 0)
         asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0"
-            : "=v"(r) : "v"(two), "v"(dw));
+            : "=v"(r) : "v"(sh), "v"(dw));
     else if constexpr (K == 1)
         asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
-            : "=v"(r) : "v"(two), "v"(dw));
+            : "=v"(r) : "v"(sh), "v"(dw));
     else if constexpr (K == 2)
         asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2"
-            : "=v"(r) : "v"(two), "v"(dw));
+            : "=v"(r) : "v"(sh), "v"(dw));
     else
         asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3"
-            : "=v"(r) : "v"(two), "v"(dw));
+            : "=v"(r) : "v"(sh), "v"(dw));
     return r;
 }
 
@@ -188,25 +189,37 @@ struct LutBlockMeta {
 // every G-th vector of its document.  Documents of a block are ordered by length class
 // ceil(m/G) (counting sort in LDS) and waves claim runs of 64/G consecutive documents from that
 // order, so the documents sharing a wave need the same number of rounds and few lanes idle.
+//
+// W = query sets per workgroup.  W = 2 (only when every document is scored for every query set)
+// stores the masks of two query sets side by side, M[t][h] = {mask of set 2y, mask of set 2y+1},
+// so one 8-byte LDS read serves 64 query vectors: a random 8-byte read costs about 6.8 cycles
+// per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
 // REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
-template <int LW, int CB, bool REMAP>
+template <int LW, int CB, bool REMAP, int W>
 __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block) {
     constexpr int L = LW * 4;
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
     constexpr int G = 8;
     constexpr int DOCS_PER_WAVE = 64 / G;
-    // static LDS: the table sits at a link-time constant address, so t*STRIDE*4 folds into the
+    // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
-    __shared__ uint32_t lut[L * STRIDE];
+    __shared__ __attribute__((aligned(8))) uint32_t lut[L * STRIDE * W];  // [t][h][w]
     __shared__ LutBlockMeta meta;
 
-    const uint32_t b = blockIdx.y;
-    const Span sp = query_span(a, b);
+    const uint32_t b0 = blockIdx.y * W;  // first query set of this workgroup
+    const Span sp = query_span(a, b0);   // W > 1: every set scores the same documents
     const uint64_t first = (uint64_t)blockIdx.x * docs_per_block;
     if (first >= sp.count) return;
     const uint32_t ndocs = (uint32_t)((first + docs_per_block < sp.count) ? docs_per_block : sp.count - first);
-    const uint32_t q_lo = q_begin(a, b), q_hi = q_begin(a, b + 1);
+    uint32_t q_lo[W], q_len[W], max_len = 0;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const bool have = b0 + w < a.n_queries;
+        q_lo[w] = have ? q_begin(a, b0 + w) : 0;
+        q_len[w] = have ? q_begin(a, b0 + w + 1) - q_lo[w] : 0;
+        max_len = q_len[w] > max_len ? q_len[w] : max_len;
+    }
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t sub = lane & (G - 1);  // lane within the document's group
     const uint32_t grp = lane / G;        // group within the wave
@@ -239,17 +252,20 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     __syncthreads();
     if (threadIdx.x < ndocs) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
 
-    const uint32_t two = 2;
-    for (uint32_t qc = q_lo; qc < q_hi; qc += 32) {
-        const uint32_t nq = (q_hi - qc < 32) ? q_hi - qc : 32;
+    const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
+    for (uint32_t c0 = 0; c0 < max_len; c0 += 32) {  // chunks of 32 query vectors
         __syncthreads();  // previous chunk's readers are done (and `order` is complete)
-        for (uint32_t i = threadIdx.x; i < L * STRIDE; i += 256) lut[i] = 0;
+        for (uint32_t i = threadIdx.x; i < L * STRIDE * W; i += 256) lut[i] = 0;
         if (threadIdx.x == 0) meta.next = 0;
         __syncthreads();
-        for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
-            uint32_t q = i / L, t = i % L;
-            uint32_t h = a.qcodes[(size_t)(qc + q) * L + t];
-            atomicOr(&lut[t * STRIDE + h], 1u << q);
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const uint32_t nq = c0 >= q_len[w] ? 0 : (q_len[w] - c0 < 32 ? q_len[w] - c0 : 32);
+            for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
+                uint32_t q = i / L, t = i % L;
+                uint32_t h = a.qcodes[(size_t)(q_lo[w] + c0 + q) * L + t];
+                atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
+            }
         }
         __syncthreads();
 
@@ -266,9 +282,11 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
             const uint64_t lo = m ? meta.lo[doc] : 0;
             const uint32_t last_j = m ? m - 1 : 0;
 
-            uint32_t mx[P];
+            uint32_t mx[W][P];
 #pragma unroll
-            for (int p = 0; p < P; ++p) mx[p] = 0;
+            for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int p = 0; p < P; ++p) mx[w][p] = 0;
 
             // lanes past the end re-read the document's last vector (a repeated vector cannot
             // change the maximum); the next round's codes are requested before this round's
@@ -291,63 +309,81 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
                 for (int w = 0; w < LW; ++w) dw[w] = nxt[w];
                 load_codes(j0 + G, nxt);
                 const char* lut_bytes = reinterpret_cast<const char*>(lut);
-                uint32_t msk[L];
+                uint32_t off[L];  // byte offset of x's entry within each table
 #pragma unroll
                 for (int w = 0; w < LW; ++w) {
-                    msk[4 * w + 0] = *(const uint32_t*)(lut_bytes + (4 * w + 0) * STRIDE * 4 + byte_x4<0>(dw[w], two));
-                    msk[4 * w + 1] = *(const uint32_t*)(lut_bytes + (4 * w + 1) * STRIDE * 4 + byte_x4<1>(dw[w], two));
-                    msk[4 * w + 2] = *(const uint32_t*)(lut_bytes + (4 * w + 2) * STRIDE * 4 + byte_x4<2>(dw[w], two));
-                    msk[4 * w + 3] = *(const uint32_t*)(lut_bytes + (4 * w + 3) * STRIDE * 4 + byte_x4<3>(dw[w], two));
+                    off[4 * w + 0] = byte_shl<0>(dw[w], entry_shift);
+                    off[4 * w + 1] = byte_shl<1>(dw[w], entry_shift);
+                    off[4 * w + 2] = byte_shl<2>(dw[w], entry_shift);
+                    off[4 * w + 3] = byte_shl<3>(dw[w], entry_shift);
                 }
-                uint32_t cnt[P];
-                csa_planes<L>(msk, cnt);
-                planes_max<P>(mx, cnt);
-            }
-            if (m == 0) {  // empty document: the maximum over nothing is 0
+                uint32_t msk[W][L];
 #pragma unroll
-                for (int p = 0; p < P; ++p) mx[p] = 0;
-            }
-            // merge the G = 8 lanes of a document: mirror within the half row, then the two
-            // quad exchanges
-            uint32_t o[P];
-#pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[p]);  // row_half_mirror
-            planes_max<P>(mx, o);
-#pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[p]);   // quad_perm [1,0,3,2]
-            planes_max<P>(mx, o);
-#pragma unroll
-            for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[p]);   // quad_perm [2,3,0,1]
-            planes_max<P>(mx, o);
-            int32_t score = 0;
-            if constexpr (!REMAP) {
-#pragma unroll
-                for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[p]);
-            } else {
-                // similarity remap (Eq. 1 as a table of L+1 fixed-point values): every lane of the
-                // group holds the merged maxima; lane `sub` un-slices query vectors sub, sub+8,
-                // sub+16, sub+24, looks their maxima up, and the eight partial sums are added
-                // (integers, so the order does not matter)
-                uint32_t part = 0;
-#pragma unroll
-                for (int jq = 0; jq < 32 / G; ++jq) {
-                    const uint32_t q = sub + G * jq;
-                    uint32_t v = 0;
-#pragma unroll
-                    for (int p = P - 1; p >= 0; --p) v = 2 * v + ((mx[p] >> q) & 1u);
-                    part += a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
+                for (int t = 0; t < L; ++t) {
+                    if constexpr (W == 1) {
+                        msk[0][t] = *(const uint32_t*)(lut_bytes + t * STRIDE * 4 + off[t]);
+                    } else {
+                        uint2 e = *(const uint2*)(lut_bytes + t * STRIDE * 8 + off[t]);
+                        msk[0][t] = e.x;
+                        msk[1][t] = e.y;
+                    }
                 }
-                part += dpp_mov<0x141>(part);  // row_half_mirror
-                part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
-                part += dpp_mov<0x4E>(part);   // quad_perm [2,3,0,1]
-                score = (int32_t)part;
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                    uint32_t cnt[P];
+                    csa_planes<L>(msk[w], cnt);
+                    planes_max<P>(mx[w], cnt);
+                }
             }
-            if (valid && sub == 0) {
-                int32_t* dst = a.scores + sp.base + first + doc;
-                if (qc == q_lo)
-                    *dst = score;
-                else
-                    *dst += score;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                if (m == 0) {  // empty document: the maximum over nothing is 0
+#pragma unroll
+                    for (int p = 0; p < P; ++p) mx[w][p] = 0;
+                }
+                // merge the G = 8 lanes of a document: mirror within the half row, then the two
+                // quad exchanges
+                uint32_t o[P];
+#pragma unroll
+                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[w][p]);  // row_half_mirror
+                planes_max<P>(mx[w], o);
+#pragma unroll
+                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[w][p]);   // quad_perm [1,0,3,2]
+                planes_max<P>(mx[w], o);
+#pragma unroll
+                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[w][p]);   // quad_perm [2,3,0,1]
+                planes_max<P>(mx[w], o);
+                int32_t score = 0;
+                if constexpr (!REMAP) {
+#pragma unroll
+                    for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[w][p]);
+                } else {
+                    // similarity remap (Eq. 1 as a table of L+1 fixed-point values): every lane of
+                    // the group holds the merged maxima; lane `sub` un-slices query vectors sub,
+                    // sub+8, sub+16, sub+24, looks their maxima up, and the eight partial sums are
+                    // added (integers, so the order does not matter)
+                    uint32_t part = 0;
+#pragma unroll
+                    for (int jq = 0; jq < 32 / G; ++jq) {
+                        const uint32_t q = sub + G * jq;
+                        uint32_t v = 0;
+#pragma unroll
+                        for (int p = P - 1; p >= 0; --p) v = 2 * v + ((mx[w][p] >> q) & 1u);
+                        part += a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
+                    }
+                    part += dpp_mov<0x141>(part);  // row_half_mirror
+                    part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
+                    part += dpp_mov<0x4E>(part);   // quad_perm [2,3,0,1]
+                    score = (int32_t)part;
+                }
+                if (valid && sub == 0 && b0 + w < a.n_queries && c0 < q_len[w]) {
+                    // W > 1 implies every set scores every document: set b0+w starts at (b0+w)*n_docs
+                    int32_t* dst = a.scores + (W == 1 ? sp.base : (uint64_t)(b0 + w) * a.n_docs) + first + doc;
+                    if (c0 == 0)
+                        *dst = score;
+                    else
+                        *dst += score;
+                }
             }
         }
     }
@@ -359,14 +395,26 @@ bool score_masklut_supported(uint32_t L, uint32_t C) {
 
 template <int LW, int CB>
 static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
-    auto kern = a.remap ? score_masklut_kernel<LW, CB, true> : score_masklut_kernel<LW, CB, false>;
+    // two query sets per workgroup when every document is scored for every set and the paired
+    // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
+    constexpr bool PAIR_OK = (size_t)LW * 4 * (1u << CB) * 8 <= 32 * 1024;
+    const bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2;
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
     // workgroups, but at least 64 so the table build stays amortised
+    const uint32_t gy = pair ? (a.n_queries + 1) / 2 : a.n_queries;
     uint32_t dpb = LUT_DOCS;
-    while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * a.n_queries < 4096) dpb /= 2;
+    while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * gy < 4096) dpb /= 2;
     uint64_t bx = (a.max_scored + dpb - 1) / dpb;
     if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)bx, a.n_queries), dim3(256), 0, stream, a, dpb);
+    if constexpr (PAIR_OK) {
+        if (pair) {
+            auto kern2 = a.remap ? score_masklut_kernel<LW, CB, true, 2> : score_masklut_kernel<LW, CB, false, 2>;
+            hipLaunchKernelGGL(kern2, dim3((unsigned)bx, gy), dim3(256), 0, stream, a, dpb);
+            return hipGetLastError();
+        }
+    }
+    auto kern = a.remap ? score_masklut_kernel<LW, CB, true, 1> : score_masklut_kernel<LW, CB, false, 1>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)bx, gy), dim3(256), 0, stream, a, dpb);
     return hipGetLastError();
 }
 
