@@ -144,7 +144,7 @@ Workspace carve(const dessert_index* ix, uint32_t B, uint64_t total_q, uint64_t 
     w.cand_off = p; p += align_up(((size_t)B + 1) * 8, 256);
     w.scores = p;   if (own_scores) p += align_up((size_t)total_scored * 4, 256);
     w.partial = p;
-    uint32_t slices = topk_slices(max_scored);
+    uint32_t slices = topk_slices(max_scored, B);
     if (k && slices > 1) p += align_up((size_t)B * slices * k * 8, 256);
     w.total = p;
     return w;

@@ -74,7 +74,7 @@ struct TopkArgs {
     uint32_t* out_ids;          // [B][k]
     int32_t* out_scores;        // [B][k]
 };
-uint32_t topk_slices(uint64_t max_scored);
+uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 
 }  // namespace dessert

@@ -1,7 +1,6 @@
 // Stand-alone top-k kernels for gfx950 (the selection itself is in topk_select.hpp).
-// One workgroup per (query set, slice) selects the k best keys of its slice; lists of up to
-// 131072 scored documents are a single slice and give the final result directly, longer lists
-// are cut into 65536-element slices whose keys a second launch selects among.
+// One workgroup per (query set, slice) selects the k best keys of its slice; a single slice
+// gives the final result directly, otherwise a second launch selects among the slices' keys.
 #include "kernels.hpp"
 #include "topk_select.hpp"
 
@@ -10,9 +9,15 @@ namespace dessert {
 constexpr uint32_t TOPK_THREADS = 512;
 constexpr uint64_t TOPK_SLICE = 1u << 16;
 
-uint32_t topk_slices(uint64_t max_scored) {
-    if (max_scored <= 2 * TOPK_SLICE) return 1;
-    return (uint32_t)((max_scored + TOPK_SLICE - 1) / TOPK_SLICE);
+// Slices per query set: long lists are cut into 65536-element slices; shorter ones are still cut
+// (down to 8192 elements per slice) when the batch alone would leave most CUs without a workgroup.
+// Non-decreasing in max_scored, so a bound on the list length bounds the slice count.
+uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries) {
+    uint64_t by_size = max_scored <= 2 * TOPK_SLICE ? 1 : (max_scored + TOPK_SLICE - 1) / TOPK_SLICE;
+    uint64_t want = n_queries ? (1024 + n_queries - 1) / n_queries : 1;
+    uint64_t by_fill = max_scored / 8192 < want ? max_scored / 8192 : want;
+    uint64_t s = by_size > by_fill ? by_size : by_fill;
+    return (uint32_t)(s ? s : 1);
 }
 
 // grid (slices, B).  slices == 1: final results; else per-slice keys to a.partial.
@@ -60,7 +65,7 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
     uint32_t kpad = 2;
     while (kpad < a.k) kpad <<= 1;
     const KeyPlan plan = make_key_plan(a.max_score, a.n_docs ? a.n_docs - 1 : 0);
-    const uint32_t slices = topk_slices(a.max_scored);
+    const uint32_t slices = topk_slices(a.max_scored, a.n_queries);
     const size_t lds = (size_t)kpad * 8;
     hipLaunchKernelGGL(topk_scores_kernel, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices,
                        kpad);
