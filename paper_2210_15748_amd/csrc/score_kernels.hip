@@ -196,7 +196,7 @@ struct LutBlockMeta {
 // per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
 // REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
 template <int LW, int CB, bool REMAP, int W>
-__global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block) {
+__global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear) {
     constexpr int L = LW * 4;
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
@@ -207,9 +207,22 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     __shared__ __attribute__((aligned(8))) uint32_t lut[L * STRIDE * W];  // [t][h][w]
     __shared__ LutBlockMeta meta;
 
-    const uint32_t b0 = blockIdx.y * W;  // first query set of this workgroup
-    const Span sp = query_span(a, b0);   // W > 1: every set scores the same documents
-    const uint64_t first = (uint64_t)blockIdx.x * docs_per_block;
+    // Which (document block, query-set group) this workgroup takes.  When every set scores every
+    // document (gy_linear != 0) the grid is linear and decoded so that the groups of one document
+    // block run back to back on ONE XCD (workgroup ids go round-robin over the 8 XCDs): the
+    // block's codes then come from HBM once and from that XCD's L2 for the other groups.
+    uint32_t bx_idx, by_idx;
+    if (gy_linear) {
+        const uint32_t xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        by_idx = j % gy_linear;
+        bx_idx = (j / gy_linear) * 8 + xcd;
+    } else {
+        bx_idx = blockIdx.x;
+        by_idx = blockIdx.y;
+    }
+    const uint32_t b0 = by_idx * W;     // first query set of this workgroup
+    const Span sp = query_span(a, b0);  // W > 1: every set scores the same documents
+    const uint64_t first = (uint64_t)bx_idx * docs_per_block;
     if (first >= sp.count) return;
     const uint32_t ndocs = (uint32_t)((first + docs_per_block < sp.count) ? docs_per_block : sp.count - first);
     uint32_t q_lo[W], q_len[W], max_len = 0;
@@ -406,15 +419,25 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * gy < 4096) dpb /= 2;
     uint64_t bx = (a.max_scored + dpb - 1) / dpb;
     if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
+    // exhaustive mode: linear grid with the XCD-aware decode (document blocks rounded up to 8)
+    dim3 grid((unsigned)bx, gy);
+    uint32_t gy_linear = 0;
+    if (a.cand_ids == nullptr) {
+        const uint64_t total = (bx + 7) / 8 * 8 * gy;
+        if (total <= 0x7fffffffull) {
+            grid = dim3((unsigned)total);
+            gy_linear = gy;
+        }
+    }
     if constexpr (PAIR_OK) {
         if (pair) {
             auto kern2 = a.remap ? score_masklut_kernel<LW, CB, true, 2> : score_masklut_kernel<LW, CB, false, 2>;
-            hipLaunchKernelGGL(kern2, dim3((unsigned)bx, gy), dim3(256), 0, stream, a, dpb);
+            hipLaunchKernelGGL(kern2, grid, dim3(256), 0, stream, a, dpb, gy_linear);
             return hipGetLastError();
         }
     }
     auto kern = a.remap ? score_masklut_kernel<LW, CB, true, 1> : score_masklut_kernel<LW, CB, false, 1>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)bx, gy), dim3(256), 0, stream, a, dpb);
+    hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, a, dpb, gy_linear);
     return hipGetLastError();
 }
 
