@@ -229,6 +229,147 @@ void oracle_topk(const int32_t *scores, const int64_t *ids, uint64_t n, uint32_t
     free(taken);
 }
 
+/* ---- candidate filter: Sec. 5 "Filtering".
+ * The paper clusters a sample of the item vectors with k-means and keeps an inverted index
+ * from centroid ids to document ids; a document is added to the bucket of the closest centroid
+ * of each of its vectors.  At query time the buckets of the filter_probe closest centroids of
+ * every query vector are aggregated into a count per document id, and only the filter_k
+ * documents with the highest count go on to be scored.
+ * Readings taken here (the paper does not say): "closest" is the squared Euclidean distance
+ * (the k-means objective), ties go to the lower centroid id; a bucket is a set (a document
+ * appears once however many of its vectors chose the centroid); a document's count is the number
+ * of (query vector, probed centroid) pairs whose bucket holds it; the filter_k best are taken by
+ * (count descending, document id ascending) among documents with count >= 1.  The centroids
+ * themselves are an input: k-means training is not part of this oracle.
+ */
+
+/* closest centroid of every vector: assign[v] = argmin_k sum_i (x_i - c_{k,i})^2 */
+void oracle_assign_centroids(const int8_t *X, uint64_t n, uint32_t d, const int8_t *Cn, uint32_t K,
+                             int32_t *assign)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < (int64_t)n; ++v) {
+        const int8_t *x = X + (size_t)v * d;
+        int64_t best = -1;
+        int32_t best_k = -1;
+        for (uint32_t k = 0; k < K; ++k) {
+            const int8_t *c = Cn + (size_t)k * d;
+            int64_t dist = 0;
+            for (uint32_t i = 0; i < d; ++i) {
+                int64_t diff = (int64_t)x[i] - (int64_t)c[i];
+                dist += diff * diff;
+            }
+            if (best_k < 0 || dist < best) {
+                best = dist;
+                best_k = (int32_t)k;
+            }
+        }
+        assign[v] = best_k;
+    }
+}
+
+/* the filter_probe closest centroids of one vector, closest first (ties: lower id first) */
+static void closest_centroids(const int8_t *x, uint32_t d, const int8_t *Cn, uint32_t K, uint32_t probe,
+                              int32_t *out)
+{
+    uint8_t *taken = (uint8_t *)calloc(K ? K : 1, 1);
+    for (uint32_t r = 0; r < probe; ++r) {
+        int64_t best = -1;
+        int32_t best_k = -1;
+        for (uint32_t k = 0; k < K; ++k) {
+            if (taken[k])
+                continue;
+            const int8_t *c = Cn + (size_t)k * d;
+            int64_t dist = 0;
+            for (uint32_t i = 0; i < d; ++i) {
+                int64_t diff = (int64_t)x[i] - (int64_t)c[i];
+                dist += diff * diff;
+            }
+            if (best_k < 0 || dist < best) {
+                best = dist;
+                best_k = (int32_t)k;
+            }
+        }
+        out[r] = best_k;
+        if (best_k >= 0)
+            taken[best_k] = 1;
+    }
+    free(taken);
+}
+
+/* inverted index from the assignments: bucket k = sorted set of documents with a vector assigned
+ * to centroid k.  Call with bucket_docs == NULL to get only bucket_offsets [K+1] (sizes), then
+ * again with room for bucket_offsets[K] ids. */
+void oracle_inverted_index(const int32_t *assign, const int64_t *offsets, uint64_t n_docs, uint32_t K,
+                           int64_t *bucket_offsets, uint32_t *bucket_docs)
+{
+    int64_t *size = (int64_t *)calloc((size_t)K + 1, sizeof(int64_t));
+    uint8_t *seen = (uint8_t *)calloc(K ? K : 1, 1);
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+            int64_t run = 0;
+            for (uint32_t k = 0; k < K; ++k) {
+                bucket_offsets[k] = run;
+                run += size[k];
+                size[k] = 0;
+            }
+            bucket_offsets[K] = run;
+            if (!bucket_docs)
+                break;
+        }
+        for (uint64_t i = 0; i < n_docs; ++i) {           /* documents in id order: buckets come out sorted */
+            for (int64_t j = offsets[i]; j < offsets[i + 1]; ++j) {
+                int32_t k = assign[j];
+                if (seen[k])
+                    continue;
+                seen[k] = 1;
+                if (pass == 1)
+                    bucket_docs[bucket_offsets[k] + size[k]] = (uint32_t)i;
+                size[k] += 1;
+            }
+            for (int64_t j = offsets[i]; j < offsets[i + 1]; ++j)
+                seen[assign[j]] = 0;
+        }
+    }
+    free(size);
+    free(seen);
+}
+
+/* one query set through the filter: counts per document, then the filter_k best.
+ * out_ids / out_counts [filter_k]; unused slots get id 0xFFFFFFFF, count 0. */
+void oracle_filter_query(const int8_t *Q, uint32_t mq, uint32_t d, const int8_t *Cn, uint32_t K,
+                         const int64_t *bucket_offsets, const uint32_t *bucket_docs, uint64_t n_docs,
+                         uint32_t probe, uint32_t filter_k, uint32_t *out_ids, int32_t *out_counts)
+{
+    int32_t *count = (int32_t *)calloc(n_docs ? n_docs : 1, sizeof(int32_t));
+    int32_t *near = (int32_t *)malloc((probe ? probe : 1) * sizeof(int32_t));
+    for (uint32_t q = 0; q < mq; ++q) {
+        closest_centroids(Q + (size_t)q * d, d, Cn, K, probe, near);
+        for (uint32_t r = 0; r < probe; ++r) {
+            if (near[r] < 0)
+                continue;
+            for (int64_t e = bucket_offsets[near[r]]; e < bucket_offsets[near[r] + 1]; ++e)
+                count[bucket_docs[e]] += 1;
+        }
+    }
+    for (uint32_t r = 0; r < filter_k; ++r) {             /* plain selection, best remaining first */
+        int64_t best = -1;
+        for (uint64_t i = 0; i < n_docs; ++i)
+            if (count[i] > 0 && (best < 0 || count[i] > count[best]))
+                best = (int64_t)i;                          /* strict '>' keeps the lower id on ties */
+        if (best < 0) {
+            out_ids[r] = 0xFFFFFFFFu;
+            out_counts[r] = 0;
+        } else {
+            out_ids[r] = (uint32_t)best;
+            out_counts[r] = count[best];
+            count[best] = -count[best];                     /* taken */
+        }
+    }
+    free(count);
+    free(near);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -108,6 +108,45 @@ def scores_eq1(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, 
     return (out, table) if want_table else out
 
 
+def assign_centroids(X: np.ndarray, centroids: np.ndarray) -> np.ndarray:
+    X = np.ascontiguousarray(X, dtype=np.int8)
+    centroids = np.ascontiguousarray(centroids, dtype=np.int8)
+    assert X.shape[1] == centroids.shape[1]
+    out = np.empty(X.shape[0], dtype=np.int32)
+    lib().oracle_assign_centroids(_p(X), C.c_uint64(X.shape[0]), C.c_uint32(X.shape[1]), _p(centroids),
+                                  C.c_uint32(centroids.shape[0]), _p(out))
+    return out
+
+
+def inverted_index(assign: np.ndarray, offsets: np.ndarray, K: int):
+    """(bucket_offsets [K+1] int64, bucket_docs uint32): sorted set of documents per centroid."""
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    assert assign.shape[0] >= offsets[-1] and (assign.size == 0 or (assign.min() >= 0 and assign.max() < K))
+    n_docs = offsets.shape[0] - 1
+    bo = np.empty(K + 1, dtype=np.int64)
+    lib().oracle_inverted_index(_p(assign), _p(offsets), C.c_uint64(n_docs), C.c_uint32(K), _p(bo), None)
+    docs = np.empty(int(bo[-1]), dtype=np.uint32)
+    lib().oracle_inverted_index(_p(assign), _p(offsets), C.c_uint64(n_docs), C.c_uint32(K), _p(bo), _p(docs))
+    return bo, docs
+
+
+def filter_query(Q: np.ndarray, centroids: np.ndarray, bucket_offsets: np.ndarray, bucket_docs: np.ndarray,
+                 n_docs: int, probe: int, filter_k: int):
+    """One query set: (ids [filter_k] uint32, counts [filter_k] int32), padded with 0xFFFFFFFF / 0."""
+    Q = np.ascontiguousarray(Q, dtype=np.int8)
+    centroids = np.ascontiguousarray(centroids, dtype=np.int8)
+    bo = np.ascontiguousarray(bucket_offsets, dtype=np.int64)
+    bd = np.ascontiguousarray(bucket_docs, dtype=np.uint32)
+    assert bo.shape[0] == centroids.shape[0] + 1 and probe <= centroids.shape[0]
+    ids = np.empty(filter_k, dtype=np.uint32)
+    cnt = np.empty(filter_k, dtype=np.int32)
+    lib().oracle_filter_query(_p(Q), C.c_uint32(Q.shape[0]), C.c_uint32(Q.shape[1]), _p(centroids),
+                              C.c_uint32(centroids.shape[0]), _p(bo), _p(bd), C.c_uint64(n_docs), C.c_uint32(probe),
+                              C.c_uint32(filter_k), _p(ids), _p(cnt))
+    return ids, cnt
+
+
 def topk(score: np.ndarray, k: int, ids=None):
     score = np.ascontiguousarray(score, dtype=np.int32)
     ids_a = None if ids is None else np.ascontiguousarray(ids, dtype=np.int64)
