@@ -37,8 +37,10 @@
  *     than k documents were scored the remaining slots hold id 0xFFFFFFFF and
  *     score -1.  Candidate ids are scored as given (duplicates appear twice).
  *   - Limits: 1 <= C <= 8, L a multiple of 4 with 4 <= L <= 128, d >= 1,
- *     (total query vectors of one set) * L <= 65535, k <= 4096.  Candidate
- *     ids must be < n_docs (not checked on the device).
+ *     (total query vectors of one set) * L <= 65535, k <= 16384.  Candidate
+ *     ids must be < n_docs (not checked on the device), except the value
+ *     0xFFFFFFFF, which marks an empty candidate slot: it is scored -1 and is
+ *     never returned by the top-k.
  */
 #ifndef DESSERT_H
 #define DESSERT_H
@@ -163,6 +165,38 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
                                 const uint32_t *q_lengths_host, uint32_t n_queries,
                                 const uint32_t *cand_ids_dev, const uint64_t *cand_offsets_host,
                                 void *workspace_dev, size_t workspace_bytes, int32_t *out_scores_dev);
+
+/* Candidate filter (Sec. 5 "Filtering"): an inverted index from centroid ids to document ids and the
+ * query-side selection of the documents to score.  The centroids are an input (the paper obtains them
+ * by k-means on a sample of the vectors; any centroid set works).  "Closest" is the squared Euclidean
+ * distance, ties to the lower centroid id.  Needs int8 vectors with d in {64, 128, 256} and a built
+ * index (dessert_build_index) over the same vectors_dev.
+ *
+ * dessert_filter_build: for every document vector the closest centroid, then bucket c = the set of
+ * documents with at least one vector assigned to c.
+ *   centroids_dev       dev, [n_centroids][d] int8 (copied in re-ordered form; may be freed afterwards)
+ *   assign_dev          dev, out, [n_vectors] u32: closest centroid of every vector
+ *   bucket_offsets_dev  dev, out, [n_centroids+1] u32: bucket c = bucket_docs[offsets[c] .. offsets[c+1])
+ *   bucket_docs_dev     dev, out, room for n_vectors u32 (upper bound of the total bucket size); a
+ *                       document appears once per bucket, in unspecified order inside the bucket
+ * The two bucket arrays must stay alive while dessert_filter_query is used.
+ *
+ * dessert_filter_query: for each query vector the filter_probe closest centroids; every document gets
+ * one count per (query vector, probed centroid) pair whose bucket holds it; per query set the
+ * filter_k documents with the highest count (ties: lower id), among documents with count >= 1.
+ *   out_ids_dev     dev, out, [n_queries][filter_k] u32, unused slots 0xFFFFFFFF: can be passed to
+ *                   dessert_search as candidate lists of equal length filter_k
+ *   out_counts_dev  dev, out, [n_queries][filter_k] i32, unused slots -1
+ * Limits: n_centroids <= 2^20, filter_probe <= min(n_centroids, 1024), filter_k <= 16384. */
+dessert_status_t dessert_filter_build(dessert_index_t *index, const int8_t *centroids_dev, uint32_t n_centroids,
+                                      const void *vectors_dev, uint32_t *assign_dev, uint32_t *bucket_offsets_dev,
+                                      uint32_t *bucket_docs_dev);
+size_t dessert_filter_workspace_bytes(const dessert_index_t *index, uint32_t n_queries, uint64_t total_q_vectors,
+                                      uint32_t filter_probe, uint32_t filter_k);
+dessert_status_t dessert_filter_query(const dessert_index_t *index, const void *q_vectors_dev,
+                                      const uint32_t *q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
+                                      uint32_t filter_k, void *workspace_dev, size_t workspace_bytes,
+                                      uint32_t *out_ids_dev, int32_t *out_counts_dev);
 
 /* Per-kernel timing of dessert_search / dessert_scores / dessert_build_index
  * calls on this handle, measured with HIP events recorded on config.stream

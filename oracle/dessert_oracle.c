@@ -336,7 +336,7 @@ void oracle_inverted_index(const int32_t *assign, const int64_t *offsets, uint64
 }
 
 /* one query set through the filter: counts per document, then the filter_k best.
- * out_ids / out_counts [filter_k]; unused slots get id 0xFFFFFFFF, count 0. */
+ * out_ids / out_counts [filter_k]; unused slots get id 0xFFFFFFFF, count -1 (the padding of oracle_topk). */
 void oracle_filter_query(const int8_t *Q, uint32_t mq, uint32_t d, const int8_t *Cn, uint32_t K,
                          const int64_t *bucket_offsets, const uint32_t *bucket_docs, uint64_t n_docs,
                          uint32_t probe, uint32_t filter_k, uint32_t *out_ids, int32_t *out_counts)
@@ -359,7 +359,7 @@ void oracle_filter_query(const int8_t *Q, uint32_t mq, uint32_t d, const int8_t 
                 best = (int64_t)i;                          /* strict '>' keeps the lower id on ties */
         if (best < 0) {
             out_ids[r] = 0xFFFFFFFFu;
-            out_counts[r] = 0;
+            out_counts[r] = -1;
         } else {
             out_ids[r] = (uint32_t)best;
             out_counts[r] = count[best];

@@ -133,7 +133,7 @@ def inverted_index(assign: np.ndarray, offsets: np.ndarray, K: int):
 
 def filter_query(Q: np.ndarray, centroids: np.ndarray, bucket_offsets: np.ndarray, bucket_docs: np.ndarray,
                  n_docs: int, probe: int, filter_k: int):
-    """One query set: (ids [filter_k] uint32, counts [filter_k] int32), padded with 0xFFFFFFFF / 0."""
+    """One query set: (ids [filter_k] uint32, counts [filter_k] int32), padded with 0xFFFFFFFF / -1."""
     Q = np.ascontiguousarray(Q, dtype=np.int8)
     centroids = np.ascontiguousarray(centroids, dtype=np.int8)
     bo = np.ascontiguousarray(bucket_offsets, dtype=np.int64)

@@ -34,6 +34,7 @@ EXPORTS = [
     "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_set_score_transform",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
+    "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
     "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
     "dessert_version",
 ]
@@ -78,6 +79,10 @@ def lib() -> C.CDLL:
     l.dessert_search_workspace_bytes.restype = sz
     l.dessert_search.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, sz, vp, vp]
     l.dessert_scores.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
+    l.dessert_filter_build.argtypes = [vp, vp, u32, vp, vp, vp, vp]
+    l.dessert_filter_workspace_bytes.argtypes = [vp, u32, u64, u32, u32]
+    l.dessert_filter_workspace_bytes.restype = sz
+    l.dessert_filter_query.argtypes = [vp, vp, vp, u32, u32, u32, vp, sz, vp, vp]
     l.dessert_enable_timing.argtypes = [vp, C.c_int]
     l.dessert_get_timing.argtypes = [vp, u32, C.POINTER(C.c_float)]
     l.dessert_probe_read_bandwidth.argtypes = [vp, sz, C.c_int, vp, C.c_int, C.POINTER(C.c_float)]
@@ -263,6 +268,41 @@ def scores(ix: Index, q_vectors: torch.Tensor, q_lengths, cand_ids: Optional[tor
                                 None if co is None else co.ctypes.data, workspace.data_ptr(), workspace.numel(),
                                 out.data_ptr()))
     return out if co is not None else out.view(B, ix.n_docs)
+
+
+def filter_build(ix: Index, centroids: torch.Tensor, vectors: torch.Tensor):
+    """dessert_filter_build.  Returns (assign [V] int32, bucket_offsets [K+1] int32, bucket_docs [V] int32);
+    only bucket_docs[: bucket_offsets[-1]] is meaningful."""
+    vectors = _check_vectors(ix, vectors)
+    if not centroids.is_cuda or centroids.dtype != torch.int8 or centroids.dim() != 2 or centroids.shape[1] != ix.cfg.d:
+        raise ValueError("centroids must be a device int8 tensor [K, d]")
+    centroids = centroids.contiguous()
+    K, V = centroids.shape[0], vectors.shape[0]
+    assign = torch.empty(V, dtype=torch.int32, device=ix.device)
+    bucket_offsets = torch.empty(K + 1, dtype=torch.int32, device=ix.device)
+    bucket_docs = torch.empty(max(V, 1), dtype=torch.int32, device=ix.device)
+    _check(lib().dessert_filter_build(ix.handle, centroids.data_ptr(), K, vectors.data_ptr(), assign.data_ptr(),
+                                      bucket_offsets.data_ptr(), bucket_docs.data_ptr()))
+    ix._keep = [bucket_offsets, bucket_docs]
+    return assign, bucket_offsets, bucket_docs
+
+
+def filter_query(ix: Index, q_vectors: torch.Tensor, q_lengths, filter_probe: int, filter_k: int,
+                 workspace: Optional[torch.Tensor] = None):
+    """dessert_filter_query.  Returns (ids [B, filter_k] uint32 with 0xFFFFFFFF padding, counts [B, filter_k] int32)."""
+    q_vectors = _check_vectors(ix, q_vectors)
+    ql = _host_u32(q_lengths)
+    B = ql.shape[0]
+    if int(ql.sum()) != q_vectors.shape[0]:
+        raise ValueError("sum(q_lengths) != number of query vectors")
+    if workspace is None:
+        nbytes = int(lib().dessert_filter_workspace_bytes(ix.handle, B, q_vectors.shape[0], filter_probe, filter_k))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=ix.device)
+    ids = torch.empty(B, filter_k, dtype=torch.uint32, device=ix.device)
+    counts = torch.empty(B, filter_k, dtype=torch.int32, device=ix.device)
+    _check(lib().dessert_filter_query(ix.handle, q_vectors.data_ptr(), ql.ctypes.data, B, filter_probe, filter_k,
+                                      workspace.data_ptr(), workspace.numel(), ids.data_ptr(), counts.data_ptr()))
+    return ids, counts
 
 
 def enable_timing(ix: Index, enable: bool = True) -> None:

@@ -7,7 +7,7 @@ import subprocess
 HERE = pathlib.Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libdessert_hip.so"
-SOURCES = ["api.hip", "hash_kernels.hip", "score_kernels.hip", "topk_kernels.hip"]
+SOURCES = ["api.hip", "hash_kernels.hip", "score_kernels.hip", "topk_kernels.hip", "filter_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA accumulators in ordinary VGPRs: the sign packing reads them with VALU ops, which

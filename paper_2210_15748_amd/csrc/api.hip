@@ -56,6 +56,14 @@ struct dessert_index {
     void* proj = nullptr;       // device, [L*C][d] int8 or float (library-owned copy)
     void* proj_mfma = nullptr;  // device, MFMA-ordered int8 copy (or null)
     uint32_t* remap = nullptr;  // device, [L+1] Eq. 1 table in Q16 (library-owned)
+    // candidate filter (library-owned: MFMA-ordered centroids, key constants, bucket cursors)
+    void* f_cent = nullptr;
+    void* f_table = nullptr;
+    uint32_t* f_cursor = nullptr;
+    uint32_t f_K = 0;
+    const uint32_t* f_bucket_off = nullptr;   // caller's
+    const uint32_t* f_bucket_docs = nullptr;  // caller's
+    bool f_built = false;
     int transform = DESSERT_SCORE_RAW_COUNTS;
     int hash_algo = DESSERT_HASH_AUTO;
     int score_algo = DESSERT_SCORE_AUTO;
@@ -387,6 +395,9 @@ void dessert_destroy(dessert_index_t* ix) {
     if (ix->proj) (void)hipFree(ix->proj);
     if (ix->proj_mfma) (void)hipFree(ix->proj_mfma);
     if (ix->remap) (void)hipFree(ix->remap);
+    if (ix->f_cent) (void)hipFree(ix->f_cent);
+    if (ix->f_table) (void)hipFree(ix->f_table);
+    if (ix->f_cursor) (void)hipFree(ix->f_cursor);
     if (ix->h_offsets) (void)hipHostFree(ix->h_offsets);
     for (auto& slot : ix->slots)
         for (auto& ev : slot.ev)
@@ -514,7 +525,7 @@ dessert_status_t dessert_search(const dessert_index_t* ix, const void* q_vectors
                                 uint32_t n_queries, const uint32_t* cand_ids_dev, const uint64_t* cand_offsets_host,
                                 uint32_t k, void* workspace_dev, size_t workspace_bytes, uint32_t* out_ids_dev,
                                 int32_t* out_scores_dev) {
-    if (k == 0 || k > 4096) return fail(DESSERT_EINVAL, "k must be in 1..4096, got %u", k);
+    if (k == 0 || k > 16384) return fail(DESSERT_EINVAL, "k must be in 1..16384, got %u", k);
     if (n_queries && (!out_ids_dev || !out_scores_dev)) return fail(DESSERT_EINVAL, "output pointer is NULL");
     return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
                        cand_offsets_host, k, workspace_dev, workspace_bytes, nullptr, out_ids_dev, out_scores_dev);
@@ -526,6 +537,122 @@ dessert_status_t dessert_scores(const dessert_index_t* ix, const void* q_vectors
     if (n_queries && !out_scores_dev) return fail(DESSERT_EINVAL, "out_scores_dev is NULL");
     return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
                        cand_offsets_host, 0, workspace_dev, workspace_bytes, out_scores_dev, nullptr, nullptr);
+}
+
+dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroids_dev, uint32_t n_centroids,
+                                      const void* vectors_dev, uint32_t* assign_dev, uint32_t* bucket_offsets_dev,
+                                      uint32_t* bucket_docs_dev) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!ix->built) return fail(DESSERT_ESTATE, "dessert_build_index has not been called");
+    if (ix->cfg.dtype != DESSERT_I8 || !filter_supported(ix->cfg.d))
+        return fail(DESSERT_EINVAL, "the candidate filter needs int8 vectors with d in {64,128,256}");
+    if (!centroids_dev || !assign_dev || !bucket_offsets_dev || !bucket_docs_dev || (ix->n_vectors && !vectors_dev))
+        return fail(DESSERT_EINVAL, "NULL argument");
+    if (n_centroids == 0 || n_centroids > (1u << 20)) return fail(DESSERT_EINVAL, "n_centroids must be in 1..2^20");
+    if (ix->n_vectors > 0xFFFFFFFFull) return fail(DESSERT_EINVAL, "more than 2^32-1 vectors");
+    if ((uintptr_t)vectors_dev % 16) return fail(DESSERT_EINVAL, "vectors_dev must be 16-byte aligned");
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    ix->f_built = false;
+    HIP_TRY(hipStreamSynchronize(ix->stream));  // earlier filter work may still read the buffers freed below
+    if (ix->f_cent) (void)hipFree(ix->f_cent);
+    if (ix->f_table) (void)hipFree(ix->f_table);
+    if (ix->f_cursor) (void)hipFree(ix->f_cursor);
+    ix->f_cent = ix->f_table = nullptr;
+    ix->f_cursor = nullptr;
+    hipError_t e = hipMalloc(&ix->f_cent, filter_centroid_bytes(n_centroids, ix->cfg.d));
+    if (e == hipSuccess) e = hipMalloc(&ix->f_table, filter_table_bytes(n_centroids));
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_cursor, (size_t)n_centroids * 4);
+    if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipMalloc(filter state): %s", hipGetErrorString(e));
+    HIP_TRY(launch_filter_prep(centroids_dev, n_centroids, ix->cfg.d, ix->f_cent, ix->f_table, ix->stream));
+    HIP_TRY(launch_filter_assign((const int8_t*)vectors_dev, ix->n_vectors, ix->cfg.d, n_centroids, ix->f_cent,
+                                 ix->f_table, assign_dev, ix->stream));
+    HIP_TRY(launch_filter_buckets(assign_dev, ix->offsets, ix->n_docs, n_centroids, ix->f_cursor, bucket_offsets_dev,
+                                  bucket_docs_dev, ix->stream));
+    ix->f_K = n_centroids;
+    ix->f_bucket_off = bucket_offsets_dev;
+    ix->f_bucket_docs = bucket_docs_dev;
+    ix->f_built = true;
+    return DESSERT_OK;
+}
+
+namespace {
+struct FilterWorkspace {
+    size_t dist, probe_ids, q_off, counts, partial, total;
+};
+FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total_q, uint32_t probe, uint32_t filter_k) {
+    FilterWorkspace w{};
+    size_t p = 0;
+    w.dist = p;      p += align_up((size_t)total_q * filter_tiles(ix->f_K) * 32 * 4, 256);
+    w.probe_ids = p; p += align_up((size_t)total_q * probe * 4, 256);
+    w.q_off = p;     p += align_up(((size_t)B + 1) * 4, 256);
+    w.counts = p;    p += align_up((size_t)B * ix->n_docs * 4, 256);
+    w.partial = p;
+    uint32_t slices = topk_slices(ix->n_docs, B);
+    if (slices > 1) p += align_up((size_t)B * slices * filter_k * 8, 256);
+    w.total = p;
+    return w;
+}
+}  // namespace
+
+size_t dessert_filter_workspace_bytes(const dessert_index_t* ix, uint32_t n_queries, uint64_t total_q_vectors,
+                                      uint32_t filter_probe, uint32_t filter_k) {
+    if (!ix || !ix->f_built) return 0;
+    return carve_filter(ix, n_queries, total_q_vectors, filter_probe, filter_k).total;
+}
+
+dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_vectors_dev,
+                                      const uint32_t* q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
+                                      uint32_t filter_k, void* workspace_dev, size_t workspace_bytes,
+                                      uint32_t* out_ids_dev, int32_t* out_counts_dev) {
+    dessert_index* ix = const_cast<dessert_index*>(cix);
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!ix->f_built) return fail(DESSERT_ESTATE, "dessert_filter_build has not been called");
+    if (n_queries == 0) return DESSERT_OK;
+    if (n_queries > 65535) return fail(DESSERT_EINVAL, "n_queries > 65535");
+    if (!q_vectors_dev || !q_lengths_host || !workspace_dev || !out_ids_dev || !out_counts_dev)
+        return fail(DESSERT_EINVAL, "NULL argument");
+    if (filter_probe == 0 || filter_probe > ix->f_K || filter_probe > 1024)
+        return fail(DESSERT_EINVAL, "filter_probe must be in 1..min(n_centroids, 1024), got %u", filter_probe);
+    if (filter_k == 0 || filter_k > 16384) return fail(DESSERT_EINVAL, "filter_k must be in 1..16384, got %u", filter_k);
+    if ((uintptr_t)workspace_dev % 256 || (uintptr_t)q_vectors_dev % 16)
+        return fail(DESSERT_EINVAL, "workspace_dev must be 256-byte and q_vectors_dev 16-byte aligned");
+    std::vector<uint32_t> q_off(n_queries + 1, 0);
+    uint32_t q_uniform = q_lengths_host[0], max_q = 0;
+    for (uint32_t b = 0; b < n_queries; ++b) {
+        if (q_lengths_host[b] == 0) return fail(DESSERT_EINVAL, "q_lengths_host[%u] = 0", b);
+        uint64_t nxt = (uint64_t)q_off[b] + q_lengths_host[b];
+        if (nxt > 0x7FFFFFFFull) return fail(DESSERT_EINVAL, "too many query vectors");
+        q_off[b + 1] = (uint32_t)nxt;
+        if (q_lengths_host[b] != q_uniform) q_uniform = 0;
+        if (q_lengths_host[b] > max_q) max_q = q_lengths_host[b];
+    }
+    const uint64_t total_q = q_off[n_queries];
+    if ((uint64_t)max_q * filter_probe > 0x7FFFFFFEull) return fail(DESSERT_EINVAL, "count range too large");
+    FilterWorkspace w = carve_filter(ix, n_queries, total_q, filter_probe, filter_k);
+    if (workspace_bytes < w.total)
+        return fail(DESSERT_EINVAL, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, w.total);
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    char* ws = (char*)workspace_dev;
+    int32_t* dist = (int32_t*)(ws + w.dist);
+    uint32_t* probe_ids = (uint32_t*)(ws + w.probe_ids);
+    uint32_t* d_q_off = (uint32_t*)(ws + w.q_off);
+    int32_t* counts = (int32_t*)(ws + w.counts);
+    if (!q_uniform)  // pageable source: the runtime stages it before returning
+        HIP_TRY(hipMemcpyAsync(d_q_off, q_off.data(), ((size_t)n_queries + 1) * 4, hipMemcpyHostToDevice, ix->stream));
+    HIP_TRY(launch_filter_distances((const int8_t*)q_vectors_dev, total_q, ix->cfg.d, ix->f_K, ix->f_cent, ix->f_table,
+                                    dist, ix->stream));
+    HIP_TRY(launch_filter_probe(dist, total_q, ix->f_K, filter_probe, probe_ids, ix->stream));
+    HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, d_q_off, q_uniform, n_queries, ix->f_bucket_off,
+                                ix->f_bucket_docs, ix->n_docs, counts, ix->stream));
+    TopkArgs ta{};
+    ta.scores = counts; ta.cand_ids = nullptr; ta.cand_off = nullptr; ta.cand_uniform = 0; ta.n_docs = ix->n_docs;
+    ta.n_queries = n_queries; ta.max_scored = ix->n_docs; ta.k = filter_k; ta.max_score = max_q * filter_probe;
+    ta.min_score = 1;  // documents no probed bucket holds are not candidates
+    ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids_dev; ta.out_scores = out_counts_dev;
+    HIP_TRY(launch_topk(ta, ix->stream));
+    return DESSERT_OK;
 }
 
 dessert_status_t dessert_enable_timing(dessert_index_t* ix, int enable) {

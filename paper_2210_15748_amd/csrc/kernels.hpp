@@ -59,6 +59,25 @@ hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
 bool score_masklut_supported(uint32_t L, uint32_t C);
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
 
+// ---- candidate filter (Sec. 5 "Filtering") ---------------------------------------------
+bool filter_supported(uint32_t d);
+uint32_t filter_tiles(uint32_t K);
+size_t filter_centroid_bytes(uint32_t K, uint32_t d);   // MFMA-ordered centroids
+size_t filter_table_bytes(uint32_t K);                  // per-row key constants
+hipError_t launch_filter_prep(const int8_t* Cn, uint32_t K, uint32_t d, void* Cp, void* T2, hipStream_t stream);
+hipError_t launch_filter_assign(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
+                                uint32_t* assign, hipStream_t stream);
+hipError_t launch_filter_distances(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
+                                   int32_t* out /*[n][filter_tiles(K)*32]*/, hipStream_t stream);
+hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off, uint64_t n_docs, uint32_t K,
+                                 uint32_t* cursor /*[K] scratch*/, uint32_t* bucket_off /*[K+1]*/, uint32_t* bucket_docs,
+                                 hipStream_t stream);
+hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K, uint32_t probe, uint32_t* probe_ids,
+                               hipStream_t stream);
+hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, const uint32_t* q_off,
+                               uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
+                               const uint32_t* bucket_docs, uint64_t n_docs, int32_t* counts, hipStream_t stream);
+
 // ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
 struct TopkArgs {
     const int32_t* scores;      // as written by the scoring kernels
@@ -70,6 +89,7 @@ struct TopkArgs {
     uint64_t max_scored;
     uint32_t k;
     uint32_t max_score;         // largest possible score (longest query set * L)
+    int32_t min_score;          // results scoring below this are replaced by padding (0: keep everything)
     uint64_t* partial;          // workspace for the two-level path: [B][slices][k] keys
     uint32_t* out_ids;          // [B][k]
     int32_t* out_scores;        // [B][k]

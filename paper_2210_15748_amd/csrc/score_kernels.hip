@@ -46,6 +46,10 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (uint64_t pos = (uint64_t)blockIdx.x * 4 + wave; pos < sp.count; pos += (uint64_t)gridDim.x * 4) {
         const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+        if (a.cand_ids && id == 0xFFFFFFFFull) {  // empty candidate slot
+            if (lane == 0) a.scores[sp.base + pos] = -1;
+            continue;
+        }
         const uint64_t lo = a.offsets[id], hi = a.offsets[id + 1];
         int32_t score = 0;
         for (uint32_t q = 0; q < mq; ++q) {
@@ -244,8 +248,11 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     if (threadIdx.x < ndocs) {
         const uint64_t pos = first + threadIdx.x;
         const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
-        const uint64_t lo = a.offsets[id];
-        const uint32_t m = (uint32_t)(a.offsets[id + 1] - lo);
+        // an empty candidate slot (id 0xFFFFFFFF) is kept as a zero-length document whose stored
+        // start is all ones; it is written as score -1 below
+        const bool empty_slot = a.cand_ids && id == 0xFFFFFFFFull;
+        const uint64_t lo = empty_slot ? ~0ull : a.offsets[id];
+        const uint32_t m = empty_slot ? 0u : (uint32_t)(a.offsets[id + 1] - lo);
         meta.lo[threadIdx.x] = lo;
         meta.m[threadIdx.x] = m;
         uint32_t rounds = (m + G - 1) / G;
@@ -392,7 +399,9 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
                 if (valid && sub == 0 && b0 + w < a.n_queries && c0 < q_len[w]) {
                     // W > 1 implies every set scores every document: set b0+w starts at (b0+w)*n_docs
                     int32_t* dst = a.scores + (W == 1 ? sp.base : (uint64_t)(b0 + w) * a.n_docs) + first + doc;
-                    if (c0 == 0)
+                    if (W == 1 && m == 0 && meta.lo[doc] == ~0ull)
+                        *dst = -1;  // empty candidate slot
+                    else if (c0 == 0)
                         *dst = score;
                     else
                         *dst += score;

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, K
     block_select<TOPK_THREADS>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
     if (slices == 1) {
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
-            write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
+            write_result(sorted[i], plan.id_bits, a.min_score, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
     } else {
         uint64_t* dst = a.partial + ((size_t)b * slices + s) * a.k;
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS) dst[i] = sorted[i];
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_merge_kernel(TopkArgs a, Ke
     StoredKeys keys{a.partial + (size_t)b * slices * a.k};
     block_select<TOPK_THREADS>(keys, (uint64_t)slices * a.k, a.k, kpad, sorted, sh, plan);
     for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
-        write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
+        write_result(sorted[i], plan.id_bits, a.min_score, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
 }
 
 hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
@@ -67,6 +67,14 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
     const KeyPlan plan = make_key_plan(a.max_score, a.n_docs ? a.n_docs - 1 : 0);
     const uint32_t slices = topk_slices(a.max_scored, a.n_queries);
     const size_t lds = (size_t)kpad * 8;
+    if (lds > 48 * 1024) {  // large k: opt in to more dynamic LDS (the selection state is another 8.3 KB)
+        static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+        static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+        if (a1 != hipSuccess) return a1;
+        if (a2 != hipSuccess) return a2;
+    }
     hipLaunchKernelGGL(topk_scores_kernel, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices,
                        kpad);
     hipError_t e = hipGetLastError();

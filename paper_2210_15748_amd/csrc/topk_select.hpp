@@ -16,7 +16,7 @@
 
 namespace dessert {
 
-constexpr uint32_t TOPK_KMAX = 4096;
+constexpr uint32_t TOPK_KMAX = 16384;
 constexpr uint32_t TOPK_DIGIT_BITS = 11;
 constexpr uint32_t TOPK_HIST = 1u << TOPK_DIGIT_BITS;
 
@@ -51,12 +51,13 @@ inline KeyPlan make_key_plan(uint32_t max_score, uint64_t max_id) {
 }
 
 __device__ inline uint64_t make_key(int32_t score, uint32_t id, uint32_t id_bits) {
+    if (score < 0) return 0;  // an empty candidate slot (scored -1) is padding
     const uint64_t idmask = (1ull << id_bits) - 1;
     return ((uint64_t)(uint32_t)(score + 1) << id_bits) | (idmask - (uint64_t)id);
 }
 
-__device__ inline void write_result(uint64_t key, uint32_t id_bits, uint32_t* id, int32_t* score) {
-    if (key == 0) {
+__device__ inline void write_result(uint64_t key, uint32_t id_bits, int32_t min_score, uint32_t* id, int32_t* score) {
+    if (key == 0 || (int32_t)(key >> id_bits) - 1 < min_score) {
         *id = 0xFFFFFFFFu;
         *score = -1;
     } else {

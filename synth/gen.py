@@ -234,3 +234,22 @@ def make(cfg: int, device="cpu", n_docs: Optional[int] = None, n_queries: Option
 
     proj = draw_projection(p, _seed(p, SEED_PROJ, seed_base), device)
     return Workload(p, docs, lengths, offsets, queries, q_lengths, planted, cand_ids, proj)
+
+
+def filter_centroids(w: Workload, n_centroids: Optional[int] = None, seed_base: Optional[int] = None) -> torch.Tensor:
+    """Centroids for the candidate filter (int8 [K, d], on the documents' device).
+
+    Stand-in for k-means on a sample of the vectors: with K equal to the number of mixture
+    centres the quantised centres themselves (what k-means would converge to on this data),
+    otherwise K document vectors drawn without replacement."""
+    p = w.preset
+    if p.dtype != "i8":
+        raise ValueError("filter centroids are generated for int8 presets only")
+    K = p.n_centres if n_centroids is None else int(n_centroids)
+    device = w.docs.device
+    if K == p.n_centres:
+        centres = draw_centres(p, _seed(p, SEED_CENTRES, seed_base), device)
+        return quantize(_normalize(centres), "i8")
+    g = _gen(_seed(p, SEED_CENTRES, seed_base) + 104729, "cpu")
+    pick = torch.randperm(w.n_vectors, generator=g)[:K]
+    return w.docs[pick.to(device)].clone()

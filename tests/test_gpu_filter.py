@@ -1,0 +1,125 @@
+"""GPU parity of the candidate filter (Sec. 5 "Filtering") against the oracle: closest-centroid assignment,
+buckets (as sets: the order inside a bucket is unspecified), probe-and-count selection, and the chain
+filter -> scoring with empty candidate slots -> top-k."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2210_15748_amd as dz
+from oracle import oracle as orc
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case]", msg, flush=True)
+    sys.stdout.flush()
+
+
+def setup(rng, d, K, n_docs, max_len, L=32, Cb=7, dup_centroids=False):
+    lens = rng.integers(0, max_len, n_docs)
+    lens[0] = max(lens[0], 1)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    pool = rng.integers(-100, 101, (K, d))
+    Cn = np.clip(pool + rng.integers(-4, 5, (K, d)), -127, 127).astype(np.int8)
+    if dup_centroids:
+        Cn[K // 2] = Cn[0]
+        Cn[K - 1] = Cn[1]
+    X = np.clip(pool[rng.integers(0, K, off[-1])] + rng.integers(-50, 51, (off[-1], d)), -127, 127).astype(np.int8)
+    X[0] = 0
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    return ix, X, Cn, R, off, lens
+
+
+def buckets_as_sets(bo, bd):
+    return [sorted(bd[bo[k]:bo[k + 1]].tolist()) for k in range(len(bo) - 1)]
+
+
+@pytest.mark.parametrize("d,K,n_docs,dup", [(128, 1000, 900, False), (64, 37, 300, True), (256, 513, 400, True),
+                                            (128, 32, 50, False), (128, 5, 2000, True)])
+def test_filter_build_assignments_and_buckets(d, K, n_docs, dup):
+    say(f"filter build d={d} K={K} N={n_docs} dup={dup}")
+    rng = np.random.default_rng(d + K)
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, 40, dup_centroids=dup)
+    assign, bo, bd = dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
+    want = orc.assign_centroids(X, Cn)
+    assert np.array_equal(assign.cpu().numpy(), want)
+    obo, obd = orc.inverted_index(want, off, K)
+    bo, bd = bo.cpu().numpy().astype(np.int64), bd.cpu().numpy().astype(np.uint32)
+    assert np.array_equal(bo, obo)
+    assert buckets_as_sets(bo, bd) == buckets_as_sets(obo, obd)
+
+
+@pytest.mark.parametrize("probe,filter_k,q_lens", [(1, 64, [32, 32, 32]), (2, 300, [5, 40, 1]), (4, 16, [32]),
+                                                   (8, 4096, [12, 7]), (37, 50, [3, 3])])
+def test_filter_query_matches_oracle(probe, filter_k, q_lens):
+    say(f"filter query probe={probe} filter_k={filter_k} q_lens={q_lens}")
+    rng = np.random.default_rng(100 + probe)
+    d, K, n_docs = 128, 37, 1500
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, 12, dup_centroids=True)
+    dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
+    nq = int(sum(q_lens))
+    Q = np.clip(Cn[rng.integers(0, K, nq)].astype(np.int64) + rng.integers(-60, 61, (nq, d)), -127, 127).astype(np.int8)
+    ids, cnt = dz.filter_query(ix, torch.from_numpy(Q).to(DEV), q_lens, probe, filter_k)
+    ids, cnt = ids.cpu().numpy(), cnt.cpu().numpy()
+    obo, obd = orc.inverted_index(orc.assign_centroids(X, Cn), off, K)
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    for b in range(len(q_lens)):
+        want_ids, want_cnt = orc.filter_query(Q[qo[b]:qo[b + 1]], Cn, obo, obd, n_docs, probe, filter_k)
+        assert np.array_equal(cnt[b], want_cnt), b
+        assert np.array_equal(ids[b], want_ids), b
+
+
+def test_filter_then_search_chain_with_empty_slots():
+    say("filter -> search chain, cfg3-like reduced")
+    w = gen.make(3, n_docs=20000, n_queries=6)
+    p = w.preset
+    Cn = gen.filter_centroids(w)                       # the 1024 mixture centres
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj.to(DEV))
+    dz.build_index(ix, w.docs.to(DEV), w.lengths)
+    dz.filter_build(ix, Cn.to(DEV), w.docs.to(DEV))
+    filter_k, probe = 512, 1
+    cand, cnt = dz.filter_query(ix, w.queries.to(DEV), w.q_lengths, probe, filter_k)
+    ids, sc = dz.search(ix, w.queries.to(DEV), w.q_lengths, p.k, cand_ids=cand)
+    raw = dz.scores(ix, w.queries.to(DEV), w.q_lengths, cand_ids=cand).cpu().numpy().reshape(p.n_queries, filter_k)
+    cand, ids, sc = cand.cpu().numpy(), ids.cpu().numpy(), sc.cpu().numpy()
+    # oracle pipeline
+    X, Q, R = w.docs.numpy(), w.queries.numpy(), w.proj.numpy()
+    off = w.offsets.numpy()
+    obo, obd = orc.inverted_index(orc.assign_centroids(X, Cn.numpy()), off, Cn.shape[0])
+    dc, qc = orc.hash_i8(X, R, p.L, p.C), orc.hash_i8(Q, R, p.L, p.C)
+    hits = 0
+    for b in range(p.n_queries):
+        q = slice(b * p.q_len, (b + 1) * p.q_len)
+        want_cand, _ = orc.filter_query(Q[q], Cn.numpy(), obo, obd, w.n_docs, probe, filter_k)
+        assert np.array_equal(cand[b], want_cand), b
+        real = want_cand != 0xFFFFFFFF
+        s = orc.scores(dc, off, qc[q], want_cand[real].astype(np.int64))
+        assert np.array_equal(raw[b][real], s) and np.all(raw[b][~real] == -1)
+        want_ids, want_sc = orc.topk(s, p.k, want_cand[real].astype(np.int64))
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+        hits += len(set(w.planted[b].tolist()) & set(cand[b].tolist()))
+    # Each planted document supplied 4 of the 32 query vectors and documents here spread their ~70 vectors over
+    # random centres, so an unrelated document already collects ~2 hits: about half of the planted ones make the
+    # cut of 512.  A uniformly random cut would keep 512/20000 of them (about 1 of 48).
+    assert hits >= 12, hits
+
+
+def test_search_all_slots_empty_and_k_larger_than_real_candidates():
+    say("search with mostly empty candidate slots")
+    rng = np.random.default_rng(9)
+    ix, X, Cn, R, off, lens = setup(rng, 128, 16, 100, 10)
+    q = torch.from_numpy(X[:8]).to(DEV)
+    cand = torch.full((2, 6), 0xFFFFFFFF, dtype=torch.int64).to(torch.int32).to(DEV)
+    cand[1, 2] = 7
+    cand[1, 4] = 3
+    ids, sc = dz.search(ix, q, [4, 4], 4, cand_ids=cand)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    assert np.all(ids[0] == 0xFFFFFFFF) and np.all(sc[0] == -1)
+    assert set(ids[1, :2].tolist()) == {3, 7} and np.all(ids[1, 2:] == 0xFFFFFFFF) and np.all(sc[1, 2:] == -1)

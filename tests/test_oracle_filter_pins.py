@@ -67,7 +67,7 @@ def test_filter_query_matches_dictionary_counting(probe, filter_k):
     ids, cnt = orc.filter_query(Q, Cn, bo, docs, n_docs, probe, filter_k)
     m = len(ranked)
     assert ids[:m].tolist() == [r[0] for r in ranked] and cnt[:m].tolist() == [r[1] for r in ranked]
-    assert np.all(ids[m:] == 0xFFFFFFFF) and np.all(cnt[m:] == 0)
+    assert np.all(ids[m:] == 0xFFFFFFFF) and np.all(cnt[m:] == -1)
     if probe == K:
         # every bucket is probed by every query vector: count = |Q| * (distinct centroids of the document)
         for doc, n in counts.items():
