@@ -179,7 +179,8 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
  *   bucket_offsets_dev  dev, out, [n_centroids+1] u32: bucket c = bucket_docs[offsets[c] .. offsets[c+1])
  *   bucket_docs_dev     dev, out, room for n_vectors u32 (upper bound of the total bucket size); a
  *                       document appears once per bucket, in unspecified order inside the bucket
- * The two bucket arrays must stay alive while dessert_filter_query is used.
+ * The two bucket arrays must stay alive while dessert_filter_query is used.  This call waits for the
+ * stream (it reads the bucket sizes back: the largest one sizes the query workspace).
  *
  * dessert_filter_query: for each query vector the filter_probe closest centroids; every document gets
  * one count per (query vector, probed centroid) pair whose bucket holds it; per query set the
@@ -187,12 +188,14 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
  *   out_ids_dev     dev, out, [n_queries][filter_k] u32, unused slots 0xFFFFFFFF: can be passed to
  *                   dessert_search as candidate lists of equal length filter_k
  *   out_counts_dev  dev, out, [n_queries][filter_k] i32, unused slots -1
+ *   workspace_dev   dev, 256-byte aligned, dessert_filter_workspace_bytes(index, n_queries, total query
+ *                   vectors, longest query set, filter_probe) bytes
  * Limits: n_centroids <= 2^20, filter_probe <= min(n_centroids, 1024), filter_k <= 16384. */
 dessert_status_t dessert_filter_build(dessert_index_t *index, const int8_t *centroids_dev, uint32_t n_centroids,
                                       const void *vectors_dev, uint32_t *assign_dev, uint32_t *bucket_offsets_dev,
                                       uint32_t *bucket_docs_dev);
 size_t dessert_filter_workspace_bytes(const dessert_index_t *index, uint32_t n_queries, uint64_t total_q_vectors,
-                                      uint32_t filter_probe, uint32_t filter_k);
+                                      uint32_t max_q_len, uint32_t filter_probe);
 dessert_status_t dessert_filter_query(const dessert_index_t *index, const void *q_vectors_dev,
                                       const uint32_t *q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
                                       uint32_t filter_k, void *workspace_dev, size_t workspace_bytes,

@@ -296,7 +296,7 @@ def filter_query(ix: Index, q_vectors: torch.Tensor, q_lengths, filter_probe: in
     if int(ql.sum()) != q_vectors.shape[0]:
         raise ValueError("sum(q_lengths) != number of query vectors")
     if workspace is None:
-        nbytes = int(lib().dessert_filter_workspace_bytes(ix.handle, B, q_vectors.shape[0], filter_probe, filter_k))
+        nbytes = int(lib().dessert_filter_workspace_bytes(ix.handle, B, q_vectors.shape[0], int(ql.max()), filter_probe))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=ix.device)
     ids = torch.empty(B, filter_k, dtype=torch.uint32, device=ix.device)
     counts = torch.empty(B, filter_k, dtype=torch.int32, device=ix.device)

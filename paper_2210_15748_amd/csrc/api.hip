@@ -63,6 +63,7 @@ struct dessert_index {
     uint32_t f_K = 0;
     const uint32_t* f_bucket_off = nullptr;   // caller's
     const uint32_t* f_bucket_docs = nullptr;  // caller's
+    uint32_t f_max_bucket = 0;                // most documents in one bucket
     bool f_built = false;
     int transform = DESSERT_SCORE_RAW_COUNTS;
     int hash_algo = DESSERT_HASH_AUTO;
@@ -569,6 +570,14 @@ dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroi
                                  ix->f_table, assign_dev, ix->stream));
     HIP_TRY(launch_filter_buckets(assign_dev, ix->offsets, ix->n_docs, n_centroids, ix->f_cursor, bucket_offsets_dev,
                                   bucket_docs_dev, ix->stream));
+    {   // the largest bucket bounds how many documents one query set can hit (sizes the query workspace)
+        std::vector<uint32_t> off((size_t)n_centroids + 1);
+        HIP_TRY(hipMemcpyAsync(off.data(), bucket_offsets_dev, off.size() * 4, hipMemcpyDeviceToHost, ix->stream));
+        HIP_TRY(hipStreamSynchronize(ix->stream));
+        uint32_t mx = 0;
+        for (uint32_t c = 0; c < n_centroids; ++c) mx = std::max(mx, off[c + 1] - off[c]);
+        ix->f_max_bucket = mx;
+    }
     ix->f_K = n_centroids;
     ix->f_bucket_off = bucket_offsets_dev;
     ix->f_bucket_docs = bucket_docs_dev;
@@ -578,27 +587,32 @@ dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroi
 
 namespace {
 struct FilterWorkspace {
-    size_t dist, probe_ids, q_off, counts, partial, total;
+    size_t dist, probe_ids, q_off, cursor, lists, list_stride, total;
 };
-FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total_q, uint32_t probe, uint32_t filter_k) {
+// max_q: vectors of the longest query set
+FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total_q, uint32_t max_q, uint32_t probe) {
     FilterWorkspace w{};
     size_t p = 0;
-    w.dist = p;      p += align_up((size_t)total_q * filter_tiles(ix->f_K) * 32 * 4, 256);
+    // probe selection: per-range lists for small probe counts, else the full distance matrix
+    const FilterProbePlan pl = filter_probe_plan(total_q, ix->f_K, probe);
+    w.dist = p;      p += align_up(pl.ranges ? pl.list_bytes : (size_t)total_q * filter_tiles(ix->f_K) * 32 * 4, 256);
     w.probe_ids = p; p += align_up((size_t)total_q * probe * 4, 256);
     w.q_off = p;     p += align_up(((size_t)B + 1) * 4, 256);
-    w.counts = p;    p += align_up((size_t)B * ix->n_docs * 4, 256);
-    w.partial = p;
-    uint32_t slices = topk_slices(ix->n_docs, B);
-    if (slices > 1) p += align_up((size_t)B * slices * filter_k * 8, 256);
+    w.cursor = p;    p += align_up((size_t)B * 4, 256);
+    // a query set hits at most (its vectors * probe) buckets of at most f_max_bucket documents each
+    uint64_t hit = (uint64_t)max_q * probe * ix->f_max_bucket;
+    if (hit > ix->n_docs) hit = ix->n_docs;
+    w.list_stride = (size_t)((hit + 31) & ~31ull);
+    w.lists = p;     p += align_up((size_t)B * w.list_stride * 8, 256);
     w.total = p;
     return w;
 }
 }  // namespace
 
 size_t dessert_filter_workspace_bytes(const dessert_index_t* ix, uint32_t n_queries, uint64_t total_q_vectors,
-                                      uint32_t filter_probe, uint32_t filter_k) {
+                                      uint32_t max_q_len, uint32_t filter_probe) {
     if (!ix || !ix->f_built) return 0;
-    return carve_filter(ix, n_queries, total_q_vectors, filter_probe, filter_k).total;
+    return carve_filter(ix, n_queries, total_q_vectors, max_q_len, filter_probe).total;
 }
 
 dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_vectors_dev,
@@ -629,7 +643,7 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     }
     const uint64_t total_q = q_off[n_queries];
     if ((uint64_t)max_q * filter_probe > 0x7FFFFFFEull) return fail(DESSERT_EINVAL, "count range too large");
-    FilterWorkspace w = carve_filter(ix, n_queries, total_q, filter_probe, filter_k);
+    FilterWorkspace w = carve_filter(ix, n_queries, total_q, max_q, filter_probe);
     if (workspace_bytes < w.total)
         return fail(DESSERT_EINVAL, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, w.total);
     DeviceGuard guard(ix->cfg.device);
@@ -638,20 +652,24 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     int32_t* dist = (int32_t*)(ws + w.dist);
     uint32_t* probe_ids = (uint32_t*)(ws + w.probe_ids);
     uint32_t* d_q_off = (uint32_t*)(ws + w.q_off);
-    int32_t* counts = (int32_t*)(ws + w.counts);
+    uint32_t* cursor = (uint32_t*)(ws + w.cursor);
+    uint64_t* lists = (uint64_t*)(ws + w.lists);
     if (!q_uniform)  // pageable source: the runtime stages it before returning
         HIP_TRY(hipMemcpyAsync(d_q_off, q_off.data(), ((size_t)n_queries + 1) * 4, hipMemcpyHostToDevice, ix->stream));
-    HIP_TRY(launch_filter_distances((const int8_t*)q_vectors_dev, total_q, ix->cfg.d, ix->f_K, ix->f_cent, ix->f_table,
-                                    dist, ix->stream));
-    HIP_TRY(launch_filter_probe(dist, total_q, ix->f_K, filter_probe, probe_ids, ix->stream));
-    HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, d_q_off, q_uniform, n_queries, ix->f_bucket_off,
-                                ix->f_bucket_docs, ix->n_docs, counts, ix->stream));
-    TopkArgs ta{};
-    ta.scores = counts; ta.cand_ids = nullptr; ta.cand_off = nullptr; ta.cand_uniform = 0; ta.n_docs = ix->n_docs;
-    ta.n_queries = n_queries; ta.max_scored = ix->n_docs; ta.k = filter_k; ta.max_score = max_q * filter_probe;
-    ta.min_score = 1;  // documents no probed bucket holds are not candidates
-    ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids_dev; ta.out_scores = out_counts_dev;
-    HIP_TRY(launch_topk(ta, ix->stream));
+    const FilterProbePlan pl = filter_probe_plan(total_q, ix->f_K, filter_probe);
+    if (pl.ranges) {
+        HIP_TRY(launch_filter_probe_lists((const int8_t*)q_vectors_dev, total_q, ix->cfg.d, ix->f_K, ix->f_cent,
+                                          ix->f_table, filter_probe, pl, (int64_t*)dist, probe_ids, ix->stream));
+    } else {
+        HIP_TRY(launch_filter_distances((const int8_t*)q_vectors_dev, total_q, ix->cfg.d, ix->f_K, ix->f_cent,
+                                        ix->f_table, dist, ix->stream));
+        HIP_TRY(launch_filter_probe(dist, total_q, ix->f_K, filter_probe, probe_ids, ix->stream));
+    }
+    HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, max_q * filter_probe, d_q_off, q_uniform, n_queries,
+                                ix->f_bucket_off, ix->f_bucket_docs, ix->n_docs, lists, w.list_stride, cursor,
+                                ix->stream));
+    HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
+                              ix->n_docs ? ix->n_docs - 1 : 0, out_ids_dev, out_counts_dev, ix->stream));
     return DESSERT_OK;
 }
 

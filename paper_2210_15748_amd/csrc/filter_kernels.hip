@@ -54,21 +54,42 @@ __global__ void filter_prep_kernel(const int8_t* __restrict__ Cn, uint32_t K, ui
 
 // ---------------------------------------------------------------------------
 // vectors x centroids.  Each wave keeps 32*NT vectors as MFMA B fragments in registers and walks
-// over all centroid tiles; the workgroup stages FILTER_TG tiles of centroids (and their key
-// constants) in LDS at a time.  STORE = false: closest centroid of every vector (running max of
-// the keys; the two lane halves of a column are merged at the end).  STORE = true: the values
-// 2 x.c - |c|^2 themselves, out[v][tiles*32] (for the query-side probe selection).
-template <int KS, int NT, bool STORE>
+// over a range of centroid tiles (blockIdx.y selects the range); the workgroup stages FILTER_TG
+// tiles of centroids (and their key constants) in LDS at a time.  Three epilogues:
+//   MODE = 0      closest centroid of every vector (running max of the keys; the two lane halves
+//                 of a column are merged at the end); one tile range only.
+//   MODE = P > 0  the P best centroids each lane has seen, as sorted lists of 64-bit entries
+//                 (value in the high word, ~id in the low word: larger = closer, then lower id),
+//                 lists[v][range][half][P]; filter_merge_kernel joins the lists of a vector.
+//   MODE = -1     the values 2 x.c - |c|^2 themselves, out[v][tiles*32] (any probe count).
+constexpr int64_t LIST_EMPTY = INT64_MIN;
+
+template <int P>
+__device__ __forceinline__ void list_insert(int64_t (&best)[P], int64_t x) {
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+        const bool gt = x > best[i];
+        const int64_t lo = gt ? best[i] : x;
+        best[i] = gt ? x : best[i];
+        x = lo;
+    }
+}
+
+template <int KS, int NT, int MODE>
 __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restrict__ X, uint64_t n,
                                                           const v4i* __restrict__ Cp, const v4i* __restrict__ T2,
-                                                          uint32_t tiles, uint32_t* __restrict__ assign,
-                                                          int32_t* __restrict__ out) {
+                                                          uint32_t tiles, uint32_t K, uint32_t tiles_per_range,
+                                                          uint32_t* __restrict__ assign, int32_t* __restrict__ out,
+                                                          int64_t* __restrict__ lists) {
     constexpr int D = KS * 32;
+    constexpr int P = MODE > 0 ? MODE : 1;
     __shared__ v4i sA[FILTER_TG * KS * 64];
     __shared__ v4i sT[FILTER_TG * 8];  // 32 ints per tile
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
     const uint64_t v0 = ((uint64_t)blockIdx.x * 4 + wave) * (32 * NT);
+    const uint32_t t_begin = blockIdx.y * tiles_per_range;
+    const uint32_t t_end = tiles - t_begin < tiles_per_range ? tiles : t_begin + tiles_per_range;
 
     v4i b[NT][KS];
 #pragma unroll
@@ -81,14 +102,17 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
     }
     int32_t best_key[NT];
     uint32_t best_tile[NT];
+    int64_t best[NT][P];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         best_key[nt] = (int32_t)0x80000000;
         best_tile[nt] = 0;
+#pragma unroll
+        for (int i = 0; i < P; ++i) best[nt][i] = LIST_EMPTY;
     }
 
-    for (uint32_t t0 = 0; t0 < tiles; t0 += FILTER_TG) {
-        const uint32_t tg = tiles - t0 < FILTER_TG ? tiles - t0 : FILTER_TG;
+    for (uint32_t t0 = t_begin; t0 < t_end; t0 += FILTER_TG) {
+        const uint32_t tg = t_end - t0 < FILTER_TG ? t_end - t0 : FILTER_TG;
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < tg * KS * 64; i += 256) sA[i] = Cp[(size_t)t0 * KS * 64 + i];
         for (uint32_t i = threadIdx.x; i < tg * 8; i += 256) sT[i] = T2[(size_t)t0 * 8 + i];
@@ -118,7 +142,7 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
                 int32_t key[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) key[r] = (int32_t)(((uint32_t)acc[nt][r] << 5) + (uint32_t)tc[r]);
-                if constexpr (STORE) {
+                if constexpr (MODE < 0) {
                     const uint64_t v = v0 + nt * 32 + col;
                     if (v < n) {
                         int32_t* dst = out + v * ((uint64_t)tiles * 32) + (uint64_t)(t0 + tt) * 32 + 4 * g;
@@ -132,17 +156,30 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
                     int32_t m = key[0];
 #pragma unroll
                     for (int r = 1; r < 16; ++r) m = key[r] > m ? key[r] : m;
-                    // across tiles only the value counts (the low 4 bits rank rows inside one tile); strict,
-                    // because an equal value in a later tile is a higher centroid id
-                    if ((m | 15) > (best_key[nt] | 15)) {
-                        best_key[nt] = m;
-                        best_tile[nt] = t0 + tt;
+                    if constexpr (MODE == 0) {
+                        // across tiles only the value counts (the low 4 bits rank rows inside one tile); strict,
+                        // because an equal value in a later tile is a higher centroid id
+                        if ((m | 15) > (best_key[nt] | 15)) {
+                            best_key[nt] = m;
+                            best_tile[nt] = t0 + tt;
+                        }
+                    } else {
+                        // a lane meets centroid ids in increasing tile order, so once its list is full only a
+                        // strictly larger value can enter: most tiles are rejected by this one comparison
+                        if ((m >> 4) > (int32_t)(best[nt][P - 1] >> 32)) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const uint32_t cid = (t0 + tt) * 32 + tile_row(r, g);
+                                const int64_t e = (int64_t)(((uint64_t)(uint32_t)(key[r] >> 4) << 32) | (uint32_t)~cid);
+                                if (cid < K && e > best[nt][P - 1]) list_insert<P>(best[nt], e);
+                            }
+                        }
                     }
                 }
             }
         }
     }
-    if constexpr (!STORE) {
+    if constexpr (MODE == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             int32_t val = best_key[nt] >> 4;
@@ -153,7 +190,37 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
             const uint64_t v = v0 + nt * 32 + col;
             if (g == 0 && v < n) assign[v] = c;
         }
+    } else if constexpr (MODE > 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const uint64_t v = v0 + nt * 32 + col;
+            if (v < n) {
+                int64_t* dst = lists + ((v * gridDim.y + blockIdx.y) * 2 + g) * P;
+#pragma unroll
+                for (int i = 0; i < P; ++i) dst[i] = best[nt][i];
+            }
+        }
     }
+}
+
+// one thread per vector: the `probe` best entries of its per_vec list entries, closest first
+template <int P>
+__global__ __launch_bounds__(256) void filter_merge_kernel(const int64_t* __restrict__ lists, uint64_t n,
+                                                           uint32_t per_vec, uint32_t probe,
+                                                           uint32_t* __restrict__ probe_ids) {
+    const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n) return;
+    int64_t best[P];
+#pragma unroll
+    for (int i = 0; i < P; ++i) best[i] = LIST_EMPTY;
+    const int64_t* src = lists + v * per_vec;
+    for (uint32_t i = 0; i < per_vec; ++i) {
+        const int64_t e = src[i];
+        if (e > best[P - 1]) list_insert<P>(best, e);
+    }
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+        if ((uint32_t)i < probe) probe_ids[v * probe + i] = best[i] == LIST_EMPTY ? 0xFFFFFFFFu : ~(uint32_t)best[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -170,14 +237,18 @@ __global__ __launch_bounds__(256) void filter_bucket_kernel(const uint32_t* __re
     const uint32_t lane = threadIdx.x & 63;
     for (uint64_t doc = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6); doc < n_docs; doc += (uint64_t)gridDim.x * 4) {
         const uint64_t lo = doc_off[doc], hi = doc_off[doc + 1];
-        for (uint64_t j = lo + lane; j < hi; j += 64) {
-            const uint32_t c = assign[j];
-            bool first = true;
-            for (uint64_t e = lo; e < j; ++e)
-                if (assign[e] == c) {
-                    first = false;
-                    break;
+        for (uint64_t j0 = lo; j0 < hi; j0 += 64) {  // 64 vectors of the document per pass, one per lane
+            const bool valid = j0 + lane < hi;
+            const uint32_t c = valid ? assign[j0 + lane] : 0xFFFFFFFFu;
+            bool first = valid;
+            for (uint64_t e0 = lo; e0 <= j0; e0 += 64) {  // against every earlier vector, 64 at a time
+                const uint32_t ce = e0 == j0 ? c : assign[e0 + lane];  // e0 < j0: a full chunk
+                const uint32_t cnt = e0 == j0 ? (uint32_t)(hi - j0 < 64 ? hi - j0 : 64) : 64u;
+                for (uint32_t e = 0; e < cnt; ++e) {
+                    const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)ce, (int)e);
+                    if (v == c && (e0 < j0 || e < lane)) first = false;
                 }
+            }
             if (first) {
                 uint32_t pos = atomicAdd(&size_or_cursor[c], 1u);
                 if constexpr (FILL) bucket_docs[bucket_off[c] + pos] = (uint32_t)doc;
@@ -245,29 +316,102 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
         p[i] = 0;
 }
 
-// one workgroup per (query vector, probe rank): every document of the probed bucket gets +1 in
-// its query set's row of counts [B][n_docs]
-__global__ __launch_bounds__(256) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
-                                                           const uint32_t* __restrict__ q_off, uint32_t q_uniform,
-                                                           uint32_t n_queries, const uint32_t* __restrict__ bucket_off,
-                                                           const uint32_t* __restrict__ bucket_docs, uint64_t n_docs,
-                                                           int32_t* __restrict__ counts) {
-    const uint32_t q = blockIdx.x / probe;
-    const uint32_t c = probe_ids[blockIdx.x];
-    if (c == 0xFFFFFFFFu) return;
-    uint32_t b;
-    if (q_uniform) {
-        b = q / q_uniform;
-    } else {  // last query set starting at or before q
-        uint32_t lo = 0, hi = n_queries;
-        while (hi - lo > 1) {
-            uint32_t mid = (lo + hi) / 2;
-            if (q_off[mid] <= q) lo = mid; else hi = mid;
+// Bucket counting without global atomics.  Workgroup (slab, query set) owns the documents
+// [slab * slab_docs, +slab_docs) and keeps one counter per document in LDS (W bytes each, packed into
+// 32-bit words; a count never exceeds the number of probed buckets, which the host bounds by the
+// counter range).  It streams every bucket its query set probes, counts the ids that fall into its
+// slab, and appends one key per document hit, (count, id) in the top-k key format, to the query set's
+// list; cursor[b] ends as the number of distinct documents hit.  The order inside a list is unspecified.
+template <int W, int T>
+__global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
+                                                            const uint32_t* __restrict__ q_off, uint32_t q_uniform,
+                                                            const uint32_t* __restrict__ bucket_off,
+                                                            const uint32_t* __restrict__ bucket_docs, uint64_t n_docs,
+                                                            uint32_t slab_docs, uint32_t id_bits,
+                                                            uint64_t* __restrict__ lists, uint64_t list_stride,
+                                                            uint32_t* __restrict__ cursor) {
+    extern __shared__ uint32_t cnt[];
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t base_sh;
+    constexpr uint32_t PER = 4 / W, BITS = 8 * W, WAVES = T / 64;
+    constexpr uint32_t MASK = W == 4 ? 0xFFFFFFFFu : (1u << (BITS % 32)) - 1;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t b = blockIdx.y;
+    const uint32_t doc0 = blockIdx.x * slab_docs;
+    const uint32_t here = n_docs - doc0 < slab_docs ? (uint32_t)(n_docs - doc0) : slab_docs;
+    const uint32_t words = (here + PER - 1) / PER;
+    for (uint32_t i = tid; i < words; i += T) cnt[i] = 0;
+    __syncthreads();
+    const uint32_t q_lo = q_uniform ? b * q_uniform : q_off[b];
+    const uint32_t q_hi = q_uniform ? q_lo + q_uniform : q_off[b + 1];
+    const uint32_t pairs = (q_hi - q_lo) * probe;
+    const uint32_t* mine = probe_ids + (uint64_t)q_lo * probe;
+    // one wave per probed bucket; a wave first fetches the bounds of up to 64 of its buckets (one per lane),
+    // so the dependent loads id -> offsets are paid once, not once per bucket
+    for (uint32_t p0 = wave; p0 < pairs; p0 += WAVES * 64) {
+        const uint32_t myp = p0 + lane * WAVES;
+        uint32_t lo_l = 0, hi_l = 0;
+        if (myp < pairs) {
+            const uint32_t c = mine[myp];
+            if (c != 0xFFFFFFFFu) {
+                lo_l = bucket_off[c];
+                hi_l = bucket_off[c + 1];
+            }
         }
-        b = lo;
+        const uint32_t left = (pairs - p0 + WAVES - 1) / WAVES;
+        const uint32_t cnt_here = left < 64 ? left : 64;
+        for (uint32_t j = 0; j < cnt_here; ++j) {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)lo_l, (int)j);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)hi_l, (int)j);
+            for (uint32_t e = lo + lane; e < hi; e += 256) {
+                uint32_t id[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) id[u] = e + 64 * u < hi ? bucket_docs[e + 64 * u] : 0xFFFFFFFFu;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t local = id[u] - doc0;  // wraps to a large value for ids below the slab
+                    if (id[u] != 0xFFFFFFFFu && local < here)
+                        atomicAdd(&cnt[local / PER], 1u << ((local % PER) * BITS));
+                }
+            }
+        }
     }
-    int32_t* row = counts + (uint64_t)b * n_docs;
-    for (uint32_t e = bucket_off[c] + threadIdx.x; e < bucket_off[c + 1]; e += 256) atomicAdd(&row[bucket_docs[e]], 1);
+    __syncthreads();
+    uint32_t nz = 0;
+    for (uint32_t i = tid; i < words; i += T) {
+        const uint32_t x = cnt[i];
+        if (x) {
+#pragma unroll
+            for (uint32_t j = 0; j < PER; ++j) nz += ((x >> (j * BITS)) & MASK) != 0;
+        }
+    }
+    uint32_t incl = nz;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t y = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += y;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < (int)WAVES; ++w) total += wsum[w];
+        base_sh = total ? atomicAdd(&cursor[b], total) : 0;
+    }
+    uint32_t before = 0;
+    for (uint32_t w = 0; w < wave; ++w) before += wsum[w];
+    __syncthreads();
+    uint64_t* dst = lists + (uint64_t)b * list_stride + base_sh + before + incl - nz;
+    for (uint32_t i = tid; i < words; i += T) {
+        const uint32_t x = cnt[i];
+        if (x) {
+#pragma unroll
+            for (uint32_t j = 0; j < PER; ++j) {
+                const uint32_t c = (x >> (j * BITS)) & MASK;
+                if (c) *dst++ = make_key((int32_t)c, doc0 + i * PER + j, id_bits);
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -284,21 +428,23 @@ hipError_t launch_filter_prep(const int8_t* Cn, uint32_t K, uint32_t d, void* Cp
     return hipGetLastError();
 }
 
-template <bool STORE>
+template <int NT, int MODE>
 static hipError_t launch_gemm(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
-                              uint32_t* assign, int32_t* out, hipStream_t stream) {
+                              uint32_t ranges, uint32_t tiles_per_range, uint32_t* assign, int32_t* out, int64_t* lists,
+                              hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    constexpr int NT = 2;
     uint64_t blocks = (n + 4 * 32 * NT - 1) / (4 * 32 * NT);
-    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    if (blocks > 0x7fffffffull || ranges == 0 || ranges > 65535) return hipErrorInvalidValue;
     const uint32_t tiles = filter_tiles(K);
-    dim3 grid((unsigned)blocks), block(256);
+    if ((uint64_t)ranges * tiles_per_range < tiles || (uint64_t)(ranges - 1) * tiles_per_range >= tiles)
+        return hipErrorInvalidValue;  // every range must hold at least one tile and together they cover all
+    dim3 grid((unsigned)blocks, ranges), block(256);
     if (d == 64)
-        hipLaunchKernelGGL((filter_gemm_kernel<2, NT, STORE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, assign, out);
+        hipLaunchKernelGGL((filter_gemm_kernel<2, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
     else if (d == 128)
-        hipLaunchKernelGGL((filter_gemm_kernel<4, NT, STORE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, assign, out);
+        hipLaunchKernelGGL((filter_gemm_kernel<4, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
     else if (d == 256)
-        hipLaunchKernelGGL((filter_gemm_kernel<8, NT, STORE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, assign, out);
+        hipLaunchKernelGGL((filter_gemm_kernel<8, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -306,12 +452,67 @@ static hipError_t launch_gemm(const int8_t* X, uint64_t n, uint32_t d, uint32_t 
 
 hipError_t launch_filter_assign(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                 uint32_t* assign, hipStream_t stream) {
-    return launch_gemm<false>(X, n, d, K, Cp, T2, assign, nullptr, stream);
+    return launch_gemm<2, 0>(X, n, d, K, Cp, T2, 1, filter_tiles(K), assign, nullptr, nullptr, stream);
 }
 
 hipError_t launch_filter_distances(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                    int32_t* out, hipStream_t stream) {
-    return launch_gemm<true>(X, n, d, K, Cp, T2, nullptr, out, stream);
+    return launch_gemm<2, -1>(X, n, d, K, Cp, T2, 1, filter_tiles(K), nullptr, out, nullptr, stream);
+}
+
+// Query side with a small probe count: the centroid tiles are split into ranges so that the few query
+// vectors of a batch still fill the chip, and every range keeps its best P = 2^ceil(log2 probe) in registers.
+static uint32_t list_width(uint32_t probe) { return probe <= 1 ? 1 : probe <= 2 ? 2 : probe <= 4 ? 4 : 8; }
+
+FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe) {
+    FilterProbePlan pl{};
+    if (probe == 0 || probe > FILTER_LIST_MAX || n == 0) return pl;  // ranges = 0: use the distance matrix
+    const uint32_t tiles = filter_tiles(K);
+    const uint32_t groups = (tiles + FILTER_TG - 1) / FILTER_TG;
+    const uint64_t blocks = (n + 127) / 128;
+    uint64_t want = (2048 + blocks - 1) / blocks;  // aim at ~2048 workgroups
+    if (want > groups) want = groups;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    const uint32_t per = (groups + (uint32_t)want - 1) / (uint32_t)want;
+    pl.tiles_per_range = per * FILTER_TG;
+    pl.ranges = (tiles + pl.tiles_per_range - 1) / pl.tiles_per_range;
+    pl.width = list_width(probe);
+    pl.list_bytes = (size_t)n * pl.ranges * 2 * pl.width * 8;
+    return pl;
+}
+
+hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
+                                     uint32_t probe, const FilterProbePlan& pl, int64_t* lists, uint32_t* probe_ids,
+                                     hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (pl.ranges == 0 || probe > K || pl.width != list_width(probe)) return hipErrorInvalidValue;
+    hipError_t e;
+    const uint32_t per_vec = pl.ranges * 2 * pl.width;
+    const dim3 mgrid((unsigned)((n + 255) / 256)), mblock(256);
+    switch (pl.width) {
+        case 1:
+            e = launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(filter_merge_kernel<1>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
+            break;
+        case 2:
+            e = launch_gemm<1, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(filter_merge_kernel<2>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
+            break;
+        case 4:
+            e = launch_gemm<1, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(filter_merge_kernel<4>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
+            break;
+        default:
+            e = launch_gemm<1, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(filter_merge_kernel<8>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
+            break;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off, uint64_t n_docs, uint32_t K,
@@ -340,17 +541,41 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
     return hipGetLastError();
 }
 
-hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, const uint32_t* q_off,
-                               uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
-                               const uint32_t* bucket_docs, uint64_t n_docs, int32_t* counts, hipStream_t stream) {
-    const uint64_t cells = (uint64_t)n_queries * n_docs;
-    if (cells == 0 || total_q == 0) return hipSuccess;
-    if (total_q * probe > 0x7fffffffull) return hipErrorInvalidValue;
-    uint64_t zb = (cells + 256 * 8 - 1) / (256 * 8);
-    if (zb > 1u << 20) zb = 1u << 20;
-    hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)zb), dim3(256), 0, stream, counts, cells);
-    hipLaunchKernelGGL(filter_count_kernel, dim3((unsigned)(total_q * probe)), dim3(256), 0, stream, probe_ids, probe,
-                       q_off, q_uniform, n_queries, bucket_off, bucket_docs, n_docs, counts);
+constexpr uint32_t FILTER_SLAB_BYTES = 64 * 1024;  // LDS counters of one workgroup (two workgroups per CU)
+constexpr int FILTER_COUNT_THREADS = 512;
+
+hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
+                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
+                               const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists, uint64_t list_stride,
+                               uint32_t* cursor, hipStream_t stream) {
+    if (n_queries == 0) return hipSuccess;
+    if (n_queries > 65535 || n_docs > 0xFFFFFFFEull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(filter_zero_kernel, dim3((n_queries + 255) / 256), dim3(256), 0, stream, (int32_t*)cursor,
+                       (uint64_t)n_queries);
+    if (n_docs == 0 || total_q == 0) return hipGetLastError();
+    const uint32_t W = max_pairs <= 255 ? 1 : max_pairs <= 65535 ? 2 : 4;  // a count is at most the number of probed buckets
+    uint64_t slab_docs = FILTER_SLAB_BYTES / W;
+    if (slab_docs > n_docs) slab_docs = (n_docs + 3) & ~3ull;
+    const uint64_t slabs = (n_docs + slab_docs - 1) / slab_docs;
+    if (slabs > 0x7fffffffull) return hipErrorInvalidValue;
+    const size_t lds = (size_t)slab_docs * W;
+    const uint32_t id_bits = bits_for(n_docs - 1);
+    const dim3 grid((unsigned)slabs, n_queries), block(FILTER_COUNT_THREADS);
+    static hipError_t attr[3] = {
+        hipFuncSetAttribute((const void*)filter_count_kernel<1, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES),
+        hipFuncSetAttribute((const void*)filter_count_kernel<2, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES),
+        hipFuncSetAttribute((const void*)filter_count_kernel<4, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES)};
+    for (hipError_t e : attr)
+        if (e != hipSuccess) return e;
+    if (W == 1)
+        hipLaunchKernelGGL((filter_count_kernel<1, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
+                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
+    else if (W == 2)
+        hipLaunchKernelGGL((filter_count_kernel<2, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
+                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
+    else
+        hipLaunchKernelGGL((filter_count_kernel<4, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
+                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
     return hipGetLastError();
 }
 

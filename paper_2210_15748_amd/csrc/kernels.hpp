@@ -69,14 +69,28 @@ hipError_t launch_filter_assign(const int8_t* X, uint64_t n, uint32_t d, uint32_
                                 uint32_t* assign, hipStream_t stream);
 hipError_t launch_filter_distances(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                    int32_t* out /*[n][filter_tiles(K)*32]*/, hipStream_t stream);
+// Probe selection inside the GEMM for probe <= FILTER_LIST_MAX (ranges = 0: not applicable, use the
+// distance matrix + launch_filter_probe instead).
+constexpr uint32_t FILTER_LIST_MAX = 8;
+struct FilterProbePlan {
+    uint32_t ranges, tiles_per_range, width;
+    size_t list_bytes;  // int64 lists[n][ranges][2][width]
+};
+FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe);
+hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
+                                     uint32_t probe, const FilterProbePlan& plan, int64_t* lists, uint32_t* probe_ids,
+                                     hipStream_t stream);
 hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off, uint64_t n_docs, uint32_t K,
                                  uint32_t* cursor /*[K] scratch*/, uint32_t* bucket_off /*[K+1]*/, uint32_t* bucket_docs,
                                  hipStream_t stream);
 hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K, uint32_t probe, uint32_t* probe_ids,
                                hipStream_t stream);
-hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, const uint32_t* q_off,
-                               uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
-                               const uint32_t* bucket_docs, uint64_t n_docs, int32_t* counts, hipStream_t stream);
+// Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
+// max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.
+hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
+                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
+                               const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists, uint64_t list_stride,
+                               uint32_t* cursor /*[B], out*/, hipStream_t stream);
 
 // ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
 struct TopkArgs {
@@ -89,12 +103,16 @@ struct TopkArgs {
     uint64_t max_scored;
     uint32_t k;
     uint32_t max_score;         // largest possible score (longest query set * L)
-    int32_t min_score;          // results scoring below this are replaced by padding (0: keep everything)
     uint64_t* partial;          // workspace for the two-level path: [B][slices][k] keys
     uint32_t* out_ids;          // [B][k]
     int32_t* out_scores;        // [B][k]
 };
 uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
+// k best of stored key lists: lists[b][0..counts[b]) (counts on the device), keys as built by make_key with
+// id_bits = bits of max_id; one workgroup per list.
+hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
+                             uint32_t k, uint32_t max_score, uint64_t max_id, uint32_t* out_ids, int32_t* out_scores,
+                             hipStream_t stream);
 
 }  // namespace dessert

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, K
     block_select<TOPK_THREADS>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
     if (slices == 1) {
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
-            write_result(sorted[i], plan.id_bits, a.min_score, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
+            write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
     } else {
         uint64_t* dst = a.partial + ((size_t)b * slices + s) * a.k;
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS) dst[i] = sorted[i];
@@ -56,7 +56,49 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_merge_kernel(TopkArgs a, Ke
     StoredKeys keys{a.partial + (size_t)b * slices * a.k};
     block_select<TOPK_THREADS>(keys, (uint64_t)slices * a.k, a.k, kpad, sorted, sh, plan);
     for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
-        write_result(sorted[i], plan.id_bits, a.min_score, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
+        write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
+}
+
+// one workgroup per stored list whose length is read from device memory
+__global__ __launch_bounds__(TOPK_THREADS) void topk_lists_kernel(const uint64_t* __restrict__ lists, uint64_t list_stride,
+                                                                  const uint32_t* __restrict__ counts, uint32_t k,
+                                                                  KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
+                                                                  int32_t* __restrict__ out_scores) {
+    extern __shared__ uint64_t sorted[];
+    __shared__ SelectShared sh;
+    const uint32_t b = blockIdx.x;
+    StoredKeys keys{lists + (size_t)b * list_stride};
+    block_select<TOPK_THREADS>(keys, counts[b], k, kpad, sorted, sh, plan);
+    for (uint32_t i = threadIdx.x; i < k; i += TOPK_THREADS)
+        write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
+}
+
+static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the selection state is another 8.3 KB)
+    static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    return a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3;
+}
+
+hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
+                             uint32_t k, uint32_t max_score, uint64_t max_id, uint32_t* out_ids, int32_t* out_scores,
+                             hipStream_t stream) {
+    if (n_queries == 0 || k == 0) return hipSuccess;
+    if (k > TOPK_KMAX) return hipErrorInvalidValue;
+    uint32_t kpad = 2;
+    while (kpad < k) kpad <<= 1;
+    const KeyPlan plan = make_key_plan(max_score, max_id);
+    const size_t lds = (size_t)kpad * 8;
+    if (lds > 48 * 1024) {
+        hipError_t e = allow_large_k();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(topk_lists_kernel, dim3(n_queries), dim3(TOPK_THREADS), lds, stream, lists, list_stride, counts, k,
+                       plan, kpad, out_ids, out_scores);
+    return hipGetLastError();
 }
 
 hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
@@ -67,13 +109,9 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
     const KeyPlan plan = make_key_plan(a.max_score, a.n_docs ? a.n_docs - 1 : 0);
     const uint32_t slices = topk_slices(a.max_scored, a.n_queries);
     const size_t lds = (size_t)kpad * 8;
-    if (lds > 48 * 1024) {  // large k: opt in to more dynamic LDS (the selection state is another 8.3 KB)
-        static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel,
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-        static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-        if (a1 != hipSuccess) return a1;
-        if (a2 != hipSuccess) return a2;
+    if (lds > 48 * 1024) {
+        hipError_t e = allow_large_k();
+        if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(topk_scores_kernel, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices,
                        kpad);

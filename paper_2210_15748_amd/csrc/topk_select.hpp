@@ -56,8 +56,8 @@ __device__ inline uint64_t make_key(int32_t score, uint32_t id, uint32_t id_bits
     return ((uint64_t)(uint32_t)(score + 1) << id_bits) | (idmask - (uint64_t)id);
 }
 
-__device__ inline void write_result(uint64_t key, uint32_t id_bits, int32_t min_score, uint32_t* id, int32_t* score) {
-    if (key == 0 || (int32_t)(key >> id_bits) - 1 < min_score) {
+__device__ inline void write_result(uint64_t key, uint32_t id_bits, uint32_t* id, int32_t* score) {
+    if (key == 0) {
         *id = 0xFFFFFFFFu;
         *score = -1;
     } else {
@@ -103,9 +103,14 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             __syncthreads();
             const uint64_t prefix = sh.prefix;
             const uint32_t need = sh.need;
-            for (uint64_t i = tid; i < n; i += T) {
-                uint64_t key = keys(i);
-                if ((key >> (shift + width)) == prefix) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & dmask], 1u);
+            for (uint64_t i = tid; i < n; i += 4 * T) {  // four loads in flight per thread
+                uint64_t key[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i + u * T < n && (key[u] >> (shift + width)) == prefix)
+                        atomicAdd(&sh.hist[(uint32_t)(key[u] >> shift) & dmask], 1u);
             }
             __syncthreads();
             // digit D with  count(digits > D) < need <= count(digits >= D):
@@ -141,12 +146,18 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         }
         const uint64_t kth = sh.prefix;   // the k-th largest key
         const uint32_t need_eq = sh.need;  // copies of it that belong to the result
-        for (uint64_t i = tid; i < n; i += T) {
-            uint64_t key = keys(i);
-            if (key > kth) {
-                sorted[atomicAdd(&sh.count, 1u)] = key;
-            } else if (key == kth) {
-                if (atomicAdd(&sh.eq_taken, 1u) < need_eq) sorted[atomicAdd(&sh.count, 1u)] = key;
+        for (uint64_t i = tid; i < n; i += 4 * T) {
+            uint64_t key[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (i + u * T >= n) continue;
+                if (key[u] > kth) {
+                    sorted[atomicAdd(&sh.count, 1u)] = key[u];
+                } else if (key[u] == kth) {
+                    if (atomicAdd(&sh.eq_taken, 1u) < need_eq) sorted[atomicAdd(&sh.count, 1u)] = key[u];
+                }
             }
         }
     }

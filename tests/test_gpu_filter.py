@@ -41,12 +41,15 @@ def buckets_as_sets(bo, bd):
     return [sorted(bd[bo[k]:bo[k + 1]].tolist()) for k in range(len(bo) - 1)]
 
 
-@pytest.mark.parametrize("d,K,n_docs,dup", [(128, 1000, 900, False), (64, 37, 300, True), (256, 513, 400, True),
-                                            (128, 32, 50, False), (128, 5, 2000, True)])
-def test_filter_build_assignments_and_buckets(d, K, n_docs, dup):
-    say(f"filter build d={d} K={K} N={n_docs} dup={dup}")
+@pytest.mark.parametrize("d,K,n_docs,dup,max_len", [(128, 1000, 900, False, 40), (64, 37, 300, True, 40),
+                                                    (256, 513, 400, True, 40), (128, 32, 50, False, 40),
+                                                    (128, 5, 2000, True, 40),
+                                                    (128, 7, 300, True, 200),      # documents of 65..199 vectors
+                                                    (64, 150, 200, False, 300)])
+def test_filter_build_assignments_and_buckets(d, K, n_docs, dup, max_len):
+    say(f"filter build d={d} K={K} N={n_docs} dup={dup} max_len={max_len}")
     rng = np.random.default_rng(d + K)
-    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, 40, dup_centroids=dup)
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, max_len, dup_centroids=dup)
     assign, bo, bd = dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
     want = orc.assign_centroids(X, Cn)
     assert np.array_equal(assign.cpu().numpy(), want)
@@ -56,13 +59,18 @@ def test_filter_build_assignments_and_buckets(d, K, n_docs, dup):
     assert buckets_as_sets(bo, bd) == buckets_as_sets(obo, obd)
 
 
-@pytest.mark.parametrize("probe,filter_k,q_lens", [(1, 64, [32, 32, 32]), (2, 300, [5, 40, 1]), (4, 16, [32]),
-                                                   (8, 4096, [12, 7]), (37, 50, [3, 3])])
-def test_filter_query_matches_oracle(probe, filter_k, q_lens):
-    say(f"filter query probe={probe} filter_k={filter_k} q_lens={q_lens}")
+@pytest.mark.parametrize("probe,filter_k,q_lens,n_docs,max_len", [
+    (1, 64, [32, 32, 32], 1500, 12), (2, 300, [5, 40, 1], 1500, 12), (4, 16, [32], 1500, 12),
+    (8, 4096, [12, 7], 1500, 12), (37, 50, [3, 3], 1500, 12),
+    (37, 200, [10, 2], 1500, 12),            # counts up to 370: 16-bit counters
+    (37, 16384, [1800, 5], 1500, 12),        # counts up to 66600: 32-bit counters
+    (2, 1000, [32, 9], 300_000, 3),          # three document slabs of 8-bit counters
+    (3, 777, [100, 30], 150_000, 3)])        # three document slabs of 16-bit counters
+def test_filter_query_matches_oracle(probe, filter_k, q_lens, n_docs, max_len):
+    say(f"filter query probe={probe} filter_k={filter_k} q_lens={q_lens} N={n_docs}")
     rng = np.random.default_rng(100 + probe)
-    d, K, n_docs = 128, 37, 1500
-    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, 12, dup_centroids=True)
+    d, K = 128, 37
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, max_len, dup_centroids=True)
     dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
     nq = int(sum(q_lens))
     Q = np.clip(Cn[rng.integers(0, K, nq)].astype(np.int64) + rng.integers(-60, 61, (nq, d)), -127, 127).astype(np.int8)
@@ -71,6 +79,33 @@ def test_filter_query_matches_oracle(probe, filter_k, q_lens):
     obo, obd = orc.inverted_index(orc.assign_centroids(X, Cn), off, K)
     qo = np.concatenate([[0], np.cumsum(q_lens)])
     for b in range(len(q_lens)):
+        want_ids, want_cnt = orc.filter_query(Q[qo[b]:qo[b + 1]], Cn, obo, obd, n_docs, probe, filter_k)
+        assert np.array_equal(cnt[b], want_cnt), b
+        assert np.array_equal(ids[b], want_ids), b
+
+
+@pytest.mark.parametrize("d,K,probe,n_q", [(128, 3000, 1, 40), (128, 3000, 3, 40), (64, 2500, 5, 300),
+                                           (256, 1200, 8, 70), (128, 3, 2, 10), (128, 3000, 9, 20),
+                                           (128, 700, 4, 5000)])
+def test_filter_probe_selection_over_tile_ranges(d, K, probe, n_q):
+    """Many centroids: the probe selection runs over several centroid-tile ranges whose lists are merged;
+    duplicated centroids sit in different ranges (ties must go to the lower id)."""
+    say(f"filter probe ranges d={d} K={K} probe={probe} n_q={n_q}")
+    rng = np.random.default_rng(7 * d + K + probe)
+    n_docs = 400
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, 30, dup_centroids=K > 3)
+    if K > 100:
+        Cn[K - 7] = Cn[3]; Cn[K // 3] = Cn[3]; Cn[40] = Cn[K - 2]
+    dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
+    Q = np.clip(Cn[rng.integers(0, K, n_q)].astype(np.int64) + rng.integers(-30, 31, (n_q, d)), -127, 127).astype(np.int8)
+    Q[: min(n_q, 8)] = Cn[np.array([3, K - 2, 0, 1, 3, K - 1, K // 2, 2])[: min(n_q, 8)] % K]       # exact ties
+    q_lens = [n_q // 2, n_q - n_q // 2]
+    filter_k = 350
+    ids, cnt = dz.filter_query(ix, torch.from_numpy(Q).to(DEV), q_lens, probe, filter_k)
+    ids, cnt = ids.cpu().numpy(), cnt.cpu().numpy()
+    obo, obd = orc.inverted_index(orc.assign_centroids(X, Cn), off, K)
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    for b in range(2):
         want_ids, want_cnt = orc.filter_query(Q[qo[b]:qo[b + 1]], Cn, obo, obd, n_docs, probe, filter_k)
         assert np.array_equal(cnt[b], want_cnt), b
         assert np.array_equal(ids[b], want_ids), b
