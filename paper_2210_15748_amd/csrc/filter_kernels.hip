@@ -21,15 +21,20 @@ __host__ __device__ inline uint32_t tile_row(uint32_t r, uint32_t g) { return 8 
 
 // ---------------------------------------------------------------------------
 // Centroids in MFMA operand order, [tiles][KS][64 lanes][16 B] (tile = 32 centroids, rows past K
-// are zero), and the per-row constants of the comparison key, [tiles][2 halves][16 registers]:
-//   key(r) = (dot << 5) + T  with  T = (15 - r) - (|c|^2 << 4)
-//          = 16 * (2 dot - |c|^2) + (15 - r),
-// so a plain signed max over a lane's 16 keys picks the largest 2 x.c - |c|^2 and, among equal
-// ones, the lowest register = lowest row.  Rows past K get a constant that can never win.
+// are zero), and the per-row constants, for accumulator register r of lane half g:
+//   H[tiles][2][16]  -ceil(|c|^2 / 2): the accumulators start from it, so that after the MFMAs
+//                    acc = x.c - ceil(|c|^2 / 2) =: h  and  2 x.c - |c|^2 = 2 h + (|c|^2 & 1);
+//                    rows past K start from -2^25, below every real value (> -2^24 / 2)
+//   PAR[tiles][2]    bit r = |c|^2 & 1
+// A lane's largest h bounds its largest value (<= 2 h + 1): most tiles are dismissed by a max
+// over the raw accumulators, without building any per-row key.
+constexpr int32_t FILTER_PAD_INIT = -(1 << 25);
+
 __global__ void filter_prep_kernel(const int8_t* __restrict__ Cn, uint32_t K, uint32_t d, int8_t* __restrict__ Cp,
-                                   int32_t* __restrict__ T2, uint32_t tiles) {
+                                   int32_t* __restrict__ H, uint32_t tiles) {
     const uint32_t KS = d / 32;
     const uint32_t total = tiles * KS * 1024;
+    uint32_t* PAR = (uint32_t*)H + (size_t)tiles * 32;
     for (uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
         uint32_t e = idx & 15, l = (idx >> 4) & 63;
         uint32_t ks = (idx >> 10) % KS, tile = (idx >> 10) / KS;
@@ -37,18 +42,21 @@ __global__ void filter_prep_kernel(const int8_t* __restrict__ Cn, uint32_t K, ui
         uint32_t kk = ks * 32 + 16 * (l >> 5) + e;
         Cp[idx] = c < K ? Cn[(size_t)c * d + kk] : (int8_t)0;
     }
-    for (uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x; idx < tiles * 32; idx += gridDim.x * blockDim.x) {
-        uint32_t r = idx & 15, g = (idx >> 4) & 1, tile = idx >> 5;
-        uint32_t c = tile * 32 + tile_row(r, g);
-        int32_t t;
-        if (c < K) {
-            int32_t nrm = 0;
-            for (uint32_t i = 0; i < d; ++i) nrm += (int32_t)Cn[(size_t)c * d + i] * (int32_t)Cn[(size_t)c * d + i];
-            t = (int32_t)(15 - r) - (nrm << 4);
-        } else {
-            t = -(1 << 30);
+    for (uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x; idx < tiles * 2; idx += gridDim.x * blockDim.x) {
+        const uint32_t g = idx & 1, tile = idx >> 1;
+        uint32_t par = 0;
+        for (uint32_t r = 0; r < 16; ++r) {
+            const uint32_t c = tile * 32 + tile_row(r, g);
+            int32_t h = FILTER_PAD_INIT;
+            if (c < K) {
+                int32_t nrm = 0;
+                for (uint32_t i = 0; i < d; ++i) nrm += (int32_t)Cn[(size_t)c * d + i] * (int32_t)Cn[(size_t)c * d + i];
+                h = -((nrm + 1) >> 1);
+                par |= (uint32_t)(nrm & 1) << r;
+            }
+            H[(size_t)idx * 16 + r] = h;
         }
-        T2[idx] = t;
+        PAR[idx] = par;
     }
 }
 
@@ -75,6 +83,11 @@ __device__ __forceinline__ void list_insert(int64_t (&best)[P], int64_t x) {
     }
 }
 
+__device__ __forceinline__ int32_t max3(int32_t a, int32_t b, int32_t c) {  // one v_max3_i32
+    const int32_t ab = a > b ? a : b;
+    return ab > c ? ab : c;
+}
+
 template <int KS, int NT, int MODE>
 __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restrict__ X, uint64_t n,
                                                           const v4i* __restrict__ Cp, const v4i* __restrict__ T2,
@@ -85,6 +98,8 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
     constexpr int P = MODE > 0 ? MODE : 1;
     __shared__ v4i sA[FILTER_TG * KS * 64];
     __shared__ v4i sT[FILTER_TG * 8];  // 32 ints per tile
+    __shared__ uint32_t sP[FILTER_TG * 2];
+    const uint32_t* PAR = (const uint32_t*)T2 + (size_t)tiles * 32;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
     const uint64_t v0 = ((uint64_t)blockIdx.x * 4 + wave) * (32 * NT);
@@ -100,6 +115,7 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) b[nt][ks] = src[ks * 2];
     }
+    // MODE 0: best_key = 16 * value + (15 - register) of the best row so far, best_tile its tile
     int32_t best_key[NT];
     uint32_t best_tile[NT];
     int64_t best[NT][P];
@@ -116,61 +132,66 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < tg * KS * 64; i += 256) sA[i] = Cp[(size_t)t0 * KS * 64 + i];
         for (uint32_t i = threadIdx.x; i < tg * 8; i += 256) sT[i] = T2[(size_t)t0 * 8 + i];
+        for (uint32_t i = threadIdx.x; i < tg * 2; i += 256) sP[i] = PAR[(size_t)t0 * 2 + i];
         __syncthreads();
 #pragma unroll 1
         for (uint32_t tt = 0; tt < tg; ++tt) {
+            v16i init;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4i t = sT[tt * 8 + g * 4 + q];
+                init[4 * q] = t.x; init[4 * q + 1] = t.y; init[4 * q + 2] = t.z; init[4 * q + 3] = t.w;
+            }
+            const uint32_t par = sP[tt * 2 + g];
             v16i acc[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nt][r] = 0;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 v4i a = sA[(tt * KS + ks) * 64 + lane];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    acc[nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[nt][ks], acc[nt], 0, 0, 0);
-            }
-            int32_t tc[16];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v4i t = sT[tt * 8 + g * 4 + q];
-                tc[4 * q] = t.x; tc[4 * q + 1] = t.y; tc[4 * q + 2] = t.z; tc[4 * q + 3] = t.w;
+                    acc[nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[nt][ks], ks == 0 ? init : acc[nt], 0, 0, 0);
             }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                int32_t key[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) key[r] = (int32_t)(((uint32_t)acc[nt][r] << 5) + (uint32_t)tc[r]);
                 if constexpr (MODE < 0) {
                     const uint64_t v = v0 + nt * 32 + col;
                     if (v < n) {
                         int32_t* dst = out + v * ((uint64_t)tiles * 32) + (uint64_t)(t0 + tt) * 32 + 4 * g;
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            v4i o = {key[4 * q] >> 4, key[4 * q + 1] >> 4, key[4 * q + 2] >> 4, key[4 * q + 3] >> 4};
+                            v4i o;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) o[j] = 2 * acc[nt][4 * q + j] + (int32_t)((par >> (4 * q + j)) & 1);
                             *(v4i*)(dst + 8 * q) = o;
                         }
                     }
                 } else {
-                    int32_t m = key[0];
+                    int32_t m = max3(acc[nt][0], acc[nt][1], acc[nt][2]);
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) m = key[r] > m ? key[r] : m;
-                    if constexpr (MODE == 0) {
-                        // across tiles only the value counts (the low 4 bits rank rows inside one tile); strict,
-                        // because an equal value in a later tile is a higher centroid id
-                        if ((m | 15) > (best_key[nt] | 15)) {
-                            best_key[nt] = m;
-                            best_tile[nt] = t0 + tt;
-                        }
-                    } else {
-                        // a lane meets centroid ids in increasing tile order, so once its list is full only a
-                        // strictly larger value can enter: most tiles are rejected by this one comparison
-                        if ((m >> 4) > (int32_t)(best[nt][P - 1] >> 32)) {
+                    for (int r = 3; r < 15; r += 2) m = max3(m, acc[nt][r], acc[nt][r + 1]);
+                    m = acc[nt][15] > m ? acc[nt][15] : m;
+                    // a lane meets centroid ids in increasing tile order, so only a strictly larger value can
+                    // replace what it holds, and no value of this tile exceeds 2 m + 1
+                    const int32_t bound = MODE == 0 ? best_key[nt] >> 4 : (int32_t)(best[nt][P - 1] >> 32);
+                    if (2 * m + 1 > bound) {
+                        if constexpr (MODE == 0) {
+                            int32_t km = (int32_t)0x80000000;
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
+                                const int32_t val = 2 * acc[nt][r] + (int32_t)((par >> r) & 1);
+                                const int32_t key = val * 16 + (15 - r);  // equal values: the lower register = lower row
+                                km = key > km ? key : km;
+                            }
+                            if ((km >> 4) > bound) {
+                                best_key[nt] = km;
+                                best_tile[nt] = t0 + tt;
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int32_t val = 2 * acc[nt][r] + (int32_t)((par >> r) & 1);
                                 const uint32_t cid = (t0 + tt) * 32 + tile_row(r, g);
-                                const int64_t e = (int64_t)(((uint64_t)(uint32_t)(key[r] >> 4) << 32) | (uint32_t)~cid);
+                                const int64_t e = (int64_t)(((uint64_t)(uint32_t)val << 32) | (uint32_t)~cid);
                                 if (cid < K && e > best[nt][P - 1]) list_insert<P>(best[nt], e);
                             }
                         }
@@ -363,12 +384,13 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
         for (uint32_t j = 0; j < cnt_here; ++j) {
             const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)lo_l, (int)j);
             const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)hi_l, (int)j);
-            for (uint32_t e = lo + lane; e < hi; e += 256) {
-                uint32_t id[4];
+            constexpr int U = 16;  // loads in flight per lane: a bucket of up to 1024 documents is one round trip
+            for (uint32_t e = lo + lane; e < hi; e += 64 * U) {
+                uint32_t id[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) id[u] = e + 64 * u < hi ? bucket_docs[e + 64 * u] : 0xFFFFFFFFu;
+                for (int u = 0; u < U; ++u) id[u] = e + 64 * u < hi ? bucket_docs[e + 64 * u] : 0xFFFFFFFFu;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const uint32_t local = id[u] - doc0;  // wraps to a large value for ids below the slab
                     if (id[u] != 0xFFFFFFFFu && local < here)
                         atomicAdd(&cnt[local / PER], 1u << ((local % PER) * BITS));
@@ -419,7 +441,7 @@ static bool filter_shape(uint32_t d) { return d == 64 || d == 128 || d == 256; }
 bool filter_supported(uint32_t d) { return filter_shape(d); }
 uint32_t filter_tiles(uint32_t K) { return (K + 31) / 32; }
 size_t filter_centroid_bytes(uint32_t K, uint32_t d) { return (size_t)filter_tiles(K) * (d / 32) * 1024; }
-size_t filter_table_bytes(uint32_t K) { return (size_t)filter_tiles(K) * 32 * 4; }
+size_t filter_table_bytes(uint32_t K) { return (size_t)filter_tiles(K) * (32 + 2) * 4; }
 
 hipError_t launch_filter_prep(const int8_t* Cn, uint32_t K, uint32_t d, void* Cp, void* T2, hipStream_t stream) {
     if (!filter_shape(d) || K == 0) return hipErrorInvalidValue;
@@ -541,8 +563,8 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
     return hipGetLastError();
 }
 
-constexpr uint32_t FILTER_SLAB_BYTES = 64 * 1024;  // LDS counters of one workgroup (two workgroups per CU)
-constexpr int FILTER_COUNT_THREADS = 512;
+constexpr uint32_t FILTER_SLAB_BYTES = 128 * 1024;  // LDS counters of one workgroup
+constexpr int FILTER_COUNT_THREADS = 1024;
 
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
