@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--hash-algo", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-queries", type=int, default=32)
+    ap.add_argument("--no-filter", action="store_true", help="skip the candidate-filter section (config 3 only)")
+    ap.add_argument("--filter-centroids", type=int, default=65536)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -142,6 +144,42 @@ def main() -> int:
     topk_ms = float(np.mean([t["topk_ms"] for t in tim]))
     value = n_scored / (ms_per_step * 1e-3)
     log(f"[bench] search: {ms_per_step:.4f} ms/step  (hash {qhash_ms:.4f}  score {score_ms:.4f}  topk {topk_ms:.4f})")
+
+    # ---- candidate filter (Sec. 5 "Filtering") in front of the same search: reported beside the metric, not part of it
+    filt = None
+    if args.config == 3 and p.dtype == "i8" and not args.no_filter:
+        def ev_ms(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                r = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps, r
+        Kc = min(args.filter_centroids, w.n_vectors)
+        Cn = gen.filter_centroids(w, Kc)
+        f_build_ms, (assign, b_off, b_docs) = ev_ms(lambda: dz.filter_build(ix, Cn, w.docs), 1)
+        f_probe, f_k = 1, p.n_cand
+        f_query_ms, (f_ids, f_cnt) = ev_ms(lambda: dz.filter_query(ix, w.queries, ql, f_probe, f_k), 10)
+        f_cand = f_ids.view(torch.int32)
+        chain_ms, _ = ev_ms(lambda: dz.search(ix, w.queries, ql, k,
+                                              cand_ids=dz.filter_query(ix, w.queries, ql, f_probe, f_k)[0].view(torch.int32)), 10)
+        kept = float(np.mean([len(set(w.planted[b].tolist()) & set(f_ids[b].cpu().tolist())) for b in range(0, B, 8)]))
+        gemm_ops = 2.0 * w.n_vectors * Kc * p.d
+        filt = {"n_centroids": Kc, "centroids": "document vectors drawn without replacement (stand-in for k-means)",
+                "bucket_entries": int(b_off[-1].item()), "build_ms": round(f_build_ms, 2),
+                "build_roofline": {"bound": "mfma", "kernel": "filter_gemm_kernel (vectors x centroids, int8)",
+                                   "achieved": round(gemm_ops / (f_build_ms * 1e-3) / 1e12, 1), "peak": 5000.0,
+                                   "unit": "TOP/s", "frac": round(gemm_ops / (f_build_ms * 1e-3) / 1e12 / 5000.0, 4),
+                                   "note": "whole dessert_filter_build call (GEMM + argmin + bucket build) over the GEMM's operations"},
+                "filter_probe": f_probe, "filter_k": f_k, "query_ms_per_batch": round(f_query_ms, 4),
+                "queries_per_s": round(B / (f_query_ms * 1e-3), 1),
+                "filter_then_search_ms_per_batch": round(chain_ms, 4),
+                "planted_docs_kept_of_%d" % p.planted_per_query: round(kept, 2)}
+        log(f"[bench] filter: {filt}")
+        del assign, b_off, b_docs, f_ids, f_cnt, f_cand
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -246,6 +284,7 @@ def main() -> int:
                                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                      "frac": round(w.n_vectors * (p.d * (1 if p.dtype == "i8" else 2) + p.L) / (hash_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                                      if hash_kernel_ms else None}},
+        "candidate_filter": filt,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -157,3 +157,74 @@ def test_cfg5_fp16_gaussian_tolerance_path():
         overlap.append(len(set(o_ids.tolist()) & set(ids[b].tolist())) / p.k)
         assert ids[b, 0] == int(w.planted[b, 0])
     assert np.mean(overlap) >= 0.99, overlap
+
+
+def test_cfg3_full_candidate_filter_sampled():
+    """Candidate filter at the benchmark's size (1M documents, 65536 centroids, probe 1, filter_k 4096).
+
+    The oracle's brute-force assignment costs 8.4M multiply-adds per vector here, so it runs on samples:
+      - closest centroid of sampled document vectors, bit for bit;
+      - for sampled documents, the set of buckets that hold the document = the set of centroids the oracle
+        assigns its vectors to;
+      - for two query sets, the count of every sampled document (oracle: number of query vectors whose closest
+        centroid is among the document's) against the filter's output, including the cut at filter_k;
+      - properties at any size: bucket offsets, no document twice in a bucket, output order and padding."""
+    say("cfg3 full: candidate filter, 65536 centroids, probe 1, filter_k 4096")
+    w = gen.make(3, device=DEV)
+    p = w.preset
+    K, probe, filter_k = 65536, 1, 4096
+    Cn = gen.filter_centroids(w, K)
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj)
+    dz.build_index(ix, w.docs, w.lengths)
+    assign, b_off, b_docs = dz.filter_build(ix, Cn, w.docs)
+    ids, cnt = dz.filter_query(ix, w.queries, w.q_lengths, probe, filter_k)
+    ids_np, cnt_np = ids.cpu().numpy(), cnt.cpu().numpy()
+    Cn_np = Cn.cpu().numpy()
+    off = w.offsets.numpy()
+    rng = np.random.default_rng(33)
+
+    # bucket structure
+    bo = b_off.cpu().numpy().astype(np.int64)
+    assert bo[0] == 0 and np.all(np.diff(bo) >= 0) and bo[-1] <= w.n_vectors
+    entries = b_docs[: int(bo[-1])].to(torch.int64)
+    bucket_of_entry = torch.searchsorted(b_off.to(torch.int64), torch.arange(int(bo[-1]), device=DEV), right=True) - 1
+    pair = bucket_of_entry * w.n_docs + entries
+    assert torch.unique(pair).numel() == pair.numel()          # a document appears once per bucket
+    del pair
+
+    # sampled vectors: closest centroid
+    rows = rng.integers(0, w.n_vectors, 1500)
+    want = orc.assign_centroids(w.docs[torch.from_numpy(rows).to(DEV)].cpu().numpy(), Cn_np)
+    assert np.array_equal(assign[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.int64), want.astype(np.int64))
+
+    # sampled documents: buckets that hold them, and their counts for two query sets
+    qsets = (5, 200)
+    sample = set(rng.integers(0, w.n_docs, 30).tolist())
+    for b in qsets:
+        sample |= set(w.planted[b].tolist()) | set(int(x) for x in ids_np[b][:12]) | set(int(x) for x in ids_np[b][-6:])
+    sample.discard(0xFFFFFFFF)
+    sample = sorted(sample)
+    cent_of_doc = {}
+    for dcm in sample:
+        X = w.docs[off[dcm]:off[dcm + 1]].cpu().numpy()
+        cs = set(orc.assign_centroids(X, Cn_np).tolist())
+        cent_of_doc[dcm] = cs
+        pos = torch.nonzero(entries == dcm).reshape(-1)
+        got = set(bucket_of_entry[pos].cpu().tolist())
+        assert got == cs, dcm
+    for b in qsets:
+        qv = w.queries[b * p.q_len:(b + 1) * p.q_len].cpu().numpy()
+        qc = orc.assign_centroids(qv, Cn_np).tolist()                  # probe = 1: the closest centroid
+        real = ids_np[b] != 0xFFFFFFFF
+        assert np.all(cnt_np[b][real] >= 1) and np.all(cnt_np[b][~real] == -1) and np.all(cnt_np[b] <= p.q_len * probe)
+        key = cnt_np[b][real].astype(np.int64) * (1 << 32) - ids_np[b][real].astype(np.int64)
+        assert np.all(np.diff(key) < 0)                                  # count descending, then id ascending, no repeats
+        assert not np.any(real[1:] & ~real[:-1])                         # padding only at the end
+        where = {int(i): int(c) for i, c in zip(ids_np[b][real], cnt_np[b][real])}
+        last = (int(cnt_np[b][real][-1]), -int(ids_np[b][real][-1])) if real.all() else (0, 0)
+        for dcm in sample:
+            c = sum(1 for x in qc if x in cent_of_doc[dcm])
+            if dcm in where:
+                assert where[dcm] == c, (b, dcm)
+            else:
+                assert c == 0 or (c, -dcm) < last, (b, dcm, c, last)
