@@ -194,6 +194,88 @@ void oracle_scores_eq1(const uint8_t *doc_codes, const int64_t *offsets, uint32_
     free(sim);
 }
 
+/* ---- wide codes: more than 8 hashes per table (Sec. 6.1: the synthetic experiment sets
+ * C = log2(m) + 1, up to 11 at m = 1024).  The same definitions as above with the table's
+ * code kept in 16 bits (C <= 16): bit c of table t still comes from projection row t*C + c.
+ */
+void oracle_hash_i8_wide(const int8_t *X, uint64_t n, uint32_t d, const int8_t *R,
+                         uint32_t L, uint32_t C, uint16_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < (int64_t)n; ++v) {
+        const int8_t *x = X + (size_t)v * d;
+        for (uint32_t t = 0; t < L; ++t) {
+            uint32_t code = 0;
+            for (uint32_t c = 0; c < C; ++c) {
+                const int8_t *r = R + (size_t)(t * C + c) * d;
+                int32_t p = 0;
+                for (uint32_t i = 0; i < d; ++i)
+                    p += (int32_t)r[i] * (int32_t)x[i];
+                if (p >= 0)
+                    code |= 1u << c;
+            }
+            codes[(size_t)v * L + t] = (uint16_t)code;
+        }
+    }
+}
+
+void oracle_hash_fp_wide(const float *X, uint64_t n, uint32_t d, const float *R,
+                         uint32_t L, uint32_t C, uint16_t *codes, double *proj)
+{
+    const uint32_t P = L * C;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < (int64_t)n; ++v) {
+        const float *x = X + (size_t)v * d;
+        for (uint32_t t = 0; t < L; ++t) {
+            uint32_t code = 0;
+            for (uint32_t c = 0; c < C; ++c) {
+                const float *r = R + (size_t)(t * C + c) * d;
+                double p = 0.0;
+                for (uint32_t i = 0; i < d; ++i)
+                    p += (double)r[i] * (double)x[i];
+                if (proj)
+                    proj[(size_t)v * P + t * C + c] = p;
+                if (p >= 0.0)
+                    code |= 1u << c;
+            }
+            codes[(size_t)v * L + t] = (uint16_t)code;
+        }
+    }
+}
+
+/* Alg. 2 with sigma = max, A = sum on 16-bit codes; eq1_C = 0: raw counts, else the
+ * remap of Eq. 1 with C = eq1_C in the same Q16 form as oracle_scores_eq1.
+ */
+void oracle_scores_wide(const uint16_t *doc_codes, const int64_t *offsets, uint32_t L, uint32_t eq1_C,
+                        const uint16_t *q_codes, uint32_t mq,
+                        const int64_t *doc_ids, uint64_t n_scored, int32_t *scores)
+{
+    double *sim = (double *)malloc((L + 1) * sizeof(double));
+    for (uint32_t c = 0; c <= L; ++c)
+        sim[c] = (c == 0 || eq1_C == 0) ? 0.0 : exp(log((double)c / (double)L) / (double)eq1_C);   /* Eq. 1 */
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t s = 0; s < (int64_t)n_scored; ++s) {
+        int64_t i = doc_ids ? doc_ids[s] : s;
+        int64_t lo = offsets[i], hi = offsets[i + 1];
+        int64_t score = 0;
+        for (uint32_t q = 0; q < mq; ++q) {
+            const uint16_t *hq = q_codes + (size_t)q * L;
+            int32_t agg = 0;                        /* max over an empty set = 0 */
+            for (int64_t j = lo; j < hi; ++j) {
+                const uint16_t *hx = doc_codes + (size_t)j * L;
+                int32_t cnt = 0;
+                for (uint32_t t = 0; t < L; ++t)
+                    cnt += (hq[t] == hx[t]);
+                if (cnt > agg)
+                    agg = cnt;                      /* Eq. 1 is increasing: max of sims = sim of max */
+            }
+            score += eq1_C ? llround(65536.0 * sim[agg]) : agg;
+        }
+        scores[s] = (int32_t)score;
+    }
+    free(sim);
+}
+
 /* ---- top-k: Alg. 2 last line (argmax), widened to the k best.
  * Order: score descending, then document id ascending.  ids may be NULL
  * (then the id of entry s is s).  Missing slots (n < k) get id 0xFFFFFFFF,

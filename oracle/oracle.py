@@ -45,6 +45,11 @@ def hash_i8(X: np.ndarray, R: np.ndarray, L: int, Cbits: int, want_proj: bool = 
     R = np.ascontiguousarray(R, dtype=np.int8)
     n, d = X.shape
     assert R.shape == (L * Cbits, d)
+    if Cbits > 8:      # wide codes: 16 bits per table
+        assert Cbits <= 16 and not want_proj
+        codes = np.empty((n, L), dtype=np.uint16)
+        lib().oracle_hash_i8_wide(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits), _p(codes))
+        return codes
     codes = np.empty((n, L), dtype=np.uint8)
     proj = np.empty((n, L * Cbits), dtype=np.int32) if want_proj else None
     lib().oracle_hash_i8(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits),
@@ -58,6 +63,13 @@ def hash_fp(X: np.ndarray, R: np.ndarray, L: int, Cbits: int, want_proj: bool = 
     R = np.ascontiguousarray(R, dtype=np.float32)
     n, d = X.shape
     assert R.shape == (L * Cbits, d)
+    if Cbits > 8:
+        assert Cbits <= 16
+        codes = np.empty((n, L), dtype=np.uint16)
+        proj = np.empty((n, L * Cbits), dtype=np.float64) if want_proj else None
+        lib().oracle_hash_fp_wide(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits),
+                                  _p(codes), _p(proj))
+        return (codes, proj) if want_proj else codes
     codes = np.empty((n, L), dtype=np.uint8)
     proj = np.empty((n, L * Cbits), dtype=np.float64) if want_proj else None
     lib().oracle_hash_fp(_p(X), C.c_uint64(n), C.c_uint32(d), _p(R), C.c_uint32(L), C.c_uint32(Cbits),
@@ -65,7 +77,28 @@ def hash_fp(X: np.ndarray, R: np.ndarray, L: int, Cbits: int, want_proj: bool = 
     return (codes, proj) if want_proj else codes
 
 
+def _scores_wide(doc_codes, offsets, q_codes, eq1_C, doc_ids):
+    doc_codes = np.ascontiguousarray(doc_codes, dtype=np.uint16)
+    q_codes = np.ascontiguousarray(q_codes, dtype=np.uint16)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    L = q_codes.shape[1]
+    assert doc_codes.ndim == 2 and doc_codes.shape[1] == L and offsets[-1] <= doc_codes.shape[0]
+    n_docs = offsets.shape[0] - 1
+    if doc_ids is None:
+        n, ids = n_docs, None
+    else:
+        ids = np.ascontiguousarray(doc_ids, dtype=np.int64)
+        n = ids.shape[0]
+        assert n == 0 or (ids.min() >= 0 and ids.max() < n_docs)
+    out = np.empty(n, dtype=np.int32)
+    lib().oracle_scores_wide(_p(doc_codes), _p(offsets), C.c_uint32(L), C.c_uint32(eq1_C), _p(q_codes),
+                             C.c_uint32(q_codes.shape[0]), _p(ids), C.c_uint64(n), _p(out))
+    return out
+
+
 def scores(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, doc_ids=None) -> np.ndarray:
+    if np.asarray(doc_codes).dtype == np.uint16:
+        return _scores_wide(doc_codes, offsets, q_codes, 0, doc_ids)
     doc_codes = np.ascontiguousarray(doc_codes, dtype=np.uint8)
     q_codes = np.ascontiguousarray(q_codes, dtype=np.uint8)
     offsets = np.ascontiguousarray(offsets, dtype=np.int64)
@@ -89,6 +122,9 @@ def scores(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, doc_
 def scores_eq1(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, Cbits: int, doc_ids=None,
                want_table: bool = False):
     """Scores with the Eq. 1 similarity remap, Q16 fixed point (see oracle_scores_eq1)."""
+    if np.asarray(doc_codes).dtype == np.uint16:
+        assert not want_table
+        return _scores_wide(doc_codes, offsets, q_codes, Cbits, doc_ids)
     doc_codes = np.ascontiguousarray(doc_codes, dtype=np.uint8)
     q_codes = np.ascontiguousarray(q_codes, dtype=np.uint8)
     offsets = np.ascontiguousarray(offsets, dtype=np.int64)
