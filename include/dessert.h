@@ -36,8 +36,11 @@
  *   - Top-k order: score descending, ties by ascending document id; if fewer
  *     than k documents were scored the remaining slots hold id 0xFFFFFFFF and
  *     score -1.  Candidate ids are scored as given (duplicates appear twice).
- *   - Limits: 1 <= C <= 8, L a multiple of 4 with 4 <= L <= 128, d >= 1,
- *     (total query vectors of one set) * L <= 65535, k <= 16384.  Candidate
+ *   - Code width: a table's code holds its C one-bit hashes in one byte when
+ *     C <= 8 and in a little-endian u16 when 9 <= C <= 16 (Sec. 6.1 uses
+ *     C = log2(m) + 1, up to 11).  "Code arrays" below are [n][L] of that type.
+ *   - Limits: 1 <= C <= 16, L a multiple of 4 with 4 <= L <= 128, d >= 1,
+ *     (vectors of one query set) * L * (bytes per code) <= 65535, k <= 16384.  Candidate
  *     ids must be < n_docs (not checked on the device), except the value
  *     0xFFFFFFFF, which marks an empty candidate slot: it is scored -1 and is
  *     never returned by the top-k.
@@ -113,12 +116,13 @@ dessert_status_t dessert_set_algo(dessert_index_t *index, int hash_algo, int sco
 enum { DESSERT_SCORE_RAW_COUNTS = 0, DESSERT_SCORE_EQ1_Q16 = 1 };
 dessert_status_t dessert_set_score_transform(dessert_index_t *index, int transform);
 
-/* Bytes of the code array for n_vectors vectors: n_vectors * L (one byte per
- * vector and table, vector-major, no padding). */
+/* Bytes of the code array for n_vectors vectors: n_vectors * L * (bytes per code), one code per
+ * vector and table, vector-major, no padding. */
 size_t dessert_code_bytes(const dessert_index_t *index, uint64_t n_vectors);
 
 /* Hash n vectors (Alg. 1 line "h = f_t(x_j)", Alg. 2 line "h_{t,q} = f_t(q)").
- * vectors_dev: dev, [n][d] row-major of config.dtype.  codes_dev: dev, [n][L] u8. */
+ * vectors_dev: dev, [n][d] row-major of config.dtype.  codes_dev: dev, out, code array [n][L]
+ * (u8, or u16 when C > 8: see "Code width"), dessert_code_bytes(index, n) bytes. */
 dessert_status_t dessert_hash(const dessert_index_t *index, const void *vectors_dev, uint64_t n,
                               uint8_t *codes_dev);
 
@@ -126,7 +130,7 @@ dessert_status_t dessert_hash(const dessert_index_t *index, const void *vectors_
  * where each document's codes live.
  *   vectors_dev   dev, [n_vectors][d]: the documents' vectors, concatenated in document order
  *   lengths_host  host, [n_docs] u32: m_i = |S_i| (0 allowed); sum must equal n_vectors
- *   codes_dev     dev, out, dessert_code_bytes(n_vectors): codes_dev[(offsets[i]+j)*L + t] = f_t(x_j of S_i)
+ *   codes_dev     dev, out, dessert_code_bytes(n_vectors): code (offsets[i]+j)*L + t of the array = f_t(x_j of S_i)
  *   offsets_dev   dev, out, [n_docs+1] u64: exclusive scan of lengths (in vectors)
  * The handle remembers codes_dev / offsets_dev for later searches. */
 dessert_status_t dessert_build_index(dessert_index_t *index, const void *vectors_dev, uint64_t n_vectors,

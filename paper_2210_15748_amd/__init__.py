@@ -185,24 +185,29 @@ def _check_vectors(ix: Index, v: torch.Tensor) -> torch.Tensor:
     return v.contiguous()
 
 
+def code_dtype(ix: Index) -> torch.dtype:
+    """Element type of the code arrays: uint8, or uint16 when C > 8."""
+    return torch.uint16 if ix.cfg.C > 8 else torch.uint8
+
+
 def hash(ix: Index, vectors: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:  # noqa: A001
-    """dessert_hash: codes [n, L] uint8."""
+    """dessert_hash: codes [n, L] of code_dtype(ix)."""
     vectors = _check_vectors(ix, vectors)
     n = vectors.shape[0]
     if out is None:
-        out = torch.empty(n, ix.cfg.L, dtype=torch.uint8, device=ix.device)
+        out = torch.empty(n, ix.cfg.L, dtype=code_dtype(ix), device=ix.device)
     _check(lib().dessert_hash(ix.handle, vectors.data_ptr(), n, out.data_ptr()))
     return out
 
 
 def build_index(ix: Index, vectors: torch.Tensor, lengths, codes: Optional[torch.Tensor] = None,
                 offsets: Optional[torch.Tensor] = None):
-    """dessert_build_index.  Returns (codes [V, L] uint8, offsets [N+1] int64), both on the device."""
+    """dessert_build_index.  Returns (codes [V, L] of code_dtype(ix), offsets [N+1] int64), both on the device."""
     vectors = _check_vectors(ix, vectors)
     lens = _host_u32(lengths)
     n_docs, V = lens.shape[0], vectors.shape[0]
     if codes is None:
-        codes = torch.empty(V, ix.cfg.L, dtype=torch.uint8, device=ix.device)
+        codes = torch.empty(V, ix.cfg.L, dtype=code_dtype(ix), device=ix.device)
     if offsets is None:
         offsets = torch.empty(n_docs + 1, dtype=torch.int64, device=ix.device)
     _check(lib().dessert_build_index(ix.handle, vectors.data_ptr(), V, lens.ctypes.data, n_docs,

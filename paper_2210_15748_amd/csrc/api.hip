@@ -107,6 +107,8 @@ struct dessert_index {
 namespace {
 
 size_t proj_elem_bytes(uint32_t kind) { return kind == DESSERT_PROJ_RADEMACHER_I8 ? 1 : 4; }
+// bytes of one table's code: C one-bit hashes packed into one byte, or two when C > 8
+uint32_t code_width(const dessert_config_t& c) { return c.C > 8 ? 2u : 1u; }
 
 bool is_i8_mfma(const dessert_config_t& c) {
     return c.dtype == DESSERT_I8 && c.proj_kind == DESSERT_PROJ_RADEMACHER_I8 && hash_mfma_supported(c.d, c.L, c.C);
@@ -148,7 +150,7 @@ Workspace carve(const dessert_index* ix, uint32_t B, uint64_t total_q, uint64_t 
                 bool own_scores) {
     Workspace w{};
     size_t p = 0;
-    w.qcodes = p;   p += align_up((size_t)total_q * ix->cfg.L, 256);
+    w.qcodes = p;   p += align_up((size_t)total_q * ix->cfg.L * code_width(ix->cfg), 256);
     w.q_off = p;    p += align_up(((size_t)B + 1) * 4, 256);
     w.cand_off = p; p += align_up(((size_t)B + 1) * 8, 256);
     w.scores = p;   if (own_scores) p += align_up((size_t)total_scored * 4, 256);
@@ -177,9 +179,9 @@ dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, con
     out->q_off.assign(B + 1, 0);
     for (uint32_t b = 0; b < B; ++b) {
         if (q_lengths[b] == 0) return fail(DESSERT_EINVAL, "q_lengths_host[%u] = 0", b);
-        if ((uint64_t)q_lengths[b] * ix->cfg.L > 65535)
-            return fail(DESSERT_EINVAL, "q_lengths_host[%u] * L = %llu exceeds 65535", b,
-                        (unsigned long long)q_lengths[b] * ix->cfg.L);
+        if ((uint64_t)q_lengths[b] * ix->cfg.L * code_width(ix->cfg) > 65535)
+            return fail(DESSERT_EINVAL, "q_lengths_host[%u]: the query set's codes (%llu bytes) exceed 65535 bytes", b,
+                        (unsigned long long)q_lengths[b] * ix->cfg.L * code_width(ix->cfg));
         uint64_t nxt = (uint64_t)out->q_off[b] + q_lengths[b];
         if (nxt > 0xFFFFFFFFull) return fail(DESSERT_EINVAL, "more than 2^32-1 query vectors");
         out->q_off[b + 1] = (uint32_t)nxt;
@@ -273,7 +275,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
 
     ScoreArgs sa{};
     sa.codes = ix->codes; sa.offsets = ix->offsets; sa.n_docs = ix->n_docs;
-    sa.L = ix->cfg.L; sa.C = ix->cfg.C;
+    sa.L = ix->cfg.L; sa.C = ix->cfg.C; sa.code_bytes = code_width(ix->cfg);
     sa.qcodes = qcodes; sa.q_off = d_q_off; sa.q_uniform = bt.q_uniform; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
     sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr; sa.cand_uniform = cand_ids ? bt.cand_uniform : 0;
     sa.max_scored = bt.max_scored; sa.scores = scores;
@@ -285,7 +287,8 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
                                                                                 : DESSERT_SCORE_BYTECMP;
     if (algo == DESSERT_SCORE_MASKLUT) {
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
-            return fail(DESSERT_EINVAL, "mask-table scoring needs L in {16,32,64,128}");
+            return fail(DESSERT_EINVAL, "mask-table scoring needs L in {8,16,32,64,128} (C <= 8), or L = 8 with C <= 11, "
+                                        "L = 16 with C <= 10, L = 32 with C = 9");
         HIP_TRY(launch_score_masklut(sa, ix->stream));
     } else if (algo == DESSERT_SCORE_BYTECMP) {
         HIP_TRY(launch_score_bytecmp(sa, ix->stream));
@@ -341,7 +344,7 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
     if (!c || !out) return fail(DESSERT_EINVAL, "config or out is NULL");
     *out = nullptr;
     if (c->d == 0) return fail(DESSERT_EINVAL, "d must be >= 1");
-    if (c->C < 1 || c->C > 8) return fail(DESSERT_EINVAL, "C must be in 1..8 (codes are one byte), got %u", c->C);
+    if (c->C < 1 || c->C > 16) return fail(DESSERT_EINVAL, "C must be in 1..16, got %u", c->C);
     if (c->L < 4 || c->L > 128 || c->L % 4) return fail(DESSERT_EINVAL, "L must be a multiple of 4 in 4..128, got %u", c->L);
     if (c->dtype != DESSERT_I8 && c->dtype != DESSERT_F16) return fail(DESSERT_EINVAL, "unknown dtype %u", c->dtype);
     if (c->proj_kind != DESSERT_PROJ_RADEMACHER_I8 && c->proj_kind != DESSERT_PROJ_GAUSSIAN_F32)
@@ -447,7 +450,7 @@ dessert_status_t dessert_set_score_transform(dessert_index_t* ix, int transform)
 }
 
 size_t dessert_code_bytes(const dessert_index_t* ix, uint64_t n_vectors) {
-    return ix ? (size_t)n_vectors * ix->cfg.L : 0;
+    return ix ? (size_t)n_vectors * ix->cfg.L * code_width(ix->cfg) : 0;
 }
 
 dessert_status_t dessert_hash(const dessert_index_t* ix, const void* vectors_dev, uint64_t n, uint8_t* codes_dev) {

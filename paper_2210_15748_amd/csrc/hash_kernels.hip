@@ -40,10 +40,10 @@ hipError_t launch_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t* R, h
 // Generic kernel: one thread per (vector, table).  int8 x int8 accumulates in
 // int32 (exact), everything else in fp32 with fused multiply-add in index
 // order.
-template <typename XT, typename RT, typename AccT>
+template <typename XT, typename RT, typename AccT, typename CT>
 __global__ __launch_bounds__(256) void hash_scalar_kernel(const XT* __restrict__ X, uint64_t n, uint32_t d,
                                                           const RT* __restrict__ R, uint32_t L, uint32_t C,
-                                                          uint8_t* __restrict__ codes) {
+                                                          CT* __restrict__ codes) {
     uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n * L) return;
     uint64_t v = idx / L;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void hash_scalar_kernel(const XT* __restrict__
         }
         code |= (acc >= (AccT)0 ? 1u : 0u) << c;
     }
-    codes[idx] = (uint8_t)code;
+    codes[idx] = (CT)code;
 }
 
 hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
@@ -71,18 +71,25 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
     uint64_t blocks64 = (total + 255) / 256;
     if (blocks64 > 0x7fffffffull) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks64), block(256);
+    if (C < 1 || C > 16) return hipErrorInvalidValue;
+#define DESSERT_SCALAR_CASE(XT_, RT_, ACC_)                                                                            \
+    do {                                                                                                               \
+        if (C <= 8)                                                                                                    \
+            hipLaunchKernelGGL((hash_scalar_kernel<XT_, RT_, ACC_, uint8_t>), grid, block, 0, stream, (const XT_*)X, n, \
+                               d, (const RT_*)R, L, C, codes);                                                         \
+        else                                                                                                           \
+            hipLaunchKernelGGL((hash_scalar_kernel<XT_, RT_, ACC_, uint16_t>), grid, block, 0, stream, (const XT_*)X,  \
+                               n, d, (const RT_*)R, L, C, (uint16_t*)codes);                                           \
+    } while (0)
     if (dtype == 0 && proj_kind == 0)
-        hipLaunchKernelGGL((hash_scalar_kernel<int8_t, int8_t, int32_t>), grid, block, 0, stream, (const int8_t*)X, n, d,
-                           (const int8_t*)R, L, C, codes);
+        DESSERT_SCALAR_CASE(int8_t, int8_t, int32_t);
     else if (dtype == 0 && proj_kind == 1)
-        hipLaunchKernelGGL((hash_scalar_kernel<int8_t, float, float>), grid, block, 0, stream, (const int8_t*)X, n, d,
-                           (const float*)R, L, C, codes);
+        DESSERT_SCALAR_CASE(int8_t, float, float);
     else if (dtype == 1 && proj_kind == 0)
-        hipLaunchKernelGGL((hash_scalar_kernel<_Float16, int8_t, float>), grid, block, 0, stream, (const _Float16*)X, n,
-                           d, (const int8_t*)R, L, C, codes);
+        DESSERT_SCALAR_CASE(_Float16, int8_t, float);
     else
-        hipLaunchKernelGGL((hash_scalar_kernel<_Float16, float, float>), grid, block, 0, stream, (const _Float16*)X, n,
-                           d, (const float*)R, L, C, codes);
+        DESSERT_SCALAR_CASE(_Float16, float, float);
+#undef DESSERT_SCALAR_CASE
     return hipGetLastError();
 }
 

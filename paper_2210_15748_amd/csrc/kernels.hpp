@@ -25,7 +25,8 @@ bool hash_mfma_f16_supported(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
                                 uint8_t* codes, hipStream_t stream);
 
-// One thread per (vector, table); any d, L, C.  dtype/proj_kind as in dessert.h.
+// One thread per (vector, table); any d, L, C <= 16.  dtype/proj_kind as in dessert.h.  Codes are one byte
+// per table for C <= 8, else two.
 hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_t d, const void* R, uint32_t proj_kind,
                               uint32_t L, uint32_t C, uint8_t* codes, hipStream_t stream);
 
@@ -34,11 +35,12 @@ hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t stream);
 
 // ---- scoring (Alg. 2: collision counts, sigma = max, A = sum) ---------------
 struct ScoreArgs {
-    const uint8_t* codes;       // [V][L]
+    const uint8_t* codes;       // [V][L] codes of code_bytes bytes each
+    uint32_t code_bytes;        // 1 (C <= 8) or 2
     const uint64_t* offsets;    // [n_docs+1]
     uint64_t n_docs;
     uint32_t L, C;
-    const uint8_t* qcodes;      // [total_q][L]
+    const uint8_t* qcodes;      // [total_q][L], same code width
     const uint32_t* q_off;      // dev [B+1]; unused when q_uniform != 0
     uint32_t q_uniform;         // != 0: every query set has this many vectors (q_off[b] = b * q_uniform)
     uint32_t n_queries;

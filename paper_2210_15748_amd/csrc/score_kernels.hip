@@ -27,19 +27,26 @@ __device__ inline Span query_span(const ScoreArgs& a, uint32_t b) {
 }
 
 // ---------------------------------------------------------------------------
-// Byte-compare kernel (plain form, any L multiple of 4, any C <= 8).
+// Code-compare kernel (plain form; any L that makes a code row a multiple of 4 bytes).
+// CW = bytes per table code: 1 (C <= 8) or 2 (C <= 16).
 // One wave per scored document; lanes stride over the document's vectors.  For
-// each query vector the lane counts equal bytes four at a time: z = q ^ x has a
-// zero byte exactly where the codes agree, and
+// each query vector the lane counts equal codes one dword at a time: z = q ^ x has a
+// zero byte (halfword) exactly where the codes agree, and
 //     nz = (((z & 0x7f7f7f7f) + 0x7f7f7f7f) | z) & 0x80808080
-// has bit 7 of a byte set exactly where z's byte is non-zero.
+// has the top bit of a byte set exactly where z's byte is non-zero (0x7fff7fff / 0x80008000
+// for halfwords).
+template <int CW>
 __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
-    extern __shared__ uint32_t sq[];  // query set's codes, [mq][L/4]
+    extern __shared__ uint32_t sq[];  // query set's codes, [mq][row dwords]
+    constexpr uint32_t LOW = CW == 1 ? 0x7f7f7f7fu : 0x7fff7fffu;
+    constexpr uint32_t TOP = CW == 1 ? 0x80808080u : 0x80008000u;
+    constexpr int PER = 4 / CW;  // codes per dword
     const uint32_t b = blockIdx.y;
     const Span sp = query_span(a, b);
     const uint32_t q_lo = q_begin(a, b), mq = q_begin(a, b + 1) - q_lo;
-    const uint32_t LW = a.L / 4;
-    const uint32_t* qsrc = (const uint32_t*)(a.qcodes + (size_t)q_lo * a.L);
+    const uint32_t row = a.L * CW;  // bytes per code row
+    const uint32_t LW = row / 4;
+    const uint32_t* qsrc = (const uint32_t*)(a.qcodes + (size_t)q_lo * row);
     for (uint32_t i = threadIdx.x; i < mq * LW; i += blockDim.x) sq[i] = qsrc[i];
     __syncthreads();
 
@@ -55,12 +62,12 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
         for (uint32_t q = 0; q < mq; ++q) {
             int32_t best = 0;
             for (uint64_t j = lo + lane; j < hi; j += 64) {
-                const uint32_t* x = (const uint32_t*)(a.codes + j * a.L);
+                const uint32_t* x = (const uint32_t*)(a.codes + j * row);
                 int32_t cnt = 0;
                 for (uint32_t w = 0; w < LW; ++w) {
                     uint32_t z = x[w] ^ sq[q * LW + w];
-                    uint32_t nz = (((z & 0x7f7f7f7fu) + 0x7f7f7f7fu) | z) & 0x80808080u;
-                    cnt += 4 - __builtin_popcount(nz);
+                    uint32_t nz = (((z & LOW) + LOW) | z) & TOP;
+                    cnt += PER - __builtin_popcount(nz);
                 }
                 best = cnt > best ? cnt : best;
             }
@@ -76,11 +83,15 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
 
 hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
-    size_t lds = (size_t)a.max_q_len * a.L;
+    if ((a.code_bytes != 1 && a.code_bytes != 2) || (a.L * a.code_bytes) % 4) return hipErrorInvalidValue;
+    size_t lds = (size_t)a.max_q_len * a.L * a.code_bytes;
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     uint64_t bx = (a.max_scored + 3) / 4;
     if (bx > 4096) bx = 4096;
-    hipLaunchKernelGGL(score_bytecmp_kernel, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a);
+    if (a.code_bytes == 1)
+        hipLaunchKernelGGL(score_bytecmp_kernel<1>, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a);
+    else
+        hipLaunchKernelGGL(score_bytecmp_kernel<2>, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -175,6 +186,19 @@ __device__ inline uint32_t byte_shl(uint32_t dw, uint32_t sh) {
     return r;
 }
 
+// halfword K of dw shifted left by sh (16-bit codes)
+template <int K>
+__device__ inline uint32_t half_shl(uint32_t dw, uint32_t sh) {
+    uint32_t r;
+    if constexpr (K == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+            : "=v"(r) : "v"(sh), "v"(dw));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+            : "=v"(r) : "v"(sh), "v"(dw));
+    return r;
+}
+
 constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2); }
 
 constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
@@ -199,9 +223,10 @@ struct LutBlockMeta {
 // so one 8-byte LDS read serves 64 query vectors: a random 8-byte read costs about 6.8 cycles
 // per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
 // REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
-template <int LW, int CB, bool REMAP, int W>
+// CW = bytes per table code (1: C <= 8, 2: wider codes); CB = bits of a table index (2^CB entries per table).
+template <int L, int CB, int CW, bool REMAP, int W>
 __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear) {
-    constexpr int L = LW * 4;
+    constexpr int LW = L * CW / 4;  // dwords per code row
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
     constexpr int G = 8;
@@ -283,7 +308,8 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
             const uint32_t nq = c0 >= q_len[w] ? 0 : (q_len[w] - c0 < 32 ? q_len[w] - c0 : 32);
             for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
                 uint32_t q = i / L, t = i % L;
-                uint32_t h = a.qcodes[(size_t)(q_lo[w] + c0 + q) * L + t];
+                const size_t at = (size_t)(q_lo[w] + c0 + q) * L + t;
+                uint32_t h = CW == 1 ? (uint32_t)a.qcodes[at] : (uint32_t)((const uint16_t*)a.qcodes)[at];
                 atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
             }
         }
@@ -314,11 +340,18 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
             auto load_codes = [&](uint32_t j0, uint32_t (&dst)[LW]) {
                 uint32_t j = j0 + sub;
                 j = j < last_j ? j : last_j;
-                const v4i* src = (const v4i*)(a.codes + (lo + j) * L);
+                const uint8_t* row = a.codes + (lo + j) * (L * CW);
+                if constexpr (LW % 4 == 0) {
+                    const v4i* src = (const v4i*)row;
 #pragma unroll
-                for (int w = 0; w < LW; w += 4) {
-                    v4i v = src[w / 4];
-                    dst[w] = v.x; dst[w + 1] = v.y; dst[w + 2] = v.z; dst[w + 3] = v.w;
+                    for (int w = 0; w < LW; w += 4) {
+                        v4i v = src[w / 4];
+                        dst[w] = v.x; dst[w + 1] = v.y; dst[w + 2] = v.z; dst[w + 3] = v.w;
+                    }
+                } else {
+                    static_assert(LW % 4 == 0 || LW == 2, "code rows of 8 or a multiple of 16 bytes");
+                    uint2 v = *(const uint2*)row;
+                    dst[0] = v.x; dst[1] = v.y;
                 }
             };
             uint32_t nxt[LW];
@@ -332,10 +365,15 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
                 uint32_t off[L];  // byte offset of x's entry within each table
 #pragma unroll
                 for (int w = 0; w < LW; ++w) {
-                    off[4 * w + 0] = byte_shl<0>(dw[w], entry_shift);
-                    off[4 * w + 1] = byte_shl<1>(dw[w], entry_shift);
-                    off[4 * w + 2] = byte_shl<2>(dw[w], entry_shift);
-                    off[4 * w + 3] = byte_shl<3>(dw[w], entry_shift);
+                    if constexpr (CW == 1) {
+                        off[4 * w + 0] = byte_shl<0>(dw[w], entry_shift);
+                        off[4 * w + 1] = byte_shl<1>(dw[w], entry_shift);
+                        off[4 * w + 2] = byte_shl<2>(dw[w], entry_shift);
+                        off[4 * w + 3] = byte_shl<3>(dw[w], entry_shift);
+                    } else {
+                        off[2 * w + 0] = half_shl<0>(dw[w], entry_shift);
+                        off[2 * w + 1] = half_shl<1>(dw[w], entry_shift);
+                    }
                 }
                 uint32_t msk[W][L];
 #pragma unroll
@@ -411,15 +449,17 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     }
 }
 
+// One-byte codes: L in {8, 16, 32, 64, 128}.  16-bit codes: the L * 2^C * 4-byte table has to fit 64 KB of LDS.
 bool score_masklut_supported(uint32_t L, uint32_t C) {
-    return (L == 16 || L == 32 || L == 64 || L == 128) && C >= 1 && C <= 8;
+    if (C >= 1 && C <= 8) return L == 8 || L == 16 || L == 32 || L == 64 || L == 128;
+    return (L == 8 && C <= 11) || (L == 16 && C <= 10) || (L == 32 && C == 9);
 }
 
-template <int LW, int CB>
+template <int L, int CB, int CW>
 static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     // two query sets per workgroup when every document is scored for every set and the paired
     // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
-    constexpr bool PAIR_OK = (size_t)LW * 4 * (1u << CB) * 8 <= 32 * 1024;
+    constexpr bool PAIR_OK = (size_t)L * (1u << CB) * 8 <= 32 * 1024;
     const bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2;
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
     // workgroups, but at least 64 so the table build stays amortised
@@ -440,26 +480,30 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     }
     if constexpr (PAIR_OK) {
         if (pair) {
-            auto kern2 = a.remap ? score_masklut_kernel<LW, CB, true, 2> : score_masklut_kernel<LW, CB, false, 2>;
+            auto kern2 = a.remap ? score_masklut_kernel<L, CB, CW, true, 2> : score_masklut_kernel<L, CB, CW, false, 2>;
             hipLaunchKernelGGL(kern2, grid, dim3(256), 0, stream, a, dpb, gy_linear);
             return hipGetLastError();
         }
     }
-    auto kern = a.remap ? score_masklut_kernel<LW, CB, true, 1> : score_masklut_kernel<LW, CB, false, 1>;
+    auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1> : score_masklut_kernel<L, CB, CW, false, 1>;
     hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, a, dpb, gy_linear);
     return hipGetLastError();
 }
 
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream) {
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
-    if (!score_masklut_supported(a.L, a.C)) return hipErrorInvalidValue;
+    if (!score_masklut_supported(a.L, a.C) || a.code_bytes != (a.C > 8 ? 2u : 1u)) return hipErrorInvalidValue;
     const uint32_t cb = a.C <= 6 ? 6 : a.C;
-#define DESSERT_LUT_CASE(LW_, CB_) \
-    if (a.L == LW_ * 4 && cb == CB_) return launch_masklut_t<LW_, CB_>(a, stream);
-    DESSERT_LUT_CASE(4, 6) DESSERT_LUT_CASE(4, 7) DESSERT_LUT_CASE(4, 8)
-    DESSERT_LUT_CASE(8, 6) DESSERT_LUT_CASE(8, 7) DESSERT_LUT_CASE(8, 8)
-    DESSERT_LUT_CASE(16, 6) DESSERT_LUT_CASE(16, 7) DESSERT_LUT_CASE(16, 8)
-    DESSERT_LUT_CASE(32, 6) DESSERT_LUT_CASE(32, 7) DESSERT_LUT_CASE(32, 8)
+#define DESSERT_LUT_CASE(L_, CB_, CW_) \
+    if (a.L == L_ && cb == CB_) return launch_masklut_t<L_, CB_, CW_>(a, stream);
+    DESSERT_LUT_CASE(8, 6, 1) DESSERT_LUT_CASE(8, 7, 1) DESSERT_LUT_CASE(8, 8, 1)
+    DESSERT_LUT_CASE(16, 6, 1) DESSERT_LUT_CASE(16, 7, 1) DESSERT_LUT_CASE(16, 8, 1)
+    DESSERT_LUT_CASE(32, 6, 1) DESSERT_LUT_CASE(32, 7, 1) DESSERT_LUT_CASE(32, 8, 1)
+    DESSERT_LUT_CASE(64, 6, 1) DESSERT_LUT_CASE(64, 7, 1) DESSERT_LUT_CASE(64, 8, 1)
+    DESSERT_LUT_CASE(128, 6, 1) DESSERT_LUT_CASE(128, 7, 1) DESSERT_LUT_CASE(128, 8, 1)
+    DESSERT_LUT_CASE(8, 9, 2) DESSERT_LUT_CASE(8, 10, 2) DESSERT_LUT_CASE(8, 11, 2)
+    DESSERT_LUT_CASE(16, 9, 2) DESSERT_LUT_CASE(16, 10, 2)
+    DESSERT_LUT_CASE(32, 9, 2)
 #undef DESSERT_LUT_CASE
     return hipErrorInvalidValue;
 }

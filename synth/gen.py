@@ -67,6 +67,16 @@ PRESETS = {
 }
 
 
+def sweep_preset(m: int, n_queries: int = 16) -> Preset:
+    """The paper's synthetic experiment (Sec. 6.1): 1000 documents of exactly m vectors, queries are whole
+    documents with added noise, L = 8 tables of C = log2(m) + 1 one-bit hashes (m a power of two, 2..1024).
+    Stand-in for the GloVe vectors used there: the same clustered int8 vectors as the other presets."""
+    if m < 2 or m > 1024 or m & (m - 1):
+        raise ValueError("m must be a power of two in 2..1024")
+    return Preset(f"sweep_m{m}", 6, 1_000, "const", (m,), 128, "i8", 1024, 0.3,
+                  8, int(math.log2(m)) + 1, "rademacher", n_queries, m, 0.2, 1, 0, 10)
+
+
 @dataclasses.dataclass
 class Workload:
     preset: Preset
@@ -164,10 +174,11 @@ def draw_projection(p: Preset, seed: int, device) -> torch.Tensor:
     return torch.randn(P, p.d, generator=g, dtype=torch.float32).to(device)
 
 
-def make(cfg: int, device="cpu", n_docs: Optional[int] = None, n_queries: Optional[int] = None,
+def make(cfg, device="cpu", n_docs: Optional[int] = None, n_queries: Optional[int] = None,
          n_cand: Optional[int] = None, seed_base: Optional[int] = None) -> Workload:
-    """Build preset ``cfg``; ``n_docs`` / ``n_queries`` / ``n_cand`` shrink it for tests."""
-    p = dataclasses.replace(PRESETS[cfg])
+    """Build preset ``cfg`` (a number, or a Preset such as sweep_preset(m)); ``n_docs`` / ``n_queries`` /
+    ``n_cand`` shrink it for tests."""
+    p = dataclasses.replace(cfg if isinstance(cfg, Preset) else PRESETS[cfg])
     if n_docs is not None:
         p.n_docs = int(n_docs)
     if n_queries is not None:

@@ -36,7 +36,7 @@ def test_create_rejects_bad_configs_before_touching_a_device():
         cfg = dz.Config(**base)
         return l.dessert_create(C.byref(cfg), C.byref(h))
 
-    assert status(C=9) == dz.EINVAL and "C must be" in dz.last_error()
+    assert status(C=17) == dz.EINVAL and "C must be" in dz.last_error()
     assert status(C=0) == dz.EINVAL
     assert status(L=30) == dz.EINVAL and "multiple of 4" in dz.last_error()
     assert status(L=132) == dz.EINVAL
