@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="preset number (3 = candidate rerank, the metric's workload)")
+    ap.add_argument("--sweep-m", type=int, default=None,
+                    help="run the synthetic-experiment shape instead of a preset: 1000 documents of m vectors, L = 8, "
+                         "C = log2(m) + 1, queries = noisy documents (not the metric's workload)")
     ap.add_argument("--n-docs", type=int, default=None, help="shrink the preset (for quick trials; not the metric)")
     ap.add_argument("--n-queries", type=int, default=None)
     ap.add_argument("--build-reps", type=int, default=5)
@@ -89,7 +92,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
 
     t0 = time.time()
-    w = gen.make(args.config, device=dev, n_docs=args.n_docs, n_queries=args.n_queries)
+    which = gen.sweep_preset(args.sweep_m) if args.sweep_m else args.config
+    w = gen.make(which, device=dev, n_docs=args.n_docs, n_queries=args.n_queries)
     p = w.preset
     torch.cuda.synchronize()
     log(f"[bench] generated {p.name}: N={w.n_docs} V={w.n_vectors} B={p.n_queries} in {time.time() - t0:.1f}s")
@@ -101,7 +105,7 @@ def main() -> int:
     dz.enable_timing(ix, True)
 
     # ---- index build (H1-H3), timed on its own
-    codes = torch.empty(w.n_vectors, p.L, dtype=torch.uint8, device=dev)
+    codes = torch.empty(w.n_vectors, p.L, dtype=dz.code_dtype(ix), device=dev)
     offsets = torch.empty(w.n_docs + 1, dtype=torch.int64, device=dev)
     lengths = w.lengths.numpy().astype(np.uint32)
     dz.build_index(ix, w.docs, lengths, codes, offsets)          # warm-up + the index used below
@@ -147,7 +151,7 @@ def main() -> int:
 
     # ---- candidate filter (Sec. 5 "Filtering") in front of the same search: reported beside the metric, not part of it
     filt = None
-    if args.config == 3 and p.dtype == "i8" and not args.no_filter:
+    if args.config == 3 and not args.sweep_m and p.dtype == "i8" and not args.no_filter:
         def ev_ms(fn, reps):
             fn()
             torch.cuda.synchronize()
@@ -198,14 +202,14 @@ def main() -> int:
     # ---- roofline of the dominant kernel (scoring): algorithmic bytes = code bytes of every scored document
     if cand is not None:
         doc_len = w.lengths.to(dev)[w.cand_ids.reshape(-1)]
-        code_bytes = int(doc_len.sum().item()) * p.L
+        code_bytes = int(doc_len.sum().item()) * p.L * codes.element_size()
     else:
-        code_bytes = w.n_vectors * p.L * B      # each query set reads every document's codes once
+        code_bytes = w.n_vectors * p.L * codes.element_size() * B      # each query set reads every document's codes once
     achieved = code_bytes / (score_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "score_masklut_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic_from_profile("score_masklut_kernel")
-                if (args.config == 3 and args.n_docs is None and args.n_queries is None) else None,
+                if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None) else None,
                 "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5),
                 "measured_stream_read_GBs": round(read_gbs, 1), "frac_of_measured_stream": round(achieved / read_gbs, 4)}
 

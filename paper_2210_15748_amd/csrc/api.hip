@@ -126,7 +126,8 @@ dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, ui
     if (algo == DESSERT_HASH_MFMA) {
         if (!use_mfma(ix))
             return fail(DESSERT_EINVAL, "MFMA hashing needs int8 vectors with +-1 projections or fp16 vectors with "
-                                        "Gaussian projections, d in {64,128,256}, L in {16,32,64}");
+                                        "Gaussian projections, d in {64,128,256}, L in {16,32,64} (int8 also L = 8, and 16-bit codes with "
+                                        "L in {8,16,32})");
         if (!aligned) return fail(DESSERT_EINVAL, "MFMA hashing needs 16-byte aligned vectors and codes");
         if (ix->cfg.dtype == DESSERT_I8)
             HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
@@ -278,7 +279,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     sa.L = ix->cfg.L; sa.C = ix->cfg.C; sa.code_bytes = code_width(ix->cfg);
     sa.qcodes = qcodes; sa.q_off = d_q_off; sa.q_uniform = bt.q_uniform; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
     sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr; sa.cand_uniform = cand_ids ? bt.cand_uniform : 0;
-    sa.max_scored = bt.max_scored; sa.scores = scores;
+    sa.max_scored = bt.max_scored; sa.total_scored = bt.total_scored; sa.n_vectors = ix->n_vectors; sa.scores = scores;
     sa.remap = ix->transform == DESSERT_SCORE_EQ1_Q16 ? ix->remap : nullptr;
     int algo = ix->score_algo;
     // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
@@ -376,7 +377,7 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
     else
         e = launch_rademacher(c->seed, (uint32_t)P, c->d, (int8_t*)ix->proj, ix->stream);
     if (e == hipSuccess && is_i8_mfma(*c)) {
-        e = hipMalloc(&ix->proj_mfma, mfma_proj_bytes(c->d, c->L));
+        e = hipMalloc(&ix->proj_mfma, mfma_proj_bytes(c->d, c->L, c->C));
         if (e == hipSuccess) e = launch_repack_proj_i8((const int8_t*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
     } else if (e == hipSuccess && is_f16_mfma(*c)) {
         e = hipMalloc(&ix->proj_mfma, mfma_f16_proj_bytes(c->d, c->L));

@@ -114,13 +114,18 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
 // The re-ordered matrix ([LT][KS][64 lanes][16 B], LT = L/4 M-tiles, KS = d/32
 // k-steps) is staged in LDS once per workgroup; each wave then loops over
 // tiles of 32*NT vectors, reading every A fragment once per NT MFMAs.
-template <int KS, int LT, int NT>
+//
+// WIDE (9 <= C <= 16, 16-bit codes): an M-tile holds 2 tables of 16 bit rows instead of 4 tables of
+// 8; register r of lane-half g is bit r of table g*(L/2) + mt, so a lane's 16 accumulators of one
+// M-tile make one code.  A code row is LT*4 bytes either way (LT = L/4 M-tiles, or L/2 when WIDE)
+// and lane-half g owns the g-th half of it.
+template <int KS, int LT, int NT, bool WIDE>
 __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restrict__ X, uint64_t n,
                                                            const v4i* __restrict__ Rp, uint32_t cmask,
                                                            uint8_t* __restrict__ codes) {
     constexpr int D = KS * 32;
-    constexpr int L = LT * 4;
-    constexpr int OW = LT / 2;  // output dwords per lane (L/2 bytes)
+    constexpr int L = LT * 4;   // bytes per code row
+    constexpr int OW = LT / 2;  // output dwords per lane (half a code row)
     extern __shared__ v4i sR[];
     for (int i = threadIdx.x; i < LT * KS * 64; i += 256) sR[i] = Rp[i];
     __syncthreads();
@@ -171,17 +176,26 @@ __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restr
                         acc[nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[nt][ks], acc[nt], 0, 0, 0);
                 }
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+                for (int nt = 0; nt < NT; ++nt) {
+                    // shift in the sign bits, most significant code bit first: neg = sum_c [p_c < 0] << c
+                    if constexpr (!WIDE) {
 #pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        // shift in the sign bits, most significant code bit first: neg = sum_c [p_c < 0] << c
+                        for (int s = 0; s < 2; ++s) {
+                            uint32_t neg = 0;
+#pragma unroll
+                            for (int c = 7; c >= 0; --c)
+                                neg = __builtin_amdgcn_alignbit(neg, (uint32_t)acc[nt][8 * s + c], 31);
+                            uint32_t code = ~neg & cmask;  // bit = [p >= 0]
+                            word[nt] |= code << (8 * (2 * h + s));
+                        }
+                    } else {
                         uint32_t neg = 0;
 #pragma unroll
-                        for (int c = 7; c >= 0; --c)
-                            neg = __builtin_amdgcn_alignbit(neg, (uint32_t)acc[nt][8 * s + c], 31);
-                        uint32_t code = ~neg & cmask;  // bit = [p >= 0]
-                        word[nt] |= code << (8 * (2 * h + s));
+                        for (int c = 15; c >= 0; --c) neg = __builtin_amdgcn_alignbit(neg, (uint32_t)acc[nt][c], 31);
+                        uint32_t code = ~neg & cmask;
+                        word[nt] |= code << (16 * h);
                     }
+                }
             }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
@@ -221,28 +235,41 @@ __global__ void repack_proj_i8_kernel(const int8_t* __restrict__ R, uint32_t d, 
     uint32_t mt = (idx >> 10) / KS;
     uint32_t i = l & 31;            // row of the M-tile
     uint32_t kk = ks * 32 + 16 * (l >> 5) + e;
-    uint32_t g = (i >> 2) & 1;
-    uint32_t s = i >> 4;
-    uint32_t c = 4 * ((i >> 3) & 1) + (i & 3);
-    uint32_t t = g * (L / 2) + 2 * mt + s;
+    uint32_t g = (i >> 2) & 1;                // lane half that receives the row
+    uint32_t r = 4 * (i >> 3) + (i & 3);      // its accumulator register
+    uint32_t t, c;
+    if (C <= 8) {  // 4 tables of 8 bit rows
+        t = g * (L / 2) + 2 * mt + (r >> 3);
+        c = r & 7;
+    } else {       // 2 tables of 16 bit rows
+        t = g * (L / 2) + mt;
+        c = r;
+    }
     Rp[idx] = (c < C) ? R[(size_t)(t * C + c) * d + kk] : (int8_t)0;
 }
 
+// M-tiles of 32 projection rows: L/4 with one-byte codes, L/2 with 16-bit codes
+static uint32_t mfma_tiles(uint32_t L, uint32_t C) { return C <= 8 ? L / 4 : L / 2; }
+
+// shapes of the fp16 kernel (one-byte codes only)
 static bool mfma_shape(uint32_t d, uint32_t L) {
     return (d == 64 || d == 128 || d == 256) && (L == 16 || L == 32 || L == 64);
 }
 
-size_t mfma_proj_bytes(uint32_t d, uint32_t L) {
-    if (!mfma_shape(d, L)) return 0;
-    return (size_t)(L / 4) * (d / 32) * 64 * 16;
+size_t mfma_proj_bytes(uint32_t d, uint32_t L, uint32_t C) {
+    if (!hash_mfma_supported(d, L, C)) return 0;
+    return (size_t)mfma_tiles(L, C) * (d / 32) * 64 * 16;
 }
 
 bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C) {
-    return mfma_shape(d, L) && C >= 1 && C <= 8 && mfma_proj_bytes(d, L) <= 64 * 1024;
+    if (!(d == 64 || d == 128 || d == 256) || C < 1 || C > 16) return false;
+    if (!(L == 8 || L == 16 || L == 32 || (L == 64 && C <= 8))) return false;
+    const uint32_t lt = mfma_tiles(L, C);  // 2, 4, 8 or 16
+    return (size_t)lt * (d / 32) * 1024 <= 64 * 1024;
 }
 
 hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
-    uint32_t total = (uint32_t)mfma_proj_bytes(d, L);
+    uint32_t total = (uint32_t)mfma_proj_bytes(d, L, C);
     if (!total) return hipErrorInvalidValue;
     hipLaunchKernelGGL(repack_proj_i8_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, R, d, L, C, (int8_t*)Rp,
                        total);
@@ -257,9 +284,15 @@ static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const v
     uint64_t blocks = (n_tiles + 3) / 4;
     if (blocks > 1024) blocks = 1024;  // persistent waves: 256 CUs x 4 workgroups
     size_t lds = (size_t)LT * KS * 64 * 16;
-    auto kern = hash_mfma_i8_kernel<KS, LT, NT>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
-                       codes);
+    if (C <= 8) {
+        auto kern = hash_mfma_i8_kernel<KS, LT, NT, false>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
+                           codes);
+    } else {
+        auto kern = hash_mfma_i8_kernel<KS, LT, NT, true>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
+                           codes);
+    }
     return hipGetLastError();
 }
 
@@ -267,14 +300,18 @@ hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t
                                uint8_t* codes, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
+    const uint32_t lt = mfma_tiles(L, C);
 #define DESSERT_MFMA_CASE(KS_, LT_) \
-    if (d == KS_ * 32 && L == LT_ * 4) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, stream);
+    if (d == KS_ * 32 && lt == LT_) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, stream);
+    DESSERT_MFMA_CASE(2, 2)
     DESSERT_MFMA_CASE(2, 4)
     DESSERT_MFMA_CASE(2, 8)
     DESSERT_MFMA_CASE(2, 16)
+    DESSERT_MFMA_CASE(4, 2)
     DESSERT_MFMA_CASE(4, 4)
     DESSERT_MFMA_CASE(4, 8)
     DESSERT_MFMA_CASE(4, 16)
+    DESSERT_MFMA_CASE(8, 2)
     DESSERT_MFMA_CASE(8, 4)
     DESSERT_MFMA_CASE(8, 8)
 #undef DESSERT_MFMA_CASE

@@ -11,8 +11,8 @@ namespace dessert {
 // Fill R [P][d] with the seed-derived Rademacher matrix.
 hipError_t launch_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t* R, hipStream_t stream);
 
-// Bytes of the MFMA-ordered copy of an int8 projection matrix, 0 if (d, L) has no MFMA kernel.
-size_t mfma_proj_bytes(uint32_t d, uint32_t L);
+// Bytes of the MFMA-ordered copy of an int8 projection matrix, 0 if (d, L, C) has no MFMA kernel.
+size_t mfma_proj_bytes(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream);
 bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
@@ -49,6 +49,8 @@ struct ScoreArgs {
     const uint64_t* cand_off;   // dev [B+1] (candidate mode); unused when cand_uniform != 0
     uint64_t cand_uniform;      // != 0: every candidate list has this many ids
     uint64_t max_scored;        // largest number of documents scored by one query set
+    uint64_t total_scored;      // all output slots (candidate mode: sum of the list lengths)
+    uint64_t n_vectors;         // vectors in the index (launch heuristics only)
     int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
     const uint32_t* remap;      // dev [L+1] fixed-point similarity per collision count (Eq. 1), or nullptr: raw counts
 };

@@ -202,6 +202,9 @@ __device__ inline uint32_t half_shl(uint32_t dw, uint32_t sh) {
 constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2); }
 
 constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
+// Threads per workgroup: a mask table of 32 KB or more limits a CU to a few workgroups, so (where the
+// register budget allows: few tables) eight waves share one table instead of four.
+constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && L <= 16) ? 512 : 256; }
 constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
 
 // Per-workgroup bookkeeping placed after the mask table in dynamic LDS.
@@ -224,8 +227,14 @@ struct LutBlockMeta {
 // per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
 // REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
 // CW = bytes per table code (1: C <= 8, 2: wider codes); CB = bits of a table index (2^CB entries per table).
-template <int L, int CB, int CW, bool REMAP, int W>
-__global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear) {
+// gz = chunk groups: with gz > 1 the 32-vector chunks of a query set are dealt round-robin to gz
+// workgroups, which add their partial sums into the (pre-zeroed) scores with integer atomics.
+// (SPLIT = false: gz is 1.)
+template <int L, int CB, int CW, bool REMAP, int W, bool SPLIT>
+__global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
+                                                            uint32_t gz_arg) {
+    const uint32_t gz = SPLIT ? gz_arg : 1u;
+    constexpr int T = masklut_threads(L, CB, W);
     constexpr int LW = L * CW / 4;  // dwords per code row
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
@@ -249,6 +258,8 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
         bx_idx = blockIdx.x;
         by_idx = blockIdx.y;
     }
+    const uint32_t cz = SPLIT ? by_idx % gz : 0u;  // chunk group
+    if constexpr (SPLIT) by_idx /= gz;
     const uint32_t b0 = by_idx * W;     // first query set of this workgroup
     const Span sp = query_span(a, b0);  // W > 1: every set scores the same documents
     const uint64_t first = (uint64_t)bx_idx * docs_per_block;
@@ -267,7 +278,7 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     const uint32_t grp = lane / G;        // group within the wave
 
     // ---- where each document lives, and the length-class ordering
-    for (uint32_t i = threadIdx.x; i < LUT_BINS; i += 256) meta.bin[i] = 0;
+    for (uint32_t i = threadIdx.x; i < LUT_BINS; i += T) meta.bin[i] = 0;
     __syncthreads();
     uint32_t my_class = 0;
     if (threadIdx.x < ndocs) {
@@ -298,15 +309,15 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
     if (threadIdx.x < ndocs) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
 
     const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
-    for (uint32_t c0 = 0; c0 < max_len; c0 += 32) {  // chunks of 32 query vectors
+    for (uint32_t c0 = cz * 32; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
         __syncthreads();  // previous chunk's readers are done (and `order` is complete)
-        for (uint32_t i = threadIdx.x; i < L * STRIDE * W; i += 256) lut[i] = 0;
+        for (uint32_t i = threadIdx.x; i < L * STRIDE * W; i += T) lut[i] = 0;
         if (threadIdx.x == 0) meta.next = 0;
         __syncthreads();
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             const uint32_t nq = c0 >= q_len[w] ? 0 : (q_len[w] - c0 < 32 ? q_len[w] - c0 : 32);
-            for (uint32_t i = threadIdx.x; i < nq * L; i += 256) {
+            for (uint32_t i = threadIdx.x; i < nq * L; i += T) {
                 uint32_t q = i / L, t = i % L;
                 const size_t at = (size_t)(q_lo[w] + c0 + q) * L + t;
                 uint32_t h = CW == 1 ? (uint32_t)a.qcodes[at] : (uint32_t)((const uint16_t*)a.qcodes)[at];
@@ -437,16 +448,32 @@ __global__ __launch_bounds__(256) void score_masklut_kernel(ScoreArgs a, uint32_
                 if (valid && sub == 0 && b0 + w < a.n_queries && c0 < q_len[w]) {
                     // W > 1 implies every set scores every document: set b0+w starts at (b0+w)*n_docs
                     int32_t* dst = a.scores + (W == 1 ? sp.base : (uint64_t)(b0 + w) * a.n_docs) + first + doc;
-                    if (W == 1 && m == 0 && meta.lo[doc] == ~0ull)
-                        *dst = -1;  // empty candidate slot
-                    else if (c0 == 0)
+                    if (W == 1 && m == 0 && meta.lo[doc] == ~0ull) {
+                        if (c0 == 0) *dst = -1;  // empty candidate slot
+                    } else if (SPLIT) {
+                        if (score) atomicAdd(dst, score);
+                    } else if (c0 == 0) {
                         *dst = score;
-                    else
+                    } else {
                         *dst += score;
+                    }
                 }
             }
         }
     }
+}
+
+__global__ void fill_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+static hipError_t launch_fill_zero(int32_t* p, uint64_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    uint64_t blocks = (n + 1023) / 1024;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, n);
+    return hipGetLastError();
 }
 
 // One-byte codes: L in {8, 16, 32, 64, 128}.  16-bit codes: the L * 2^C * 4-byte table has to fit 64 KB of LDS.
@@ -460,33 +487,61 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     // two query sets per workgroup when every document is scored for every set and the paired
     // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
     constexpr bool PAIR_OK = (size_t)L * (1u << CB) * 8 <= 32 * 1024;
-    const bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2;
+    bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2;
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
-    // workgroups, but at least 64 so the table build stays amortised
-    const uint32_t gy = pair ? (a.n_queries + 1) / 2 : a.n_queries;
+    // workgroups, but at least 64 (32 = one run of 8 documents for each of the four waves when the
+    // documents are long: about 4096 vectors per workgroup keep the table build amortised)
+    uint32_t gy = pair ? (a.n_queries + 1) / 2 : a.n_queries;
+    const uint64_t mean_len = a.n_docs ? (a.n_vectors + a.n_docs - 1) / a.n_docs : 1;
+    const uint32_t wave_docs = masklut_threads(L, CB, pair ? 2 : 1) / 64 * 8;  // one run of 8 documents per wave
+    uint32_t dpb_min = wave_docs > 64 ? wave_docs : 64;
+    while (dpb_min > wave_docs && (uint64_t)(dpb_min / 2) * mean_len >= 4096) dpb_min /= 2;
     uint32_t dpb = LUT_DOCS;
-    while (dpb > 64 && ((a.max_scored + dpb - 1) / dpb) * gy < 4096) dpb /= 2;
+    while (dpb > dpb_min && ((a.max_scored + dpb - 1) / dpb) * gy < 4096) dpb /= 2;
     uint64_t bx = (a.max_scored + dpb - 1) / dpb;
     if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
+    // long query sets on a grid that is still small: split the 32-vector chunks over gz workgroups
+    const uint32_t chunks = (a.max_q_len + 31) / 32;
+    uint32_t gz = 1;
+    if (chunks > 1 && bx * gy < 2048) {
+        pair = false;  // the split kernels take one query set per workgroup
+        gy = a.n_queries;
+        gz = (uint32_t)((2048 + bx * gy - 1) / (bx * gy));
+        if (gz > chunks) gz = chunks;
+        if (gz < 2) gz = 2;
+    }
+    const uint64_t gyz = (uint64_t)gy * gz;
+    if (gyz > 65535) return hipErrorInvalidValue;
+    if (gz > 1) {  // partial sums are added into the scores
+        const uint64_t n = a.cand_ids ? a.total_scored : (uint64_t)a.n_queries * a.n_docs;
+        hipError_t e = launch_fill_zero(a.scores, n, stream);
+        if (e != hipSuccess) return e;
+    }
     // exhaustive mode: linear grid with the XCD-aware decode (document blocks rounded up to 8)
-    dim3 grid((unsigned)bx, gy);
+    dim3 grid((unsigned)bx, (unsigned)gyz);
     uint32_t gy_linear = 0;
     if (a.cand_ids == nullptr) {
-        const uint64_t total = (bx + 7) / 8 * 8 * gy;
+        const uint64_t total = (bx + 7) / 8 * 8 * gyz;
         if (total <= 0x7fffffffull) {
             grid = dim3((unsigned)total);
-            gy_linear = gy;
+            gy_linear = (uint32_t)gyz;
         }
     }
     if constexpr (PAIR_OK) {
         if (pair) {
-            auto kern2 = a.remap ? score_masklut_kernel<L, CB, CW, true, 2> : score_masklut_kernel<L, CB, CW, false, 2>;
-            hipLaunchKernelGGL(kern2, grid, dim3(256), 0, stream, a, dpb, gy_linear);
+            auto kern2 = a.remap ? score_masklut_kernel<L, CB, CW, true, 2, false>
+                                 : score_masklut_kernel<L, CB, CW, false, 2, false>;
+            hipLaunchKernelGGL(kern2, grid, dim3(masklut_threads(L, CB, 2)), 0, stream, a, dpb, gy_linear, 1u);
             return hipGetLastError();
         }
     }
-    auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1> : score_masklut_kernel<L, CB, CW, false, 1>;
-    hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, a, dpb, gy_linear);
+    if (gz > 1) {
+        auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1, true> : score_masklut_kernel<L, CB, CW, false, 1, true>;
+        hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, gz);
+        return hipGetLastError();
+    }
+    auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1, false> : score_masklut_kernel<L, CB, CW, false, 1, false>;
+    hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, 1u);
     return hipGetLastError();
 }
 

@@ -43,6 +43,24 @@ def test_hash_wide_and_l8_bit_exact(d, L, Cb, n):
                           orc.hash_i8(X, orc.rademacher(99, L * Cb, d), L, Cb))
 
 
+@pytest.mark.parametrize("algo", [dz.HASH_SCALAR, dz.HASH_MFMA])
+@pytest.mark.parametrize("d,L,Cb", [(128, 8, 11), (128, 8, 9), (64, 8, 16), (256, 8, 10), (128, 16, 12), (64, 32, 9),
+                                    (128, 32, 16), (256, 16, 13), (128, 8, 1), (64, 8, 8), (256, 8, 5), (128, 8, 7)])
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4099])
+def test_hash_mfma_wide_and_l8_shapes(algo, d, L, Cb, n):
+    say(f"hash algo={algo} d={d} L={L} C={Cb} n={n}")
+    rng = np.random.default_rng(d + L + Cb + n)
+    X = rng.integers(-127, 128, (n, d)).astype(np.int8)
+    X[0] = 0
+    if n > 2:
+        X[2] = -X[1]
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, algo, dz.SCORE_AUTO)
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    assert np.array_equal(got, orc.hash_i8(X, R, L, Cb))
+
+
 def test_hash_wide_fp16_gaussian_within_tolerance():
     say("hash fp16/gaussian L=8 C=11")
     rng = np.random.default_rng(3)
