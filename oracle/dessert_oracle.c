@@ -276,6 +276,64 @@ void oracle_scores_wide(const uint16_t *doc_codes, const int64_t *offsets, uint3
     free(sim);
 }
 
+/* ---- other inner aggregations and a weighted outer aggregation (Sec. 4.1, the lemma on
+ * sigma(x) = (1/m) sum_i phi(x_i); Sec. 4.2, F(Q,S) = (1/m_q) sum_j w_j sigma(s_hat(q_j, S))).
+ * Alg. 2 in the paper's order: s_hat = count / L  ->  phi  ->  sigma over the document's vectors
+ * ->  weighted sum over the query vectors.
+ *   phi: 0 identity phi(x) = x;  1 phi(x) = e^x - 1;  2 debiased sigmoid 1/(1+e^-x) - 1/2
+ *        (the three examples the paper gives for that lemma);  3 the similarity remap of Eq. 1
+ *        with C = eq1_C, phi(x) = x^(1/C) (Sec. 5; phi(0) = 0);
+ *   sigma: 0 max over the document's vectors, 1 mean (1/m) sum.
+ * Number format (reading taken here; the paper fixes none): phi(s_hat) enters as the integer
+ * round(65536 * phi) (llround); the mean is the integer (sum + floor(m/2)) / m (round half up; an
+ * empty document gives 0); a weight is an integer w in [0, 65536] standing for w / 65536 and a
+ * query vector contributes (w * sigma + 32768) >> 16, which is sigma itself for w = 65536 and when
+ * weights is NULL.  The division by m_q of Sec. 4.2 is left out (same ranking).
+ * code_bytes = 1 or 2 selects the code width.
+ */
+void oracle_scores_general(const void *doc_codes, const int64_t *offsets, uint32_t L, uint32_t code_bytes,
+                           uint32_t phi, uint32_t eq1_C, uint32_t sigma, const void *q_codes, uint32_t mq,
+                           const uint32_t *weights, const int64_t *doc_ids, uint64_t n_scored, int32_t *scores,
+                           double *phi_table)
+{
+    int64_t *T = (int64_t *)malloc((L + 1) * sizeof(int64_t));
+    for (uint32_t c = 0; c <= L; ++c) {
+        double s_hat = (double)c / (double)L;                       /* Alg. 2: s_hat / L */
+        double y = phi == 0 ? s_hat
+                 : phi == 1 ? exp(s_hat) - 1.0
+                 : phi == 2 ? 1.0 / (1.0 + exp(-s_hat)) - 0.5
+                 : (c == 0 ? 0.0 : exp(log(s_hat) / (double)eq1_C));    /* Eq. 1 */
+        if (phi_table)
+            phi_table[c] = y;
+        T[c] = llround(65536.0 * y);
+    }
+    const uint8_t *d8 = (const uint8_t *)doc_codes, *q8 = (const uint8_t *)q_codes;
+    const uint16_t *d16 = (const uint16_t *)doc_codes, *q16 = (const uint16_t *)q_codes;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t s = 0; s < (int64_t)n_scored; ++s) {
+        int64_t i = doc_ids ? doc_ids[s] : s;
+        int64_t lo = offsets[i], hi = offsets[i + 1], m = hi - lo;
+        int64_t score = 0;
+        for (uint32_t q = 0; q < mq; ++q) {
+            int64_t best = 0, sum = 0;
+            for (int64_t j = lo; j < hi; ++j) {
+                int32_t cnt = 0;
+                for (uint32_t t = 0; t < L; ++t)
+                    cnt += code_bytes == 1 ? (q8[(size_t)q * L + t] == d8[(size_t)j * L + t])
+                                           : (q16[(size_t)q * L + t] == d16[(size_t)j * L + t]);
+                int64_t y = T[cnt];                                  /* phi(s_hat) in Q16 */
+                if (y > best)
+                    best = y;
+                sum += y;
+            }
+            int64_t sg = sigma == 0 ? best : (m ? (sum + m / 2) / m : 0);
+            score += weights ? (((int64_t)weights[q] * sg + 32768) >> 16) : sg;
+        }
+        scores[s] = (int32_t)score;
+    }
+    free(T);
+}
+
 /* ---- top-k: Alg. 2 last line (argmax), widened to the k best.
  * Order: score descending, then document id ascending.  ids may be NULL
  * (then the id of entry s is s).  Missing slots (n < k) get id 0xFFFFFFFF,

@@ -144,6 +144,41 @@ def scores_eq1(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, 
     return (out, table) if want_table else out
 
 
+PHI_IDENTITY, PHI_EXPM1, PHI_SIGMOID, PHI_EQ1 = 0, 1, 2, 3
+SIGMA_MAX, SIGMA_MEAN = 0, 1
+
+
+def scores_general(doc_codes: np.ndarray, offsets: np.ndarray, q_codes: np.ndarray, phi: int, sigma: int,
+                   weights=None, doc_ids=None, want_table: bool = False, eq1_C: int = 1):
+    """Alg. 2 with sigma = max or mean of phi(count / L) and a weighted sum over the query vectors, in Q16
+    (see oracle_scores_general).  weights: integers in [0, 65536], one per query vector, or None."""
+    wide = np.asarray(doc_codes).dtype == np.uint16
+    dt = np.uint16 if wide else np.uint8
+    doc_codes = np.ascontiguousarray(doc_codes, dtype=dt)
+    q_codes = np.ascontiguousarray(q_codes, dtype=dt)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    L = q_codes.shape[1]
+    assert doc_codes.ndim == 2 and doc_codes.shape[1] == L and offsets[-1] <= doc_codes.shape[0]
+    n_docs = offsets.shape[0] - 1
+    if doc_ids is None:
+        n, ids = n_docs, None
+    else:
+        ids = np.ascontiguousarray(doc_ids, dtype=np.int64)
+        n = ids.shape[0]
+        assert n == 0 or (ids.min() >= 0 and ids.max() < n_docs)
+    w = None
+    if weights is not None:
+        w = np.ascontiguousarray(weights, dtype=np.uint32)
+        assert w.shape == (q_codes.shape[0],) and (w.size == 0 or w.max() <= 65536)
+    out = np.empty(n, dtype=np.int32)
+    table = np.empty(L + 1, dtype=np.float64) if want_table else None
+    lib().oracle_scores_general(_p(doc_codes), _p(offsets), C.c_uint32(L), C.c_uint32(2 if wide else 1),
+                                C.c_uint32(phi), C.c_uint32(eq1_C), C.c_uint32(sigma), _p(q_codes),
+                                C.c_uint32(q_codes.shape[0]),
+                                _p(w), _p(ids), C.c_uint64(n), _p(out), _p(table))
+    return (out, table) if want_table else out
+
+
 def assign_centroids(X: np.ndarray, centroids: np.ndarray) -> np.ndarray:
     X = np.ascontiguousarray(X, dtype=np.int8)
     centroids = np.ascontiguousarray(centroids, dtype=np.int8)

@@ -40,6 +40,8 @@ def load_hand():
         if not line or line.startswith("#"):
             continue
         tag, rest = line[0], line[1:]
+        if tag == "G":          # other aggregations: read by tests/test_oracle_aggregation_pins.py
+            continue
         parts = [[int(t) for t in p.split()] for p in rest.split("|")]
         if tag == "R":
             R.append(parts[0])
