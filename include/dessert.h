@@ -112,9 +112,34 @@ dessert_status_t dessert_set_algo(dessert_index_t *index, int hash_algo, int sco
  *     integers over the query vectors.  score / (65536 * |Q|) is the paper's "average of max
  *     similarities" (Sec. 6, experiment setup).  Integer sums keep the result independent of
  *     summation order.  Needs |Q| <= 16383.
+ *   DESSERT_SCORE_MAX_* / DESSERT_SCORE_MEAN_* (Sec. 4.1, the lemma on sigma(x) = (1/m) sum_i phi(x_i) and its
+ *     three example phi; Alg. 2 with s_hat = count / L): the inner aggregation sigma over the document's
+ *     vectors is the maximum (MAX) or the mean (MEAN) of phi(count / L), with phi(x) = x (IDENTITY),
+ *     e^x - 1 (EXPM1) or 1/(1+e^-x) - 1/2 (SIGMOID).  phi is tabulated for the L+1 counts as
+ *     round(65536 * phi); the mean of a document of m vectors is the integer (sum + floor(m/2)) / m, 0 for an
+ *     empty document; the score is the sum over the query vectors.  Needs |Q| <= 16383.  The MEAN
+ *     transforms run on the code-compare kernel only.
  * Applies to later dessert_search / dessert_scores calls. */
-enum { DESSERT_SCORE_RAW_COUNTS = 0, DESSERT_SCORE_EQ1_Q16 = 1 };
+enum {
+    DESSERT_SCORE_RAW_COUNTS = 0,
+    DESSERT_SCORE_EQ1_Q16 = 1,
+    DESSERT_SCORE_MAX_IDENTITY_Q16 = 2,
+    DESSERT_SCORE_MAX_EXPM1_Q16 = 3,
+    DESSERT_SCORE_MAX_SIGMOID_Q16 = 4,
+    DESSERT_SCORE_MEAN_IDENTITY_Q16 = 5,
+    DESSERT_SCORE_MEAN_EXPM1_Q16 = 6,
+    DESSERT_SCORE_MEAN_SIGMOID_Q16 = 7
+};
 dessert_status_t dessert_set_score_transform(dessert_index_t *index, int transform);
+
+/* Weighted outer aggregation (Sec. 4.2: F(Q,S) = (1/m_q) sum_j w_j sigma(s_hat(q_j, S)), 0 <= w_j <= 1;
+ * the division by m_q is left out).  weights_dev: dev, [n_weights] u32, weight j stands for w_j = value / 65536
+ * (values above 65536 are an error of the caller, not checked on the device) and multiplies query vector j
+ * of the batches passed to later dessert_search / dessert_scores calls, whose total number of query
+ * vectors must equal n_weights (else DESSERT_EINVAL); a query vector then contributes
+ * (w * sigma + 32768) >> 16.  Needs a *_Q16 score transform.  NULL removes the weights.  The array is
+ * read by the later calls and must stay alive until they have run. */
+dessert_status_t dessert_set_query_weights(dessert_index_t *index, const uint32_t *weights_dev, uint64_t n_weights);
 
 /* Bytes of the code array for n_vectors vectors: n_vectors * L * (bytes per code), one code per
  * vector and table, vector-major, no padding. */

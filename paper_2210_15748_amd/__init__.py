@@ -29,9 +29,12 @@ HASH_AUTO, HASH_SCALAR, HASH_MFMA = 0, 1, 2
 SCORE_AUTO, SCORE_BYTECMP, SCORE_MASKLUT = 0, 1, 2
 
 SCORE_RAW_COUNTS, SCORE_EQ1_Q16 = 0, 1
+SCORE_MAX_IDENTITY_Q16, SCORE_MAX_EXPM1_Q16, SCORE_MAX_SIGMOID_Q16 = 2, 3, 4
+SCORE_MEAN_IDENTITY_Q16, SCORE_MEAN_EXPM1_Q16, SCORE_MEAN_SIGMOID_Q16 = 5, 6, 7
 
 EXPORTS = [
     "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_set_score_transform",
+    "dessert_set_query_weights",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
@@ -71,6 +74,7 @@ def lib() -> C.CDLL:
     l.dessert_get_projection.argtypes = [vp, vp]
     l.dessert_set_algo.argtypes = [vp, C.c_int, C.c_int]
     l.dessert_set_score_transform.argtypes = [vp, C.c_int]
+    l.dessert_set_query_weights.argtypes = [vp, vp, u64]
     l.dessert_code_bytes.argtypes = [vp, u64]
     l.dessert_code_bytes.restype = sz
     l.dessert_hash.argtypes = [vp, vp, u64, vp]
@@ -169,6 +173,19 @@ def set_algo(ix: Index, hash_algo: int = HASH_AUTO, score_algo: int = SCORE_AUTO
 
 def set_score_transform(ix: Index, transform: int) -> None:
     _check(lib().dessert_set_score_transform(ix.handle, transform))
+
+
+def set_query_weights(ix: Index, weights: Optional[torch.Tensor]) -> None:
+    """dessert_set_query_weights: a device tensor of Q16 weights (uint32 / int32 values in 0..65536), one per query
+    vector of the following batches, or None."""
+    if weights is None:
+        ix._weights = None
+        _check(lib().dessert_set_query_weights(ix.handle, None, 0))
+        return
+    if not weights.is_cuda or weights.dtype not in (torch.int32, torch.uint32) or weights.dim() != 1:
+        raise ValueError("weights must be a 1-d device tensor of int32 / uint32")
+    ix._weights = weights.contiguous()
+    _check(lib().dessert_set_query_weights(ix.handle, ix._weights.data_ptr(), ix._weights.numel()))
 
 
 def get_projection(ix: Index) -> torch.Tensor:

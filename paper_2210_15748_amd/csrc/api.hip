@@ -55,7 +55,10 @@ struct dessert_index {
     hipStream_t stream = nullptr;
     void* proj = nullptr;       // device, [L*C][d] int8 or float (library-owned copy)
     void* proj_mfma = nullptr;  // device, MFMA-ordered int8 copy (or null)
-    uint32_t* remap = nullptr;  // device, [L+1] Eq. 1 table in Q16 (library-owned)
+    uint32_t* remap = nullptr;  // device, [L+1] table of the current score transform in Q16 (library-owned)
+    uint32_t remap_max = 0;     // its largest entry
+    const uint32_t* q_weights = nullptr;  // caller's, Q16 weights of the query vectors (Sec. 4.2)
+    uint64_t n_weights = 0;
     // candidate filter (library-owned: MFMA-ordered centroids, key constants, bucket cursors)
     void* f_cent = nullptr;
     void* f_table = nullptr;
@@ -220,8 +223,13 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     dessert_status_t st = check_batch(ix, q_vectors, q_lengths, B, cand_ids, cand_off, &bt);
     if (st != DESSERT_OK) return st;
     if (B == 0) return DESSERT_OK;
-    if (ix->transform == DESSERT_SCORE_EQ1_Q16 && bt.max_q_len > 16383)
-        return fail(DESSERT_EINVAL, "the Eq. 1 score transform needs query sets of at most 16383 vectors");
+    if (ix->transform != DESSERT_SCORE_RAW_COUNTS && bt.max_q_len > 16383)
+        return fail(DESSERT_EINVAL, "the fixed-point score transforms need query sets of at most 16383 vectors");
+    if (ix->q_weights && ix->transform == DESSERT_SCORE_RAW_COUNTS)
+        return fail(DESSERT_EINVAL, "query weights need a fixed-point (*_Q16) score transform");
+    if (ix->q_weights && ix->n_weights != bt.total_q)
+        return fail(DESSERT_EINVAL, "%llu query weights set, the batch has %llu query vectors",
+                    (unsigned long long)ix->n_weights, (unsigned long long)bt.total_q);
     if (!workspace) return fail(DESSERT_EINVAL, "workspace_dev is NULL");
     if ((uintptr_t)workspace % 256) return fail(DESSERT_EINVAL, "workspace_dev must be 256-byte aligned");
     const bool own_scores = scores_out == nullptr;
@@ -280,13 +288,17 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     sa.qcodes = qcodes; sa.q_off = d_q_off; sa.q_uniform = bt.q_uniform; sa.n_queries = B; sa.max_q_len = bt.max_q_len;
     sa.cand_ids = cand_ids; sa.cand_off = cand_ids ? d_cand_off : nullptr; sa.cand_uniform = cand_ids ? bt.cand_uniform : 0;
     sa.max_scored = bt.max_scored; sa.total_scored = bt.total_scored; sa.n_vectors = ix->n_vectors; sa.scores = scores;
-    sa.remap = ix->transform == DESSERT_SCORE_EQ1_Q16 ? ix->remap : nullptr;
+    sa.remap = ix->transform != DESSERT_SCORE_RAW_COUNTS ? ix->remap : nullptr;
+    sa.sigma_mean = ix->transform >= DESSERT_SCORE_MEAN_IDENTITY_Q16 ? 1u : 0u;
+    sa.q_weights = ix->q_weights;
     int algo = ix->score_algo;
+    if (algo == DESSERT_SCORE_AUTO && sa.sigma_mean) algo = DESSERT_SCORE_BYTECMP;  // the mean has no mask-table form
     // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
     if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
         algo = (score_masklut_supported(ix->cfg.L, ix->cfg.C) && ix->n_vectors) ? DESSERT_SCORE_MASKLUT
                                                                                 : DESSERT_SCORE_BYTECMP;
     if (algo == DESSERT_SCORE_MASKLUT) {
+        if (sa.sigma_mean) return fail(DESSERT_EINVAL, "the MEAN score transforms run on the code-compare kernel only");
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
             return fail(DESSERT_EINVAL, "mask-table scoring needs L in {8,16,32,64,128} (C <= 8), or L = 8 with C <= 11, "
                                         "L = 16 with C <= 10, L = 32 with C = 9");
@@ -301,7 +313,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     if (k) {
         TopkArgs ta{};
         ta.scores = scores; ta.cand_ids = cand_ids; ta.cand_off = sa.cand_off; ta.cand_uniform = sa.cand_uniform; ta.n_docs = ix->n_docs;
-        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = sa.remap ? bt.max_q_len * 65536u : bt.max_q_len * ix->cfg.L;
+        ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = sa.remap ? bt.max_q_len * ix->remap_max : bt.max_q_len * ix->cfg.L;
         ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
         HIP_TRY(launch_topk(ta, ix->stream));
         if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
@@ -434,19 +446,42 @@ dessert_status_t dessert_set_algo(dessert_index_t* ix, int hash_algo, int score_
 
 dessert_status_t dessert_set_score_transform(dessert_index_t* ix, int transform) {
     if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
-    if (transform != DESSERT_SCORE_RAW_COUNTS && transform != DESSERT_SCORE_EQ1_Q16)
+    if (transform < DESSERT_SCORE_RAW_COUNTS || transform > DESSERT_SCORE_MEAN_SIGMOID_Q16)
         return fail(DESSERT_EINVAL, "unknown score transform %d", transform);
-    if (transform == DESSERT_SCORE_EQ1_Q16 && !ix->remap) {
-        // Eq. 1 for the L+1 possible collision counts: sim(c) = exp(ln(c/L)/C), sim(0) = 0, in Q16
+    if (transform != DESSERT_SCORE_RAW_COUNTS && transform != ix->transform) {
+        // phi(count / L) for the L+1 possible collision counts, in Q16
         DeviceGuard guard(ix->cfg.device);
         const uint32_t L = ix->cfg.L, C = ix->cfg.C;
         std::vector<uint32_t> tab(L + 1, 0);
-        for (uint32_t c = 1; c <= L; ++c)
-            tab[c] = (uint32_t)std::llround(65536.0 * std::exp(std::log((double)c / (double)L) / (double)C));
-        HIP_TRY(hipMalloc((void**)&ix->remap, (L + 1) * sizeof(uint32_t)));
+        uint32_t mx = 0;
+        for (uint32_t c = 1; c <= L; ++c) {
+            const double s = (double)c / (double)L;
+            double y;
+            switch (transform) {
+                case DESSERT_SCORE_EQ1_Q16: y = std::exp(std::log(s) / (double)C); break;  // Eq. 1: s^(1/C)
+                case DESSERT_SCORE_MAX_IDENTITY_Q16:
+                case DESSERT_SCORE_MEAN_IDENTITY_Q16: y = s; break;
+                case DESSERT_SCORE_MAX_EXPM1_Q16:
+                case DESSERT_SCORE_MEAN_EXPM1_Q16: y = std::exp(s) - 1.0; break;
+                default: y = 1.0 / (1.0 + std::exp(-s)) - 0.5; break;
+            }
+            tab[c] = (uint32_t)std::llround(65536.0 * y);
+            mx = std::max(mx, tab[c]);
+        }
+        HIP_TRY(hipStreamSynchronize(ix->stream));  // searches in flight may still read the old table
+        if (!ix->remap) HIP_TRY(hipMalloc((void**)&ix->remap, (L + 1) * sizeof(uint32_t)));
         HIP_TRY(hipMemcpy(ix->remap, tab.data(), (L + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+        ix->remap_max = mx;
     }
     ix->transform = transform;
+    return DESSERT_OK;
+}
+
+dessert_status_t dessert_set_query_weights(dessert_index_t* ix, const uint32_t* weights_dev, uint64_t n_weights) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (weights_dev && n_weights == 0) return fail(DESSERT_EINVAL, "n_weights is 0");
+    ix->q_weights = weights_dev;
+    ix->n_weights = weights_dev ? n_weights : 0;
     return DESSERT_OK;
 }
 

@@ -52,7 +52,9 @@ struct ScoreArgs {
     uint64_t total_scored;      // all output slots (candidate mode: sum of the list lengths)
     uint64_t n_vectors;         // vectors in the index (launch heuristics only)
     int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
-    const uint32_t* remap;      // dev [L+1] fixed-point similarity per collision count (Eq. 1), or nullptr: raw counts
+    const uint32_t* remap;      // dev [L+1] fixed-point phi per collision count (Eq. 1, Sec. 4.1 examples), or nullptr: raw counts
+    uint32_t sigma_mean;        // != 0: sigma = rounded mean of remap[count] over the document's vectors (else the max)
+    const uint32_t* q_weights;  // dev [total_q] Q16 weights of the outer sum (Sec. 4.2), or nullptr
 };
 // first query vector / first candidate slot of query set b (b may be n_queries: one past the end)
 __device__ inline uint32_t q_begin(const ScoreArgs& a, uint32_t b) { return a.q_uniform ? b * a.q_uniform : a.q_off[b]; }

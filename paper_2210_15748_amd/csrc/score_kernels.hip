@@ -37,7 +37,7 @@ __device__ inline Span query_span(const ScoreArgs& a, uint32_t b) {
 // for halfwords).
 template <int CW>
 __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
-    extern __shared__ uint32_t sq[];  // query set's codes, [mq][row dwords]
+    extern __shared__ uint32_t sq[];  // query set's codes, [mq][row dwords], then the phi table [L+1]
     constexpr uint32_t LOW = CW == 1 ? 0x7f7f7f7fu : 0x7fff7fffu;
     constexpr uint32_t TOP = CW == 1 ? 0x80808080u : 0x80008000u;
     constexpr int PER = 4 / CW;  // codes per dword
@@ -48,6 +48,9 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
     const uint32_t LW = row / 4;
     const uint32_t* qsrc = (const uint32_t*)(a.qcodes + (size_t)q_lo * row);
     for (uint32_t i = threadIdx.x; i < mq * LW; i += blockDim.x) sq[i] = qsrc[i];
+    uint32_t* tab = sq + (size_t)a.max_q_len * LW;
+    if (a.remap)
+        for (uint32_t i = threadIdx.x; i <= a.L; i += blockDim.x) tab[i] = a.remap[i];
     __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -58,9 +61,11 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
             continue;
         }
         const uint64_t lo = a.offsets[id], hi = a.offsets[id + 1];
+        const uint64_t m = hi - lo;
         int32_t score = 0;
         for (uint32_t q = 0; q < mq; ++q) {
             int32_t best = 0;
+            uint64_t sum = 0;  // sigma = mean: sum of phi over this lane's vectors
             for (uint64_t j = lo + lane; j < hi; j += 64) {
                 const uint32_t* x = (const uint32_t*)(a.codes + j * row);
                 int32_t cnt = 0;
@@ -70,12 +75,21 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
                     cnt += PER - __builtin_popcount(nz);
                 }
                 best = cnt > best ? cnt : best;
+                if (a.sigma_mean) sum += tab[cnt];
             }
-            for (int off = 32; off >= 1; off >>= 1) {
-                int32_t o = __shfl_xor(best, off, 64);
-                best = o > best ? o : best;
+            uint32_t sg;
+            if (a.sigma_mean) {
+                for (int off = 32; off >= 1; off >>= 1) sum += (uint64_t)__shfl_xor((long long)sum, off, 64);
+                sg = m ? (uint32_t)((sum + m / 2) / m) : 0u;
+            } else {
+                for (int off = 32; off >= 1; off >>= 1) {
+                    int32_t o = __shfl_xor(best, off, 64);
+                    best = o > best ? o : best;
+                }
+                sg = a.remap ? tab[best] : (uint32_t)best;
             }
-            score += a.remap ? (int32_t)a.remap[best] : best;
+            if (a.q_weights) sg = (uint32_t)(((uint64_t)a.q_weights[q_lo + q] * sg + 32768) >> 16);
+            score += (int32_t)sg;
         }
         if (lane == 0) a.scores[sp.base + pos] = score;
     }
@@ -84,8 +98,17 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
 hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
     if ((a.code_bytes != 1 && a.code_bytes != 2) || (a.L * a.code_bytes) % 4) return hipErrorInvalidValue;
-    size_t lds = (size_t)a.max_q_len * a.L * a.code_bytes;
-    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    if (a.sigma_mean && !a.remap) return hipErrorInvalidValue;
+    size_t lds = (size_t)a.max_q_len * a.L * a.code_bytes + ((size_t)a.L + 1) * 4;
+    if (lds > 65536 + 1024) return hipErrorInvalidValue;
+    if (lds > 48 * 1024) {
+        static hipError_t a1 = hipFuncSetAttribute((const void*)score_bytecmp_kernel<1>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 65536 + 1024);
+        static hipError_t a2 = hipFuncSetAttribute((const void*)score_bytecmp_kernel<2>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 65536 + 1024);
+        if (a1 != hipSuccess) return a1;
+        if (a2 != hipSuccess) return a2;
+    }
     uint64_t bx = (a.max_scored + 3) / 4;
     if (bx > 4096) bx = 4096;
     if (a.code_bytes == 1)
@@ -225,12 +248,13 @@ struct LutBlockMeta {
 // stores the masks of two query sets side by side, M[t][h] = {mask of set 2y, mask of set 2y+1},
 // so one 8-byte LDS read serves 64 query vectors: a random 8-byte read costs about 6.8 cycles
 // per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
-// REMAP: apply the fixed-point similarity table a.remap (Eq. 1) to each per-query-vector maximum.
+// REMAP: 1 = apply the fixed-point table a.remap (Eq. 1, or another phi) to each per-query-vector maximum;
+// 2 = and weight the query vectors by a.q_weights (Sec. 4.2); 0 = raw counts.
 // CW = bytes per table code (1: C <= 8, 2: wider codes); CB = bits of a table index (2^CB entries per table).
 // gz = chunk groups: with gz > 1 the 32-vector chunks of a query set are dealt round-robin to gz
 // workgroups, which add their partial sums into the (pre-zeroed) scores with integer atomics.
 // (SPLIT = false: gz is 1.)
-template <int L, int CB, int CW, bool REMAP, int W, bool SPLIT>
+template <int L, int CB, int CW, int REMAP, int W, bool SPLIT>
 __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
                                                             uint32_t gz_arg) {
     const uint32_t gz = SPLIT ? gz_arg : 1u;
@@ -438,7 +462,10 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                         uint32_t v = 0;
 #pragma unroll
                         for (int p = P - 1; p >= 0; --p) v = 2 * v + ((mx[w][p] >> q) & 1u);
-                        part += a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
+                        uint32_t term = a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
+                        if (REMAP == 2 && c0 + q < q_len[w])
+                            term = (uint32_t)(((uint64_t)a.q_weights[q_lo[w] + c0 + q] * term + 32768) >> 16);
+                        part += term;
                     }
                     part += dpp_mov<0x141>(part);  // row_half_mirror
                     part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
@@ -529,18 +556,23 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     }
     if constexpr (PAIR_OK) {
         if (pair) {
-            auto kern2 = a.remap ? score_masklut_kernel<L, CB, CW, true, 2, false>
-                                 : score_masklut_kernel<L, CB, CW, false, 2, false>;
+            auto kern2 = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 2, false>
+                         : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 2, false>
+                                     : score_masklut_kernel<L, CB, CW, 0, 2, false>;
             hipLaunchKernelGGL(kern2, grid, dim3(masklut_threads(L, CB, 2)), 0, stream, a, dpb, gy_linear, 1u);
             return hipGetLastError();
         }
     }
     if (gz > 1) {
-        auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1, true> : score_masklut_kernel<L, CB, CW, false, 1, true>;
+        auto kern = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 1, true>
+                    : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 1, true>
+                                : score_masklut_kernel<L, CB, CW, 0, 1, true>;
         hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, gz);
         return hipGetLastError();
     }
-    auto kern = a.remap ? score_masklut_kernel<L, CB, CW, true, 1, false> : score_masklut_kernel<L, CB, CW, false, 1, false>;
+    auto kern = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 1, false>
+                : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 1, false>
+                            : score_masklut_kernel<L, CB, CW, 0, 1, false>;
     hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, 1u);
     return hipGetLastError();
 }
@@ -548,6 +580,7 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream) {
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
     if (!score_masklut_supported(a.L, a.C) || a.code_bytes != (a.C > 8 ? 2u : 1u)) return hipErrorInvalidValue;
+    if (a.sigma_mean || (a.q_weights && !a.remap)) return hipErrorInvalidValue;  // max of a tabulated phi only
     const uint32_t cb = a.C <= 6 ? 6 : a.C;
 #define DESSERT_LUT_CASE(L_, CB_, CW_) \
     if (a.L == L_ && cb == CB_) return launch_masklut_t<L_, CB_, CW_>(a, stream);
