@@ -11,7 +11,11 @@ Workload: the candidate-rerank preset (1M documents in HBM, lengths ~ truncated 
 d=128 int8, L=32, C=7, 256 query sets x 32 vectors, 4096 candidates each, top-10), all synthetic and
 generated on the device from fixed seeds.
 
-Prints ONE JSON line; see the design doc for the meaning of every field.
+Prints ONE JSON line.  "value" = doc-set scores per second of the whole step with inputs resident in HBM;
+"roofline" = the scoring kernel's algorithmic code bytes per launch over its measured duration, against the
+published HBM peak (plus the HBM traffic read from the rocprofv3 counter summary under profiles/ and what a plain
+streaming read achieves in the same run); "index_build" and "candidate_filter" = the build and the pre-filter timed
+on their own; "cpu_baseline" = the CPU oracle on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
