@@ -510,6 +510,52 @@ void oracle_filter_query(const int8_t *Q, uint32_t mq, uint32_t d, const int8_t 
     free(near);
 }
 
+/* ---- k-means for the filter's centroids (Sec. 5 "Filtering": k-means clustering on a sample of the
+ * vectors at the start of indexing).  The paper names the method only; taken here: Lloyd's iteration with
+ * the squared Euclidean distance, starting from the centroids the caller passes, a fixed number of
+ * iterations, everything in integers: each iteration assigns every sample vector to its closest centroid
+ * (ties to the lower id, as oracle_assign_centroids) and replaces every centroid that received vectors by
+ * the coordinate-wise mean rounded to the nearest integer (half rounds up: floor((2 sum + n) / (2 n)));
+ * a centroid that received none stays.  Cn [K][d] is updated in place; inertia (optional, [iters]) receives
+ * the sum of squared distances of each iteration's assignment step.
+ */
+static int64_t floor_div(int64_t a, int64_t b)   /* b > 0 */
+{
+    int64_t q = a / b;
+    return (a % b != 0 && a < 0) ? q - 1 : q;
+}
+
+void oracle_kmeans(const int8_t *X, uint64_t n, uint32_t d, int8_t *Cn, uint32_t K, uint32_t iters,
+                   int64_t *inertia)
+{
+    int32_t *assign = (int32_t *)malloc((n ? n : 1) * sizeof(int32_t));
+    int64_t *sum = (int64_t *)malloc((size_t)K * d * sizeof(int64_t));
+    int64_t *cnt = (int64_t *)malloc((size_t)K * sizeof(int64_t));
+    for (uint32_t it = 0; it < iters; ++it) {
+        oracle_assign_centroids(X, n, d, Cn, K, assign);
+        memset(sum, 0, (size_t)K * d * sizeof(int64_t));
+        memset(cnt, 0, (size_t)K * sizeof(int64_t));
+        int64_t total = 0;
+        for (uint64_t v = 0; v < n; ++v) {
+            const int8_t *x = X + (size_t)v * d, *c = Cn + (size_t)assign[v] * d;
+            cnt[assign[v]] += 1;
+            for (uint32_t i = 0; i < d; ++i) {
+                sum[(size_t)assign[v] * d + i] += x[i];
+                total += ((int64_t)x[i] - c[i]) * ((int64_t)x[i] - c[i]);
+            }
+        }
+        if (inertia)
+            inertia[it] = total;
+        for (uint32_t k = 0; k < K; ++k)
+            if (cnt[k])
+                for (uint32_t i = 0; i < d; ++i)
+                    Cn[(size_t)k * d + i] = (int8_t)floor_div(2 * sum[(size_t)k * d + i] + cnt[k], 2 * cnt[k]);
+    }
+    free(assign);
+    free(sum);
+    free(cnt);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -189,6 +189,17 @@ def assign_centroids(X: np.ndarray, centroids: np.ndarray) -> np.ndarray:
     return out
 
 
+def kmeans(X: np.ndarray, init_centroids: np.ndarray, iters: int, want_inertia: bool = False):
+    """Lloyd's k-means in integers (see oracle_kmeans): returns the centroids after `iters` iterations."""
+    X = np.ascontiguousarray(X, dtype=np.int8)
+    Cn = np.array(init_centroids, dtype=np.int8, order="C", copy=True)
+    assert X.ndim == 2 and Cn.ndim == 2 and X.shape[1] == Cn.shape[1] and Cn.shape[0] >= 1
+    inertia = np.zeros(iters, dtype=np.int64) if want_inertia else None
+    lib().oracle_kmeans(_p(X), C.c_uint64(X.shape[0]), C.c_uint32(X.shape[1]), _p(Cn), C.c_uint32(Cn.shape[0]),
+                        C.c_uint32(iters), _p(inertia))
+    return (Cn, inertia) if want_inertia else Cn
+
+
 def inverted_index(assign: np.ndarray, offsets: np.ndarray, K: int):
     """(bucket_offsets [K+1] int64, bucket_docs uint32): sorted set of documents per centroid."""
     assign = np.ascontiguousarray(assign, dtype=np.int32)
