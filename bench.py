@@ -80,6 +80,8 @@ def main() -> int:
                          "a few eager calls before the capture)")
     ap.add_argument("--no-filter", action="store_true", help="skip the candidate-filter section (config 3 only)")
     ap.add_argument("--filter-centroids", type=int, default=65536)
+    ap.add_argument("--kmeans-iters", type=int, default=4, help="Lloyd iterations for the filter's centroids (0: sampled vectors)")
+    ap.add_argument("--kmeans-sample", type=int, default=1 << 20)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -188,7 +190,15 @@ def main() -> int:
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / reps, r
         Kc = min(args.filter_centroids, w.n_vectors)
-        Cn = gen.filter_centroids(w, Kc)
+        Cn = gen.filter_centroids(w, Kc)                    # K document vectors drawn without replacement
+        kmeans_ms = None
+        if args.kmeans_iters:
+            gs = torch.Generator(device=dev)
+            gs.manual_seed(1000 * p.cfg + 77)
+            n_s = min(args.kmeans_sample, w.n_vectors)
+            sample = w.docs[torch.randint(0, w.n_vectors, (n_s,), generator=gs, device=dev)].contiguous()
+            kmeans_ms, Cn = ev_ms(lambda: dz.filter_kmeans(ix, sample, Cn, args.kmeans_iters), 1)
+            del sample
         f_build_ms, (assign, b_off, b_docs) = ev_ms(lambda: dz.filter_build(ix, Cn, w.docs), 1)
         f_probe, f_k = 1, p.n_cand
         f_query_ms, (f_ids, f_cnt) = ev_ms(lambda: dz.filter_query(ix, w.queries, ql, f_probe, f_k), 10)
@@ -197,7 +207,11 @@ def main() -> int:
                                               cand_ids=dz.filter_query(ix, w.queries, ql, f_probe, f_k)[0].view(torch.int32)), 10)
         kept = float(np.mean([len(set(w.planted[b].tolist()) & set(f_ids[b].cpu().tolist())) for b in range(0, B, 8)]))
         gemm_ops = 2.0 * w.n_vectors * Kc * p.d
-        filt = {"n_centroids": Kc, "centroids": "document vectors drawn without replacement (stand-in for k-means)",
+        filt = {"n_centroids": Kc,
+                "centroids": (f"{args.kmeans_iters} Lloyd iterations on {min(args.kmeans_sample, w.n_vectors)} sampled vectors, "
+                              "started from document vectors drawn without replacement") if args.kmeans_iters
+                else "document vectors drawn without replacement",
+                "kmeans_ms": None if kmeans_ms is None else round(kmeans_ms, 2),
                 "bucket_entries": int(b_off[-1].item()), "build_ms": round(f_build_ms, 2),
                 "build_roofline": {"bound": "mfma", "kernel": "filter_gemm_kernel (vectors x centroids, int8)",
                                    "achieved": round(gemm_ops / (f_build_ms * 1e-3) / 1e12, 1), "peak": 5000.0,

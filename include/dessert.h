@@ -196,8 +196,8 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
                                 void *workspace_dev, size_t workspace_bytes, int32_t *out_scores_dev);
 
 /* Candidate filter (Sec. 5 "Filtering"): an inverted index from centroid ids to document ids and the
- * query-side selection of the documents to score.  The centroids are an input (the paper obtains them
- * by k-means on a sample of the vectors; any centroid set works).  "Closest" is the squared Euclidean
+ * query-side selection of the documents to score.  The centroids are an input (any centroid set works;
+ * dessert_filter_kmeans below trains them as the paper does, by k-means on a sample of the vectors).  "Closest" is the squared Euclidean
  * distance, ties to the lower centroid id.  Needs int8 vectors with d in {64, 128, 256} and a built
  * index (dessert_build_index) over the same vectors_dev.
  *
@@ -220,6 +220,21 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
  *   workspace_dev   dev, 256-byte aligned, dessert_filter_workspace_bytes(index, n_queries, total query
  *                   vectors, longest query set, filter_probe) bytes
  * Limits: n_centroids <= 2^20, filter_probe <= min(n_centroids, 1024), filter_k <= 16384. */
+/* k-means for the filter's centroids (Sec. 5 "Filtering": k-means clustering on a sample of the vectors at
+ * the start of indexing).  Lloyd's iteration in integers: each of the `iterations` rounds assigns every
+ * sample vector to its closest centroid (squared Euclidean distance, ties to the lower id) and replaces
+ * every centroid that received vectors by their coordinate-wise mean rounded to the nearest integer
+ * (half rounds up); a centroid without vectors stays.
+ *   sample_dev     dev, [n_sample][d] int8, 16-byte aligned, n_sample <= 2^23
+ *   centroids_dev  dev, in/out, [n_centroids][d] int8: the initial centroids (e.g. distinct sample vectors) on
+ *                  entry, the result on return; pass it to dessert_filter_build
+ *   workspace_dev  dev, 256-byte aligned, dessert_filter_kmeans_workspace_bytes(index, n_sample, n_centroids)
+ * Uses only d, the device and the stream of the index (no built index needed).  Asynchronous. */
+size_t dessert_filter_kmeans_workspace_bytes(const dessert_index_t *index, uint64_t n_sample, uint32_t n_centroids);
+dessert_status_t dessert_filter_kmeans(const dessert_index_t *index, const int8_t *sample_dev, uint64_t n_sample,
+                                       int8_t *centroids_dev, uint32_t n_centroids, uint32_t iterations,
+                                       void *workspace_dev, size_t workspace_bytes);
+
 dessert_status_t dessert_filter_build(dessert_index_t *index, const int8_t *centroids_dev, uint32_t n_centroids,
                                       const void *vectors_dev, uint32_t *assign_dev, uint32_t *bucket_offsets_dev,
                                       uint32_t *bucket_docs_dev);

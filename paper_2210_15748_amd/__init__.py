@@ -37,6 +37,7 @@ EXPORTS = [
     "dessert_set_query_weights",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
+    "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
     "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
     "dessert_version",
@@ -83,6 +84,9 @@ def lib() -> C.CDLL:
     l.dessert_search_workspace_bytes.restype = sz
     l.dessert_search.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, sz, vp, vp]
     l.dessert_scores.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
+    l.dessert_filter_kmeans_workspace_bytes.argtypes = [vp, u64, u32]
+    l.dessert_filter_kmeans_workspace_bytes.restype = sz
+    l.dessert_filter_kmeans.argtypes = [vp, vp, u64, vp, u32, u32, vp, sz]
     l.dessert_filter_build.argtypes = [vp, vp, u32, vp, vp, vp, vp]
     l.dessert_filter_workspace_bytes.argtypes = [vp, u32, u64, u32, u32]
     l.dessert_filter_workspace_bytes.restype = sz
@@ -290,6 +294,21 @@ def scores(ix: Index, q_vectors: torch.Tensor, q_lengths, cand_ids: Optional[tor
                                 None if co is None else co.ctypes.data, workspace.data_ptr(), workspace.numel(),
                                 out.data_ptr()))
     return out if co is not None else out.view(B, ix.n_docs)
+
+
+def filter_kmeans(ix: Index, sample: torch.Tensor, init_centroids: torch.Tensor, iterations: int) -> torch.Tensor:
+    """dessert_filter_kmeans: Lloyd iterations from init_centroids on the sample; returns the new centroids [K, d] int8."""
+    sample = _check_vectors(ix, sample)
+    if not init_centroids.is_cuda or init_centroids.dtype != torch.int8 or init_centroids.dim() != 2 \
+            or init_centroids.shape[1] != ix.cfg.d:
+        raise ValueError("init_centroids must be a device int8 tensor [K, d]")
+    cent = init_centroids.contiguous().clone()
+    K, n = cent.shape[0], sample.shape[0]
+    nbytes = int(lib().dessert_filter_kmeans_workspace_bytes(ix.handle, n, K))
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=ix.device)
+    _check(lib().dessert_filter_kmeans(ix.handle, sample.data_ptr(), n, cent.data_ptr(), K, iterations,
+                                       ws.data_ptr(), ws.numel()))
+    return cent
 
 
 def filter_build(ix: Index, centroids: torch.Tensor, vectors: torch.Tensor):

@@ -625,6 +625,56 @@ dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroi
 }
 
 namespace {
+struct KmeansWorkspace {
+    size_t assign, sums, counts, cent, table, total;
+};
+KmeansWorkspace carve_kmeans(uint32_t d, uint64_t n, uint32_t K) {
+    KmeansWorkspace w{};
+    size_t p = 0;
+    w.assign = p; p += align_up((size_t)(n ? n : 1) * 4, 256);
+    w.sums = p;   p += align_up((size_t)K * d * 4, 256);
+    w.counts = p; p += align_up((size_t)K * 4, 256);
+    w.cent = p;   p += align_up(filter_centroid_bytes(K, d), 256);
+    w.table = p;  p += align_up(filter_table_bytes(K), 256);
+    w.total = p;
+    return w;
+}
+}  // namespace
+
+size_t dessert_filter_kmeans_workspace_bytes(const dessert_index_t* ix, uint64_t n_sample, uint32_t n_centroids) {
+    if (!ix || n_centroids == 0) return 0;
+    return carve_kmeans(ix->cfg.d, n_sample, n_centroids).total;
+}
+
+dessert_status_t dessert_filter_kmeans(const dessert_index_t* ix, const int8_t* sample_dev, uint64_t n_sample,
+                                       int8_t* centroids_dev, uint32_t n_centroids, uint32_t iterations,
+                                       void* workspace_dev, size_t workspace_bytes) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (ix->cfg.dtype != DESSERT_I8 || !filter_supported(ix->cfg.d))
+        return fail(DESSERT_EINVAL, "the candidate filter needs int8 vectors with d in {64,128,256}");
+    if (!centroids_dev || !workspace_dev || (n_sample && !sample_dev)) return fail(DESSERT_EINVAL, "NULL argument");
+    if (n_centroids == 0 || n_centroids > (1u << 20)) return fail(DESSERT_EINVAL, "n_centroids must be in 1..2^20");
+    if (n_sample > (1ull << 23)) return fail(DESSERT_EINVAL, "at most 2^23 sample vectors (32-bit coordinate sums)");
+    if ((uintptr_t)sample_dev % 16 || (uintptr_t)workspace_dev % 256)
+        return fail(DESSERT_EINVAL, "sample_dev must be 16-byte and workspace_dev 256-byte aligned");
+    const KmeansWorkspace w = carve_kmeans(ix->cfg.d, n_sample, n_centroids);
+    if (workspace_bytes < w.total)
+        return fail(DESSERT_EINVAL, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, w.total);
+    DeviceGuard guard(ix->cfg.device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    char* ws = (char*)workspace_dev;
+    uint32_t* assign = (uint32_t*)(ws + w.assign);
+    for (uint32_t it = 0; it < iterations; ++it) {
+        HIP_TRY(launch_filter_prep(centroids_dev, n_centroids, ix->cfg.d, ws + w.cent, ws + w.table, ix->stream));
+        HIP_TRY(launch_filter_assign(sample_dev, n_sample, ix->cfg.d, n_centroids, ws + w.cent, ws + w.table, assign,
+                                     ix->stream));
+        HIP_TRY(launch_kmeans_update(sample_dev, n_sample, ix->cfg.d, assign, n_centroids, (int32_t*)(ws + w.sums),
+                                     (uint32_t*)(ws + w.counts), centroids_dev, ix->stream));
+    }
+    return DESSERT_OK;
+}
+
+namespace {
 struct FilterWorkspace {
     size_t dist, probe_ids, q_off, cursor, lists, list_stride, total;
 };

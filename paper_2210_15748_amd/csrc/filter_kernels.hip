@@ -437,6 +437,61 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
 }
 
 // ---------------------------------------------------------------------------
+// k-means for the centroids (Sec. 5 "Filtering": k-means on a sample of the vectors): Lloyd's iteration
+// in integers.  The assignment step is the GEMM above; these two kernels are the update step.
+// One thread per (vector, 4 coordinates): sums[c][i] += x[i]; the thread of the first coordinates counts the vector.
+__global__ __launch_bounds__(256) void kmeans_accumulate_kernel(const int8_t* __restrict__ X, uint64_t n, uint32_t d,
+                                                                const uint32_t* __restrict__ assign,
+                                                                int32_t* __restrict__ sums, uint32_t* __restrict__ counts) {
+    const uint32_t parts = d / 4;
+    const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n * parts) return;
+    const uint64_t v = idx / parts;
+    const uint32_t part = (uint32_t)(idx - v * parts);
+    const uint32_t c = assign[v];
+    const uint32_t x = *(const uint32_t*)(X + v * d + part * 4);
+    int32_t* dst = sums + (size_t)c * d + part * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int32_t xi = (int32_t)(int8_t)(x >> (8 * i));
+        if (xi) atomicAdd(dst + i, xi);
+    }
+    if (part == 0) atomicAdd(counts + c, 1u);
+}
+
+// centroid = coordinate-wise mean rounded to the nearest integer, half up: floor((2 sum + n) / (2 n));
+// a centroid that received no vector stays
+__global__ __launch_bounds__(256) void kmeans_update_kernel(const int32_t* __restrict__ sums,
+                                                            const uint32_t* __restrict__ counts, uint32_t K, uint32_t d,
+                                                            int8_t* __restrict__ Cn) {
+    const uint32_t idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= K * d) return;
+    const int64_t cnt = counts[idx / d];
+    if (cnt == 0) return;
+    const int64_t a = 2 * (int64_t)sums[idx] + cnt, b = 2 * cnt;
+    int64_t q = a / b;
+    if (a % b != 0 && a < 0) --q;  // floor division
+    Cn[idx] = (int8_t)q;
+}
+
+hipError_t launch_kmeans_update(const int8_t* X, uint64_t n, uint32_t d, const uint32_t* assign, uint32_t K,
+                                int32_t* sums, uint32_t* counts, int8_t* Cn, hipStream_t stream) {
+    if (d % 4 || K == 0 || (uint64_t)K * d > 0x7fffffffull) return hipErrorInvalidValue;
+    const uint64_t cells = (uint64_t)K * d;
+    hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)((cells + 2047) / 2048)), dim3(256), 0, stream, sums, cells);
+    hipLaunchKernelGGL(filter_zero_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, (int32_t*)counts, (uint64_t)K);
+    if (n) {
+        const uint64_t blocks = (n * (d / 4) + 255) / 256;
+        if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kmeans_accumulate_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, X, n, d, assign, sums,
+                           counts);
+    }
+    hipLaunchKernelGGL(kmeans_update_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, stream, sums, counts, K,
+                       d, Cn);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 static bool filter_shape(uint32_t d) { return d == 64 || d == 128 || d == 256; }
 bool filter_supported(uint32_t d) { return filter_shape(d); }
 uint32_t filter_tiles(uint32_t K) { return (K + 31) / 32; }

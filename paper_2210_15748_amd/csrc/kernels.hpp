@@ -75,6 +75,10 @@ hipError_t launch_filter_assign(const int8_t* X, uint64_t n, uint32_t d, uint32_
                                 uint32_t* assign, hipStream_t stream);
 hipError_t launch_filter_distances(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                    int32_t* out /*[n][filter_tiles(K)*32]*/, hipStream_t stream);
+// Update step of Lloyd's k-means: per-cluster coordinate sums and counts of the assigned vectors, then the rounded means
+// written over Cn [K][d] (clusters without vectors keep their centroid).  sums [K][d] i32, counts [K] u32 are scratch.
+hipError_t launch_kmeans_update(const int8_t* X, uint64_t n, uint32_t d, const uint32_t* assign, uint32_t K,
+                                int32_t* sums, uint32_t* counts, int8_t* Cn, hipStream_t stream);
 // Probe selection inside the GEMM for probe <= FILTER_LIST_MAX (ranges = 0: not applicable, use the
 // distance matrix + launch_filter_probe instead).
 constexpr uint32_t FILTER_LIST_MAX = 8;

@@ -158,3 +158,49 @@ def test_search_all_slots_empty_and_k_larger_than_real_candidates():
     ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
     assert np.all(ids[0] == 0xFFFFFFFF) and np.all(sc[0] == -1)
     assert set(ids[1, :2].tolist()) == {3, 7} and np.all(ids[1, 2:] == 0xFFFFFFFF) and np.all(sc[1, 2:] == -1)
+
+
+@pytest.mark.parametrize("d,K,n,iters", [(128, 7, 500, 3), (64, 1, 301, 2), (256, 300, 5000, 4), (128, 40, 3000, 6),
+                                         (128, 5, 0, 2), (64, 33, 64, 1)])
+def test_filter_kmeans_matches_oracle(d, K, n, iters):
+    say(f"filter kmeans d={d} K={K} n={n} iters={iters}")
+    rng = np.random.default_rng(d + K + n)
+    pool = rng.integers(-110, 111, (max(K // 2, 1), d))
+    X = np.clip(pool[rng.integers(0, len(pool), n)] + rng.integers(-30, 31, (n, d)), -127, 127).astype(np.int8)
+    if n >= K:
+        init = X[rng.choice(n, K, replace=False)].copy()
+    else:
+        init = rng.integers(-127, 128, (K, d)).astype(np.int8)
+    if K > 3:
+        init[K - 1] = 127                      # far from everything: stays empty
+        init[K - 2] = init[0]                  # duplicate: ties go to the lower id, so this one stays empty too
+    ix = dz.create(d, 32, 7, seed=1)
+    Xd = torch.from_numpy(X).to(DEV) if n else torch.zeros(0, d, dtype=torch.int8, device=DEV)
+    got = dz.filter_kmeans(ix, Xd, torch.from_numpy(init).to(DEV), iters).cpu().numpy()
+    want = orc.kmeans(X, init, iters)
+    assert np.array_equal(got, want)
+    if K > 3:
+        assert np.array_equal(got[K - 1], init[K - 1])
+
+
+def test_filter_kmeans_then_filter_chain():
+    say("kmeans -> filter_build -> filter_query, cfg3-like reduced")
+    w = gen.make(3, n_docs=4000, n_queries=4)
+    p = w.preset
+    K, iters, probe, filter_k = 500, 3, 2, 256
+    rng = np.random.default_rng(0)
+    sample_rows = rng.choice(w.n_vectors, 20000, replace=False)
+    sample = w.docs.numpy()[sample_rows]
+    init = sample[:K].copy()
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj.to(DEV))
+    dz.build_index(ix, w.docs.to(DEV), w.lengths)
+    cent = dz.filter_kmeans(ix, torch.from_numpy(sample).to(DEV), torch.from_numpy(init).to(DEV), iters)
+    want_cent = orc.kmeans(sample, init, iters)
+    assert np.array_equal(cent.cpu().numpy(), want_cent)
+    dz.filter_build(ix, cent, w.docs.to(DEV))
+    ids, cnt = dz.filter_query(ix, w.queries.to(DEV), w.q_lengths, probe, filter_k)
+    obo, obd = orc.inverted_index(orc.assign_centroids(w.docs.numpy(), want_cent), w.offsets.numpy(), K)
+    for b in range(p.n_queries):
+        q = w.queries.numpy()[b * p.q_len:(b + 1) * p.q_len]
+        want_ids, want_cnt = orc.filter_query(q, want_cent, obo, obd, w.n_docs, probe, filter_k)
+        assert np.array_equal(ids[b].cpu().numpy(), want_ids) and np.array_equal(cnt[b].cpu().numpy(), want_cnt), b
