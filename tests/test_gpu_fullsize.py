@@ -228,3 +228,89 @@ def test_cfg3_full_candidate_filter_sampled():
                 assert where[dcm] == c, (b, dcm)
             else:
                 assert c == 0 or (c, -dcm) < last, (b, dcm, c, last)
+
+
+def test_cfg4_full_large_exhaustive_sampled():
+    """The large exhaustive preset at full size (8M documents, 560M vectors = 72 GB of int8 in HBM, 32 query sets,
+    k = 100).  The oracle cannot score 2.6e8 pairs, so: hash codes and raw scores of sampled documents (4000 random
+    ones, every document the GPU ranks, every planted one) for all 32 query sets, bit for bit; the top-100 of every
+    query set re-derived by the oracle's selection from the GPU's score dump restricted to scores >= the 100th."""
+    say("cfg4 full: generating 8M documents on the device")
+    w = gen.make(4, device=DEV)
+    p = w.preset
+    say(f"cfg4 full: {w.n_vectors} vectors generated; build + search")
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj)
+    codes, offsets = dz.build_index(ix, w.docs, w.lengths)
+    ids, sc = dz.search(ix, w.queries, w.q_lengths, p.k)
+    raw_dev = dz.scores(ix, w.queries, w.q_lengths)
+    torch.cuda.synchronize()
+    say("cfg4 full: scores computed; checking the top-k against the dump")
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    raw = raw_dev.cpu().numpy().reshape(p.n_queries, w.n_docs)
+    del raw_dev
+    assert raw.min() >= 0 and raw.max() <= p.q_len * p.L
+    for b in range(p.n_queries):
+        kth = sc[b, -1]
+        assert int((raw[b] > kth).sum()) < p.k                      # the cut is in the right place
+        cand = np.nonzero(raw[b] >= kth)[0]
+        want_ids, want_sc = orc.topk(raw[b][cand], p.k, cand)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+        assert ids[b, 0] == int(w.planted[b, 0])
+    say("cfg4 full: oracle on sampled documents")
+    rng = np.random.default_rng(4)
+    sample = np.unique(np.concatenate([rng.integers(0, w.n_docs, 4000), ids.reshape(-1).astype(np.int64),
+                                       w.planted.numpy().reshape(-1)]))
+    rows, dcodes, sub_off = oracle_codes_of_docs(w, sample)
+    assert np.array_equal(codes[torch.from_numpy(rows).to(DEV)].cpu().numpy(), dcodes)
+    qc = orc.hash_i8(w.queries.cpu().numpy(), w.proj.cpu().numpy(), p.L, p.C)
+    for b in range(p.n_queries):
+        want = orc.scores(dcodes, sub_off, qc[b * p.q_len:(b + 1) * p.q_len])
+        assert np.array_equal(raw[b, sample], want), b
+    off_last = offsets[-1].item()
+    assert off_last == w.n_vectors
+
+
+def test_cfg5_full_fp16_sampled():
+    """The fp16 / Gaussian preset at full size (500k documents, 72M vectors of d = 256 = 37 GB, L = 64, C = 8, 64 query
+    sets of 128 vectors, k = 10): hashing tolerance on sampled documents, the top-10 of every query set re-derived from
+    the GPU's score dump, planted documents first, and raw scores of sampled documents within the bound that the
+    tolerated bit flips allow (a flipped code bit changes at most one table of one vector pair)."""
+    say("cfg5 full: generating 500k fp16 documents on the device")
+    w = gen.make(5, device=DEV)
+    p = w.preset
+    say(f"cfg5 full: {w.n_vectors} vectors generated; build + search")
+    ix = dz.create(p.d, p.L, p.C, dtype=dz.F16, proj_kind=dz.PROJ_GAUSSIAN_F32, proj=w.proj)
+    codes, _ = dz.build_index(ix, w.docs, w.lengths)
+    ids, sc = dz.search(ix, w.queries, w.q_lengths, p.k)
+    raw = dz.scores(ix, w.queries, w.q_lengths).cpu().numpy()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    say("cfg5 full: checking the top-k against the dump")
+    for b in range(p.n_queries):
+        kth = sc[b, -1]
+        assert int((raw[b] > kth).sum()) < p.k
+        cand = np.nonzero(raw[b] >= kth)[0]
+        want_ids, want_sc = orc.topk(raw[b][cand], p.k, cand)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+        assert ids[b, 0] == int(w.planted[b, 0])
+    say("cfg5 full: oracle hashing of sampled documents")
+    rng = np.random.default_rng(55)
+    off = w.offsets.numpy()
+    sample = np.unique(np.concatenate([rng.integers(0, w.n_docs, 300), w.planted[:, 0].numpy()]))
+    rows = np.concatenate([np.arange(off[i], off[i + 1]) for i in sample])
+    X = w.docs[torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    R = w.proj.cpu().numpy()
+    want, proj = orc.hash_fp(X, R, p.L, p.C, want_proj=True)
+    got = codes[torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    diff = np.unpackbits(got[..., None], axis=2, bitorder="little") != np.unpackbits(want[..., None], axis=2, bitorder="little")
+    assert diff.mean() <= 1e-4, diff.mean()
+    norms = np.linalg.norm(X.astype(np.float64), axis=1)
+    margins = np.abs(proj.reshape(X.shape[0], p.L, p.C))
+    assert np.all(margins[diff] < 1e-3 * np.broadcast_to(norms[:, None, None], margins.shape)[diff])
+    # scores of the sampled documents from the oracle's own codes: equal up to the flipped bits
+    sub_off = np.concatenate([[0], np.cumsum(off[sample + 1] - off[sample])])
+    oq = orc.hash_fp(w.queries.cpu().numpy(), R, p.L, p.C)
+    flips = int(diff.sum())
+    for b in (0, 31, 63):
+        s = orc.scores(want, sub_off, oq[b * p.q_len:(b + 1) * p.q_len])
+        d = np.abs(raw[b, sample].astype(np.int64) - s)
+        assert d.sum() <= 2 * (flips + 64) and (d == 0).mean() >= 0.95, (d.sum(), flips)
