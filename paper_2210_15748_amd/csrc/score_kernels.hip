@@ -372,9 +372,10 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
             // lanes past the end re-read the document's last vector (a repeated vector cannot
             // change the maximum); the next round's codes are requested before this round's
             // table reads so that HBM latency overlaps the bit-sliced arithmetic
-            auto load_codes = [&](uint32_t j0, uint32_t (&dst)[LW]) {
-                uint32_t j = j0 + sub;
-                j = j < last_j ? j : last_j;
+            auto load_codes = [&](int32_t j0, uint32_t (&dst)[LW]) {
+                int32_t j = j0 + (int32_t)sub;
+                j = j < 0 ? 0 : j;
+                j = j < (int32_t)last_j ? j : (int32_t)last_j;
                 const uint8_t* row = a.codes + (lo + j) * (L * CW);
                 if constexpr (LW % 4 == 0) {
                     const v4i* src = (const v4i*)row;
@@ -389,9 +390,14 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                     dst[0] = v.x; dst[1] = v.y;
                 }
             };
+            // a round's G rows start on a 128-byte line of the code array (rows before the document's
+            // first clamp to it), so the rows of one round are whole lines and no line is requested
+            // by two rounds
+            constexpr uint32_t ROWS_PER_LINE = 128 / (L * CW) < 1 ? 1 : (128 / (L * CW) > G ? G : 128 / (L * CW));
+            const int32_t j_first = -(int32_t)((uint32_t)lo & (ROWS_PER_LINE - 1));
             uint32_t nxt[LW];
-            load_codes(0, nxt);
-            for (uint32_t j0 = 0; __any(j0 < m); j0 += G) {
+            load_codes(j_first, nxt);
+            for (int32_t j0 = j_first; __any(j0 < (int32_t)m); j0 += G) {
                 uint32_t dw[LW];
 #pragma unroll
                 for (int w = 0; w < LW; ++w) dw[w] = nxt[w];
