@@ -266,7 +266,8 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
     constexpr int DOCS_PER_WAVE = 64 / G;
     // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
-    __shared__ __attribute__((aligned(8))) uint32_t lut[L * STRIDE * W];  // [t][h][w]
+    constexpr int LUT_WORDS = L * STRIDE * W;
+    __shared__ __attribute__((aligned(8))) uint32_t lut[LUT_WORDS];  // [t][h][w]
     __shared__ LutBlockMeta meta;
 
     // Which (document block, query-set group) this workgroup takes.  When every set scores every
@@ -301,19 +302,64 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
     const uint32_t sub = lane & (G - 1);  // lane within the document's group
     const uint32_t grp = lane / G;        // group within the wave
 
-    // ---- where each document lives, and the length-class ordering
-    for (uint32_t i = threadIdx.x; i < LUT_BINS; i += T) meta.bin[i] = 0;
-    __syncthreads();
-    uint32_t my_class = 0;
-    if (threadIdx.x < ndocs) {
+    // ---- prologue: where each document lives, the length-class ordering, and the first chunk's mask
+    // table.  Global loads are issued first and used late, so the dependent chain candidate id ->
+    // offsets runs while the table is zeroed and the query codes arrive.
+    const uint32_t c_first = cz * 32;  // first chunk of 32 query vectors taken by this workgroup
+    auto chunk_len = [&](int w, uint32_t c0) { return c0 >= q_len[w] ? 0u : (q_len[w] - c0 < 32 ? q_len[w] - c0 : 32u); };
+    auto query_code = [&](int w, uint32_t c0, uint32_t i) {  // entry i = (q, t) of the chunk: the code of q in table t
+        const size_t at = (size_t)(q_lo[w] + c0) * L + i;
+        return CW == 1 ? (uint32_t)a.qcodes[at] : (uint32_t)((const uint16_t*)a.qcodes)[at];
+    };
+    auto table_or = [&](int w, uint32_t i, uint32_t h) {
+        const uint32_t q = i / L, t = i % L;
+        atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
+    };
+    auto zero_table = [&]() {
+        for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
+    };
+    const bool have_doc = threadIdx.x < ndocs;
+    uint64_t my_id = 0;
+    if (have_doc) {
         const uint64_t pos = first + threadIdx.x;
-        const uint64_t id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
-        // an empty candidate slot (id 0xFFFFFFFF) is kept as a zero-length document whose stored
-        // start is all ones; it is written as score -1 below
-        const bool empty_slot = a.cand_ids && id == 0xFFFFFFFFull;
-        const uint64_t lo = empty_slot ? ~0ull : a.offsets[id];
-        const uint32_t m = empty_slot ? 0u : (uint32_t)(a.offsets[id + 1] - lo);
-        meta.lo[threadIdx.x] = lo;
+        my_id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+    }
+    constexpr int QPT = (32 * L + T - 1) / T;  // table entries per thread and query set
+    uint32_t qh[W][QPT];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const uint32_t n_ent = chunk_len(w, c_first) * L;
+#pragma unroll
+        for (int n = 0; n < QPT; ++n) {
+            const uint32_t i = threadIdx.x + n * T;
+            qh[w][n] = i < n_ent ? query_code(w, c_first, i) : 0u;
+        }
+    }
+    zero_table();
+    for (uint32_t i = threadIdx.x; i < LUT_BINS; i += T) meta.bin[i] = 0;
+    if (threadIdx.x == 0) meta.next = 0;
+    // an empty candidate slot (id 0xFFFFFFFF) is kept as a zero-length document whose stored
+    // start is all ones; it is written as score -1 below
+    const bool empty_slot = a.cand_ids && my_id == 0xFFFFFFFFull;
+    uint64_t my_lo = ~0ull, my_hi = ~0ull;
+    if (have_doc && !empty_slot) {
+        my_lo = a.offsets[my_id];
+        my_hi = a.offsets[my_id + 1];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const uint32_t n_ent = chunk_len(w, c_first) * L;
+#pragma unroll
+        for (int n = 0; n < QPT; ++n) {
+            const uint32_t i = threadIdx.x + n * T;
+            if (i < n_ent) table_or(w, i, qh[w][n]);
+        }
+    }
+    uint32_t my_class = 0;
+    if (have_doc) {
+        const uint32_t m = (uint32_t)(my_hi - my_lo);  // 0 for an empty slot
+        meta.lo[threadIdx.x] = my_lo;
         meta.m[threadIdx.x] = m;
         uint32_t rounds = (m + G - 1) / G;
         my_class = rounds < LUT_BINS ? LUT_BINS - 1 - rounds : 0;  // class 0 = longest
@@ -330,25 +376,22 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
         meta.bin[lane] = incl - c;
     }
     __syncthreads();
-    if (threadIdx.x < ndocs) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
+    if (have_doc) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
 
     const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
-    for (uint32_t c0 = cz * 32; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
-        __syncthreads();  // previous chunk's readers are done (and `order` is complete)
-        for (uint32_t i = threadIdx.x; i < L * STRIDE * W; i += T) lut[i] = 0;
-        if (threadIdx.x == 0) meta.next = 0;
-        __syncthreads();
+    for (uint32_t c0 = c_first; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
+        if (c0 != c_first) {  // the first chunk's table was built above
+            __syncthreads();  // previous chunk's readers are done
+            zero_table();
+            if (threadIdx.x == 0) meta.next = 0;
+            __syncthreads();
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            const uint32_t nq = c0 >= q_len[w] ? 0 : (q_len[w] - c0 < 32 ? q_len[w] - c0 : 32);
-            for (uint32_t i = threadIdx.x; i < nq * L; i += T) {
-                uint32_t q = i / L, t = i % L;
-                const size_t at = (size_t)(q_lo[w] + c0 + q) * L + t;
-                uint32_t h = CW == 1 ? (uint32_t)a.qcodes[at] : (uint32_t)((const uint16_t*)a.qcodes)[at];
-                atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
+            for (int w = 0; w < W; ++w) {
+                const uint32_t n_ent = chunk_len(w, c0) * L;
+                for (uint32_t i = threadIdx.x; i < n_ent; i += T) table_or(w, i, query_code(w, c0, i));
             }
         }
-        __syncthreads();
+        __syncthreads();  // table and `order` complete
 
         for (;;) {
             uint32_t claim = 0;
@@ -372,11 +415,9 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
             // lanes past the end re-read the document's last vector (a repeated vector cannot
             // change the maximum); the next round's codes are requested before this round's
             // table reads so that HBM latency overlaps the bit-sliced arithmetic
-            auto load_codes = [&](int32_t j0, uint32_t (&dst)[LW]) {
-                int32_t j = j0 + (int32_t)sub;
-                j = j < 0 ? 0 : j;
-                j = j < (int32_t)last_j ? j : (int32_t)last_j;
-                const uint8_t* row = a.codes + (lo + j) * (L * CW);
+            const uint8_t* doc_codes = a.codes + lo * (L * CW);
+            auto load_codes = [&](int32_t j, uint32_t (&dst)[LW]) {  // j: row within the document, already clamped
+                const uint8_t* row = doc_codes + (uint32_t)j * (uint32_t)(L * CW);
                 if constexpr (LW % 4 == 0) {
                     const v4i* src = (const v4i*)row;
 #pragma unroll
@@ -390,18 +431,8 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                     dst[0] = v.x; dst[1] = v.y;
                 }
             };
-            // a round's G rows start on a 128-byte line of the code array (rows before the document's
-            // first clamp to it), so the rows of one round are whole lines and no line is requested
-            // by two rounds
-            constexpr uint32_t ROWS_PER_LINE = 128 / (L * CW) < 1 ? 1 : (128 / (L * CW) > G ? G : 128 / (L * CW));
-            const int32_t j_first = -(int32_t)((uint32_t)lo & (ROWS_PER_LINE - 1));
-            uint32_t nxt[LW];
-            load_codes(j_first, nxt);
-            for (int32_t j0 = j_first; __any(j0 < (int32_t)m); j0 += G) {
-                uint32_t dw[LW];
-#pragma unroll
-                for (int w = 0; w < LW; ++w) dw[w] = nxt[w];
-                load_codes(j0 + G, nxt);
+            // one round: the table reads of this lane's vector, the carry-save count and the running maximum
+            auto process = [&](const uint32_t (&dw)[LW]) {
                 const char* lut_bytes = reinterpret_cast<const char*>(lut);
                 uint32_t off[L];  // byte offset of x's entry within each table
 #pragma unroll
@@ -433,6 +464,48 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                     csa_planes<L>(msk[w], cnt);
                     planes_max<P>(mx[w], cnt);
                 }
+            };
+            // a round's G rows start on a 128-byte line of the code array (rows before the document's
+            // first clamp to it), so the rows of one round are whole lines and no line is requested
+            // by two rounds
+            constexpr uint32_t ROWS_PER_LINE = 128 / (L * CW) < 1 ? 1 : (128 / (L * CW) > G ? G : 128 / (L * CW));
+            int32_t j = (int32_t)sub - (int32_t)((uint32_t)lo & (ROWS_PER_LINE - 1));  // this lane's row in the round at hand
+            const int32_t j_end = (int32_t)m + (int32_t)sub;  // rounds run while j - sub < m
+            auto clamped = [&](int32_t jj) { return jj < (int32_t)last_j ? jj : (int32_t)last_j; };
+            // code buffers used in turn (the loop body is one round per buffer), so no register copies;
+            // DEPTH rounds of codes are in flight while a round is processed
+            constexpr int DEPTH = (W == 1 && LW <= 8) ? 2 : 1;
+            if constexpr (DEPTH == 1) {
+                uint32_t buf_a[LW], buf_b[LW];
+                load_codes(clamped(j < 0 ? 0 : j), buf_a);
+                for (;;) {
+                    load_codes(clamped(j + G), buf_b);
+                    process(buf_a);
+                    j += G;
+                    if (!__any(j < j_end)) break;
+                    load_codes(clamped(j + G), buf_a);
+                    process(buf_b);
+                    j += G;
+                    if (!__any(j < j_end)) break;
+                }
+            } else {
+                uint32_t buf_a[LW], buf_b[LW], buf_c[LW];
+                load_codes(clamped(j < 0 ? 0 : j), buf_a);
+                load_codes(clamped(j + G), buf_b);
+                for (;;) {
+                    load_codes(clamped(j + 2 * G), buf_c);
+                    process(buf_a);
+                    j += G;
+                    if (!__any(j < j_end)) break;
+                    load_codes(clamped(j + 2 * G), buf_a);
+                    process(buf_b);
+                    j += G;
+                    if (!__any(j < j_end)) break;
+                    load_codes(clamped(j + 2 * G), buf_b);
+                    process(buf_c);
+                    j += G;
+                    if (!__any(j < j_end)) break;
+                }
             }
 #pragma unroll
             for (int w = 0; w < W; ++w) {
@@ -440,12 +513,14 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
 #pragma unroll
                     for (int p = 0; p < P; ++p) mx[w][p] = 0;
                 }
-                // merge the G = 8 lanes of a document: mirror within the half row, then the two
+                // merge the G lanes of a document: (G = 8) mirror within the half row, then the two
                 // quad exchanges
                 uint32_t o[P];
+                if constexpr (G == 8) {
 #pragma unroll
-                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[w][p]);  // row_half_mirror
-                planes_max<P>(mx[w], o);
+                    for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[w][p]);  // row_half_mirror
+                    planes_max<P>(mx[w], o);
+                }
 #pragma unroll
                 for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[w][p]);   // quad_perm [1,0,3,2]
                 planes_max<P>(mx[w], o);
@@ -473,7 +548,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                             term = (uint32_t)(((uint64_t)a.q_weights[q_lo[w] + c0 + q] * term + 32768) >> 16);
                         part += term;
                     }
-                    part += dpp_mov<0x141>(part);  // row_half_mirror
+                    if constexpr (G == 8) part += dpp_mov<0x141>(part);  // row_half_mirror
                     part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
                     part += dpp_mov<0x4E>(part);   // quad_perm [2,3,0,1]
                     score = (int32_t)part;
@@ -529,7 +604,9 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     const uint32_t wave_docs = masklut_threads(L, CB, pair ? 2 : 1) / 64 * 8;  // one run of 8 documents per wave
     uint32_t dpb_min = wave_docs > 64 ? wave_docs : 64;
     while (dpb_min > wave_docs && (uint64_t)(dpb_min / 2) * mean_len >= 4096) dpb_min /= 2;
-    uint32_t dpb = LUT_DOCS;
+    // candidate lists are gathered from all over the code array and the kernel is bound by those reads:
+    // smaller workgroups (their start-up phases overlap better) measure faster as long as the table is small
+    uint32_t dpb = (a.cand_ids && (size_t)L * (1u << CB) * 4 <= 16 * 1024) ? LUT_DOCS / 2 : LUT_DOCS;
     while (dpb > dpb_min && ((a.max_scored + dpb - 1) / dpb) * gy < 4096) dpb /= 2;
     uint64_t bx = (a.max_scored + dpb - 1) / dpb;
     if (bx > 0x7fffffffull || a.n_queries > 65535) return hipErrorInvalidValue;
