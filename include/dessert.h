@@ -26,7 +26,11 @@
  *     and unchanged while the index is searched.
  *   - Asynchrony: all device work is enqueued on config.stream; calls return
  *     without synchronising.  Host arrays are read before the call returns.
- *     Outputs are valid once the caller has synchronised the stream.
+ *     Outputs are valid once the caller has synchronised the stream.  (One
+ *     copy runs on a stream the handle owns: the offsets upload of
+ *     dessert_build_index, beside the hash kernel; it starts after the work
+ *     config.stream held at entry and config.stream waits for it before the
+ *     call's work counts as done, so the caller sees stream order as usual.)
  *   - Errors: every call returns a status.  Argument errors are detected on
  *     the host before anything is launched (DESSERT_EINVAL), HIP failures
  *     give DESSERT_EHIP; dessert_last_error() returns a thread-local message.

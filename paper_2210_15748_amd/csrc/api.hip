@@ -80,6 +80,8 @@ struct dessert_index {
     uint64_t* h_offsets = nullptr;
     size_t h_offsets_cap = 0;
     hipEvent_t upload_done = nullptr;  // recorded after each offsets upload
+    hipStream_t copy_stream = nullptr; // library-owned: carries the offsets upload beside the hash kernel
+    hipEvent_t build_entry = nullptr;  // recorded on the caller's stream when dessert_build_index starts
     bool upload_pending = false;
     // pinned staging ring for the per-batch offset arrays of a search (keeps the uploads asynchronous)
     static constexpr unsigned kMetaSlots = 8;
@@ -396,6 +398,8 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
         if (e == hipSuccess) e = launch_repack_proj_f16((const float*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->upload_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->build_entry, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ix->copy_stream, hipStreamNonBlocking);
     if (e != hipSuccess) {
         dessert_destroy(ix);
         return fail(DESSERT_EHIP, "projection setup: %s", hipGetErrorString(e));
@@ -408,7 +412,12 @@ void dessert_destroy(dessert_index_t* ix) {
     if (!ix) return;
     DeviceGuard guard(ix->cfg.device);
     (void)hipStreamSynchronize(ix->stream);
+    if (ix->copy_stream) {
+        (void)hipStreamSynchronize(ix->copy_stream);
+        (void)hipStreamDestroy(ix->copy_stream);
+    }
     if (ix->upload_done) (void)hipEventDestroy(ix->upload_done);
+    if (ix->build_entry) (void)hipEventDestroy(ix->build_entry);
     if (ix->proj) (void)hipFree(ix->proj);
     if (ix->proj_mfma) (void)hipFree(ix->proj_mfma);
     if (ix->remap) (void)hipFree(ix->remap);
@@ -517,8 +526,11 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     ix->built = false;
     dessert_index::TimingSlot& ts = ix->begin_timed();
     if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
-    // The code layout does not depend on document boundaries, so hashing starts first and the
-    // host scans the lengths while the GPU works.
+    // The code layout does not depend on document boundaries, so hashing starts first, the host
+    // scans the lengths while the GPU works, and the offsets go up on the library's own stream
+    // beside the hash kernel: after whatever the caller's stream held at entry (it may still read
+    // offsets_dev), and the caller's stream waits for the upload at the end.
+    HIP_TRY(hipEventRecord(ix->build_entry, ix->stream));
     dessert_status_t st = run_hash(ix, vectors_dev, n_vectors, codes_dev);
     if (st != DESSERT_OK) return st;
     if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
@@ -541,8 +553,10 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
         run += lengths_host[i];
     }
     ix->h_offsets[n_docs] = run;
-    HIP_TRY(hipMemcpyAsync(offsets_dev, ix->h_offsets, (n_docs + 1) * 8, hipMemcpyHostToDevice, ix->stream));
-    HIP_TRY(hipEventRecord(ix->upload_done, ix->stream));
+    HIP_TRY(hipStreamWaitEvent(ix->copy_stream, ix->build_entry, 0));
+    HIP_TRY(hipMemcpyAsync(offsets_dev, ix->h_offsets, (n_docs + 1) * 8, hipMemcpyHostToDevice, ix->copy_stream));
+    HIP_TRY(hipEventRecord(ix->upload_done, ix->copy_stream));
+    HIP_TRY(hipStreamWaitEvent(ix->stream, ix->upload_done, 0));
     ix->upload_pending = true;
     if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
     ix->codes = codes_dev;
