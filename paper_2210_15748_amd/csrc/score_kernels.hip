@@ -227,7 +227,10 @@ constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2
 constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
 // Threads per workgroup: a mask table of 32 KB or more limits a CU to a few workgroups, so (where the
 // register budget allows: few tables) eight waves share one table instead of four.
-constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && L <= 16) ? 512 : 256; }
+constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && (L <= 16 || (L << CB) * 4 * W >= 64 * 1024)) ? 512 : 256; }
+// Waves per SIMD the register allocation must allow: the rotated form (L = 64) keeps 24 more per-lane
+// constants and would otherwise drop from 4 to 3.
+constexpr int masklut_min_waves(int L, int CW, int W) { return (L == 64 && CW == 1 && W == 1) ? 4 : 1; }
 constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
 
 // Per-workgroup bookkeeping placed after the mask table in dynamic LDS.
@@ -254,9 +257,32 @@ struct LutBlockMeta {
 // gz = chunk groups: with gz > 1 the 32-vector chunks of a query set are dealt round-robin to gz
 // workgroups, which add their partial sums into the (pre-zeroed) scores with integer atomics.
 // (SPLIT = false: gz is 1.)
+//
+// Rotated table order (L = 64, one-byte codes, one query set per workgroup).  LDS serves the 32 lanes of a
+// half-wave in one pass when their dwords lie in 32 different banks (bank = dword address mod 32).  With
+// M[t][h] the bank is the low bits of the code, i.e. random: a read takes about 2.4 passes, and with 64
+// reads per document vector this form is bound by LDS.  Here the table is stored code-major, row h =
+// the 64 masks {M[t][h]} at byte h * 256, and in any one read instruction the 32 lanes of a half-wave
+// ask for 32 different tables whose positions differ mod 32, so whatever their codes are they address
+// different banks.  A lane's read of register k (a dword of its code row), byte b, is for table
+//     t = 4 * (k ^ r0 ^ 4*a) + ((b + rb) & 3):
+//   a  (lane bits 2-3)  the lane loads the four 16-byte quarters of its code row in a permuted order;
+//   r0 (lane bit 4)     neighbouring registers are exchanged (one select per register);
+//   rb (lane bits 0-1)  the byte picked from the register is rotated - free, the byte index sits in
+//                       the per-lane selector of the v_perm that forms the address.
+// Table t sits at slot rot_slot(t) of a row: bit 1 of k, the one bit of t that the lanes of a read share,
+// moved to the top.  The address (h << 8) | (4 * slot) is one v_perm: byte 1 from the code register,
+// byte 0 from a per-lane constant.  (Measured on the fp16 stress preset: scoring 198 -> 102 ms.  The same
+// order for paired L = 32 tables, 8-byte slots, was 7 % slower than M[t][h]: that form is bound by the
+// vector ALU, not by LDS.)
+__device__ inline uint32_t rot_slot(uint32_t k, uint32_t b) {  // k = (k3 k2 k1 k0): slot (k1 k3 k2 k0 b1 b0)
+    return ((k >> 1) & 1) * 32 + ((k >> 3) & 1) * 16 + ((k >> 2) & 1) * 8 + (k & 1) * 4 + b;
+}
+
 template <int L, int CB, int CW, int REMAP, int W, bool SPLIT>
-__global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
+__global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW, W)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
                                                             uint32_t gz_arg) {
+    constexpr bool ROT = (L == 64 && CW == 1 && W == 1);
     const uint32_t gz = SPLIT ? gz_arg : 1u;
     constexpr int T = masklut_threads(L, CB, W);
     constexpr int LW = L * CW / 4;  // dwords per code row
@@ -267,7 +293,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
     // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
     constexpr int LUT_WORDS = L * STRIDE * W;
-    __shared__ __attribute__((aligned(8))) uint32_t lut[LUT_WORDS];  // [t][h][w]
+    __shared__ __attribute__((aligned(256))) uint32_t lut[LUT_WORDS];  // [t][h][w]; ROT: [h][pos(t)]
     __shared__ LutBlockMeta meta;
 
     // Which (document block, query-set group) this workgroup takes.  When every set scores every
@@ -313,7 +339,8 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
     };
     auto table_or = [&](int w, uint32_t i, uint32_t h) {
         const uint32_t q = i / L, t = i % L;
-        atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
+        if constexpr (ROT) atomicOr(&lut[h * 64 + rot_slot(t >> 2, t & 3)], 1u << q);
+        else atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
     };
     auto zero_table = [&]() {
         for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
@@ -379,6 +406,31 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
     if (have_doc) meta.order[atomicAdd(&meta.bin[my_class], 1u)] = (uint16_t)threadIdx.x;
 
     const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
+    // ROT: lane-dependent table order (see above)
+    uint32_t rot_sel[4], rot_posc[ROT ? LW : 1], rot_quarter[ROT ? LW / 4 : 1], rot_swap = 0;
+    if constexpr (ROT) {
+        const uint32_t rb = lane & 3, aq = (lane >> 2) & 3, r0 = (lane >> 4) & 1;
+        rot_swap = r0 ? ~0u : 0u;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) rot_sel[b] = 0x0c0c0000u | ((4 + ((b + rb) & 3)) << 8) | b;
+#pragma unroll
+        for (int q = 0; q < LW / 4; ++q) rot_quarter[q] = 16 * (q ^ aq);  // byte offset of the piece loaded into registers 4q..4q+3
+#pragma unroll
+        for (int k = 0; k < LW; ++k) {
+            rot_posc[k] = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                rot_posc[k] |= (rot_slot(k ^ r0 ^ (aq << 2), (b + rb) & 3) * 4) << (8 * b);
+        }
+        // keep the per-lane constants in registers (otherwise they are rebuilt inside the loop)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) asm volatile("" : "+v"(rot_sel[b]));
+#pragma unroll
+        for (int q = 0; q < LW / 4; ++q) asm volatile("" : "+v"(rot_quarter[q]));
+#pragma unroll
+        for (int k = 0; k < LW; ++k) asm volatile("" : "+v"(rot_posc[k]));
+        asm volatile("" : "+v"(rot_swap));
+    }
     for (uint32_t c0 = c_first; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
         if (c0 != c_first) {  // the first chunk's table was built above
             __syncthreads();  // previous chunk's readers are done
@@ -418,7 +470,13 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
             const uint8_t* doc_codes = a.codes + lo * (L * CW);
             auto load_codes = [&](int32_t j, uint32_t (&dst)[LW]) {  // j: row within the document, already clamped
                 const uint8_t* row = doc_codes + (uint32_t)j * (uint32_t)(L * CW);
-                if constexpr (LW % 4 == 0) {
+                if constexpr (ROT) {
+#pragma unroll
+                    for (int q = 0; q < LW / 4; ++q) {
+                        const v4i v = *(const v4i*)(doc_codes + ((uint32_t)j * (uint32_t)(L * CW) + rot_quarter[q]));
+                        dst[4 * q] = v.x; dst[4 * q + 1] = v.y; dst[4 * q + 2] = v.z; dst[4 * q + 3] = v.w;
+                    }
+                } else if constexpr (LW % 4 == 0) {
                     const v4i* src = (const v4i*)row;
 #pragma unroll
                     for (int w = 0; w < LW; w += 4) {
@@ -437,7 +495,11 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                 uint32_t off[L];  // byte offset of x's entry within each table
 #pragma unroll
                 for (int w = 0; w < LW; ++w) {
-                    if constexpr (CW == 1) {
+                    if constexpr (ROT) {
+                        const uint32_t v = select3(rot_swap, dw[w ^ 1], dw[w]);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) off[4 * w + b] = __builtin_amdgcn_perm(v, rot_posc[w], rot_sel[b]);
+                    } else if constexpr (CW == 1) {
                         off[4 * w + 0] = byte_shl<0>(dw[w], entry_shift);
                         off[4 * w + 1] = byte_shl<1>(dw[w], entry_shift);
                         off[4 * w + 2] = byte_shl<2>(dw[w], entry_shift);
@@ -450,7 +512,9 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W)) void score_masklut_kerne
                 uint32_t msk[W][L];
 #pragma unroll
                 for (int t = 0; t < L; ++t) {
-                    if constexpr (W == 1) {
+                    if constexpr (ROT) {
+                        msk[0][t] = *(const uint32_t*)(lut_bytes + off[t]);
+                    } else if constexpr (W == 1) {
                         msk[0][t] = *(const uint32_t*)(lut_bytes + t * STRIDE * 4 + off[t]);
                     } else {
                         uint2 e = *(const uint2*)(lut_bytes + t * STRIDE * 8 + off[t]);
