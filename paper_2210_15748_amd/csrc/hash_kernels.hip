@@ -334,25 +334,42 @@ hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int KS, int LT, int NT>  // KS = d/16 k-steps, LT = L/4 M-tiles, NT n-tiles of 32 vectors per wave
-__global__ __launch_bounds__(256) void hash_mfma_f16_kernel(const _Float16* __restrict__ X, uint64_t n,
+template <int KS, int LT, int NT, int WV>  // KS = d/16 k-steps, LT = L/4 M-tiles, NT n-tiles of 32 vectors per wave, WV waves per workgroup
+__global__ __launch_bounds__(WV * 64, 2) void hash_mfma_f16_kernel(const _Float16* __restrict__ X, uint64_t n,
                                                             const v8h* __restrict__ Rp, uint32_t cmask,
                                                             uint8_t* __restrict__ codes) {
     constexpr int D = KS * 16;
     constexpr int L = LT * 4;
     constexpr int OW = LT / 2;
     constexpr int TILE_FRAGS = 2 * KS * 64;  // 16-byte fragments of one M-tile (hi then lo)
-    __shared__ v8h sA[TILE_FRAGS];
+    constexpr int T = WV * 64;
+    constexpr int FPT = TILE_FRAGS / T;      // fragments each thread moves per tile
+    static_assert(TILE_FRAGS % T == 0, "a tile of R divides over the threads");
+    // two tiles of R in LDS: while the waves multiply tile mt, the next one is copied from global memory
+    // straight into the other buffer (global_load ... lds: no staging registers; a wave's 64 lanes fill
+    // 1 KB of consecutive LDS per instruction), one barrier per tile
+    __shared__ v8h sA[2][TILE_FRAGS];
+    auto copy_tile = [&](int mt, int buf) {
+#pragma unroll
+        for (int f = 0; f < FPT; ++f) {
+            const v8h* src = Rp + (size_t)mt * TILE_FRAGS + threadIdx.x + f * T;
+            v8h* dst = &sA[buf][(threadIdx.x & ~63) + f * T];  // wave-uniform; lane i lands 16*i bytes further
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        }
+    };
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int col = lane & 31;
     const int g = lane >> 5;
-    const uint64_t block_vecs = 4 * 32 * NT;
+    const uint64_t block_vecs = WV * 32 * NT;
     const uint64_t n_blocks = (n + block_vecs - 1) / block_vecs;
 
     for (uint64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
         const uint64_t v0 = blk * block_vecs + (uint64_t)wave * 32 * NT;
+        __syncthreads();  // every wave is done with both buffers (previous block of vectors)
+        copy_tile(0, 0);
         v8h b[NT][KS];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -367,56 +384,61 @@ __global__ __launch_bounds__(256) void hash_mfma_f16_kernel(const _Float16* __re
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int w = 0; w < OW; ++w) outw[nt][w] = 0;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
 
+        uint32_t word[NT];
 #pragma unroll 1
-        for (int mp = 0; mp < OW; ++mp) {
-            uint32_t word[NT];
+        for (int mt = 0; mt < LT; ++mt) {
+            const int h = mt & 1;
+            const v8h* tile = sA[h];
+            // the other buffer was last read during tile mt-1, before the barrier that ended it
+            if (mt + 1 < LT) copy_tile(mt + 1, h ^ 1);
+            if (h == 0) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) word[nt] = 0;
-#pragma unroll 1
-            for (int h = 0; h < 2; ++h) {
-                const int mt = mp * 2 + h;
-                __syncthreads();  // every wave is done with the previous tile of R
-                for (int i = threadIdx.x; i < TILE_FRAGS; i += 256) sA[i] = Rp[(size_t)mt * TILE_FRAGS + i];
-                __syncthreads();
-                v16f accH[NT], accL[NT];
+                for (int nt = 0; nt < NT; ++nt) word[nt] = 0;
+            }
+            v16f accH[NT], accL[NT];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        accH[nt][r] = 0.f;
-                        accL[nt][r] = 0.f;
-                    }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    v8h ah = sA[ks * 64 + lane];
-                    v8h al = sA[(KS + ks) * 64 + lane];
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        accH[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, b[nt][ks], accH[nt], 0, 0, 0);
-                        accL[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b[nt][ks], accL[nt], 0, 0, 0);
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    accH[nt][r] = 0.f;
+                    accL[nt][r] = 0.f;
                 }
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+            for (int ks = 0; ks < KS; ++ks) {
+                v8h ah = tile[ks * 64 + lane];
+                v8h al = tile[(KS + ks) * 64 + lane];
 #pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        uint32_t neg = 0;
+                for (int nt = 0; nt < NT; ++nt) {
+                    accH[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, b[nt][ks], accH[nt], 0, 0, 0);
+                    accL[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b[nt][ks], accL[nt], 0, 0, 0);
+                }
+            }
 #pragma unroll
-                        for (int c = 7; c >= 0; --c) {
-                            float p = __builtin_fmaf(accL[nt][8 * s + c], 1.0f / 2048.0f, accH[nt][8 * s + c]);
-                            neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(p), 31);  // sign bit: p < 0
-                        }
-                        uint32_t code = ~neg & cmask;
-                        word[nt] |= code << (8 * (2 * h + s));
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    uint32_t neg = 0;
+#pragma unroll
+                    for (int c = 7; c >= 0; --c) {
+                        float p = __builtin_fmaf(accL[nt][8 * s2 + c], 1.0f / 2048.0f, accH[nt][8 * s2 + c]);
+                        neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(p), 31);  // sign bit: p < 0
                     }
-            }
+                    uint32_t code = ~neg & cmask;
+                    word[nt] |= code << (8 * (2 * h + s2));
+                }
+            if (h == 1) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+                for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-                for (int w = 0; w + 1 < OW; ++w) outw[nt][w] = outw[nt][w + 1];
-                outw[nt][OW - 1] = word[nt];
+                    for (int w = 0; w + 1 < OW; ++w) outw[nt][w] = outw[nt][w + 1];
+                    outw[nt][OW - 1] = word[nt];
+                }
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's part of tile mt+1 has landed
+            __syncthreads();  // tile mt+1 is in place, and nobody reads tile mt any more
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -473,11 +495,14 @@ template <int KS, int LT>
 static hipError_t launch_mfma_f16_t(const void* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
                                     hipStream_t stream) {
     constexpr int NT = 2;
-    const uint64_t block_vecs = 4 * 32 * NT;
+    // eight waves share each staged tile of R when a tile is large (d = 256: 32 KB), four otherwise
+    constexpr int WV = KS >= 16 ? 8 : 4;
+    const uint64_t block_vecs = WV * 32 * NT;
     uint64_t blocks = (n + block_vecs - 1) / block_vecs;
-    if (blocks > 512) blocks = 512;  // persistent workgroups: 256 CUs x 2
-    auto kern = hash_mfma_f16_kernel<KS, LT, NT>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, stream, (const _Float16*)X, n, (const v8h*)Rp,
+    const uint64_t persistent = 256 * (8 / WV);  // 256 CUs x 8 waves
+    if (blocks > persistent) blocks = persistent;
+    auto kern = hash_mfma_f16_kernel<KS, LT, NT, WV>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WV * 64), 0, stream, (const _Float16*)X, n, (const v8h*)Rp,
                        (1u << C) - 1u, codes);
     return hipGetLastError();
 }
