@@ -59,17 +59,19 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_merge_kernel(TopkArgs a, Ke
         write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
 }
 
-// one workgroup per stored list whose length is read from device memory
-__global__ __launch_bounds__(TOPK_THREADS) void topk_lists_kernel(const uint64_t* __restrict__ lists, uint64_t list_stride,
-                                                                  const uint32_t* __restrict__ counts, uint32_t k,
-                                                                  KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
-                                                                  int32_t* __restrict__ out_scores) {
+// one workgroup per stored list whose length is read from device memory.  There are only as many workgroups
+// as lists, so each is wide and keeps many loads in flight: a pass over a list is a few round trips.
+constexpr uint32_t TOPK_LIST_THREADS = 1024;
+__global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const uint64_t* __restrict__ lists, uint64_t list_stride,
+                                                                       const uint32_t* __restrict__ counts, uint32_t k,
+                                                                       KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
+                                                                       int32_t* __restrict__ out_scores) {
     extern __shared__ uint64_t sorted[];
     __shared__ SelectShared sh;
     const uint32_t b = blockIdx.x;
     StoredKeys keys{lists + (size_t)b * list_stride};
-    block_select<TOPK_THREADS>(keys, counts[b], k, kpad, sorted, sh, plan);
-    for (uint32_t i = threadIdx.x; i < k; i += TOPK_THREADS)
+    block_select<TOPK_LIST_THREADS, StoredKeys, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+    for (uint32_t i = threadIdx.x; i < k; i += TOPK_LIST_THREADS)
         write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
 }
 
@@ -96,7 +98,7 @@ hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const 
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(topk_lists_kernel, dim3(n_queries), dim3(TOPK_THREADS), lds, stream, lists, list_stride, counts, k,
+    hipLaunchKernelGGL(topk_lists_kernel, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists, list_stride, counts, k,
                        plan, kpad, out_ids, out_scores);
     return hipGetLastError();
 }

@@ -78,8 +78,9 @@ struct SelectShared {
 
 // Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
 // T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
+// U = key loads a thread keeps in flight while it scans the list (a pass over n keys is n / (T*U) round trips).
 // sorted: kpad = next power of two >= max(k, 2) entries of LDS.
-template <int T, typename Keys>
+template <int T, typename Keys, int U = 4>
 __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
                              SelectShared& sh, const KeyPlan& plan) {
     const uint32_t tid = threadIdx.x;
@@ -103,14 +104,30 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             __syncthreads();
             const uint64_t prefix = sh.prefix;
             const uint32_t need = sh.need;
-            for (uint64_t i = tid; i < n; i += 4 * T) {  // four loads in flight per thread
-                uint64_t key[4];
+            for (uint64_t i = tid; i < n; i += U * T) {  // U loads in flight per thread
+                uint64_t key[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
+                for (int u = 0; u < U; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (i + u * T < n && (key[u] >> (shift + width)) == prefix)
-                        atomicAdd(&sh.hist[(uint32_t)(key[u] >> shift) & dmask], 1u);
+                for (int u = 0; u < U; ++u) {
+                    const bool in = i + u * T < n && (key[u] >> (shift + width)) == prefix;
+                    const uint32_t bin = (uint32_t)(key[u] >> shift) & dmask;
+                    if (d == 0) {
+                        // the leading digit holds the score's top bits and few values occur: lanes with the same
+                        // bin add once (a few rounds of "first lane's bin, who else has it"), the rest singly
+                        uint64_t todo = __ballot(in);
+                        for (int r = 0; r < 4 && todo; ++r) {
+                            const uint32_t first = (uint32_t)__builtin_ctzll(todo);
+                            const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)bin, (int)first);
+                            const uint64_t same = __ballot(in && bin == v) & todo;
+                            if (lane == first) atomicAdd(&sh.hist[v], (uint32_t)__builtin_popcountll(same));
+                            todo &= ~same;
+                        }
+                        if (in && ((todo >> lane) & 1)) atomicAdd(&sh.hist[bin], 1u);
+                    } else if (in) {
+                        atomicAdd(&sh.hist[bin], 1u);
+                    }
+                }
             }
             __syncthreads();
             // digit D with  count(digits > D) < need <= count(digits >= D):
@@ -146,12 +163,12 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         }
         const uint64_t kth = sh.prefix;   // the k-th largest key
         const uint32_t need_eq = sh.need;  // copies of it that belong to the result
-        for (uint64_t i = tid; i < n; i += 4 * T) {
-            uint64_t key[4];
+        for (uint64_t i = tid; i < n; i += U * T) {
+            uint64_t key[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
+            for (int u = 0; u < U; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) {
                 if (i + u * T >= n) continue;
                 if (key[u] > kth) {
                     sorted[atomicAdd(&sh.count, 1u)] = key[u];

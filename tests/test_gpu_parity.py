@@ -210,6 +210,65 @@ def test_scores_masklut_other_shapes(L, Cb):
     assert np.array_equal(got[1], orc.scores(dc, off, qc[20:]))
 
 
+@pytest.mark.parametrize("L,Cb", [(8, 7), (16, 6), (32, 7), (64, 8), (128, 6)])
+def test_scores_short_documents_at_every_line_alignment(L, Cb):
+    """The scoring rounds start on 128-byte lines of the code array: documents of 1..12 vectors placed so that
+    every start position modulo a line occurs, first and last documents included, candidate lists and all documents."""
+    say(f"scores short documents at every alignment L={L} C={Cb}")
+    rng = np.random.default_rng(900 + L)
+    d = 64
+    lens = np.concatenate([np.arange(1, 13), rng.integers(1, 13, 400), [1, 1, 1, 2, 3, 5, 7, 11, 12, 1]]).astype(np.int64)
+    V = int(lens.sum())
+    off = np.concatenate([[0], np.cumsum(lens)])
+    rows_per_line = max(1, 128 // L)
+    assert len(set((off[:-1] % rows_per_line).tolist())) == rows_per_line
+    pool = rng.integers(-127, 128, (30, d))
+    X = np.clip(pool[rng.integers(0, 30, V)] + rng.integers(-25, 26, (V, d)), -127, 127).astype(np.int8)
+    q_lens = np.array([32, 9, 40], dtype=np.int64)
+    Q = np.clip(pool[rng.integers(0, 30, int(q_lens.sum()))] + rng.integers(-25, 26, (int(q_lens.sum()), d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_AUTO, dz.SCORE_MASKLUT)
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens).cpu().numpy()
+    for b in range(len(q_lens)):
+        assert np.array_equal(got[b], orc.scores(dc, off, qc[qo[b]:qo[b + 1]])), b
+    n = len(lens)
+    cands = [rng.permutation(n)[:137], np.array([0, n - 1, n - 2, 1]), rng.integers(0, n, 300)]
+    co = np.concatenate([[0], np.cumsum([len(c) for c in cands])])
+    flat = torch.from_numpy(np.concatenate(cands).astype(np.int32)).to(DEV)
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens, cand_ids=flat, cand_offsets=co).cpu().numpy()
+    for b, c in enumerate(cands):
+        assert np.array_equal(got[co[b]:co[b + 1]], orc.scores(dc, off, qc[qo[b]:qo[b + 1]], c)), b
+
+
+def test_build_index_again_on_the_same_handle():
+    """Two builds in a row on one handle (the offsets travel on the library's own stream beside the hash kernel),
+    each searched straight away without a synchronisation in between."""
+    say("build_index twice on one handle, search after each")
+    rng = np.random.default_rng(4242)
+    d, L, Cb = 128, 32, 7
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    Q = rng.integers(-127, 128, (32, d)).astype(np.int8)
+    qc = orc.hash_i8(Q, R, L, Cb)
+    codes = offsets = None
+    for n_docs, lo, hi in [(5000, 1, 40), (1200, 8, 100), (7000, 1, 12)]:
+        lens = rng.integers(lo, hi, n_docs).astype(np.int64)
+        X = rng.integers(-127, 128, (int(lens.sum()), d)).astype(np.int8)
+        X[rng.integers(0, len(X), 64)] = Q[rng.integers(0, 32, 64)]     # some exact copies of query vectors
+        codes, offsets = dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+        ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), [32], 20)
+        dc = orc.hash_i8(X, R, L, Cb)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        assert np.array_equal(offsets.cpu().numpy(), off)
+        want_ids, want_sc, _ = orc.search(dc, off, [qc], 20)
+        assert np.array_equal(ids.cpu().numpy(), want_ids)
+        assert np.array_equal(sc.cpu().numpy(), want_sc)
+
+
 # ------------------------------------------------------------------ top-k and whole search
 def check_search(w, tag, score_algo=dz.SCORE_AUTO):
     p = w.preset
