@@ -63,6 +63,8 @@ struct dessert_index {
     void* f_cent = nullptr;
     void* f_table = nullptr;
     uint32_t* f_cursor = nullptr;
+    uint32_t* f_sub_off = nullptr;   // [K*S+1] sub-bucket starts (library-owned)
+    FilterSubPlan f_sub{1, 15};
     uint32_t f_K = 0;
     const uint32_t* f_bucket_off = nullptr;   // caller's
     const uint32_t* f_bucket_docs = nullptr;  // caller's
@@ -424,6 +426,7 @@ void dessert_destroy(dessert_index_t* ix) {
     if (ix->f_cent) (void)hipFree(ix->f_cent);
     if (ix->f_table) (void)hipFree(ix->f_table);
     if (ix->f_cursor) (void)hipFree(ix->f_cursor);
+    if (ix->f_sub_off) (void)hipFree(ix->f_sub_off);
     if (ix->h_offsets) (void)hipHostFree(ix->h_offsets);
     for (auto& slot : ix->slots)
         for (auto& ev : slot.ev)
@@ -612,17 +615,21 @@ dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroi
     if (ix->f_cent) (void)hipFree(ix->f_cent);
     if (ix->f_table) (void)hipFree(ix->f_table);
     if (ix->f_cursor) (void)hipFree(ix->f_cursor);
+    if (ix->f_sub_off) (void)hipFree(ix->f_sub_off);
     ix->f_cent = ix->f_table = nullptr;
-    ix->f_cursor = nullptr;
+    ix->f_cursor = ix->f_sub_off = nullptr;
+    ix->f_sub = filter_sub_plan(ix->n_docs, n_centroids);
+    const size_t n_sub = (size_t)n_centroids * ix->f_sub.S;
     hipError_t e = hipMalloc(&ix->f_cent, filter_centroid_bytes(n_centroids, ix->cfg.d));
     if (e == hipSuccess) e = hipMalloc(&ix->f_table, filter_table_bytes(n_centroids));
-    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_cursor, (size_t)n_centroids * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_cursor, n_sub * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_sub_off, (n_sub + 1) * 4);
     if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipMalloc(filter state): %s", hipGetErrorString(e));
     HIP_TRY(launch_filter_prep(centroids_dev, n_centroids, ix->cfg.d, ix->f_cent, ix->f_table, ix->stream));
     HIP_TRY(launch_filter_assign((const int8_t*)vectors_dev, ix->n_vectors, ix->cfg.d, n_centroids, ix->f_cent,
                                  ix->f_table, assign_dev, ix->stream));
-    HIP_TRY(launch_filter_buckets(assign_dev, ix->offsets, ix->n_docs, n_centroids, ix->f_cursor, bucket_offsets_dev,
-                                  bucket_docs_dev, ix->stream));
+    HIP_TRY(launch_filter_buckets(assign_dev, ix->offsets, ix->n_docs, n_centroids, ix->f_sub, ix->f_cursor, ix->f_sub_off,
+                                  bucket_offsets_dev, bucket_docs_dev, ix->stream));
     {   // the largest bucket bounds how many documents one query set can hit (sizes the query workspace)
         std::vector<uint32_t> off((size_t)n_centroids + 1);
         HIP_TRY(hipMemcpyAsync(off.data(), bucket_offsets_dev, off.size() * 4, hipMemcpyDeviceToHost, ix->stream));
@@ -769,7 +776,7 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
         HIP_TRY(launch_filter_probe(dist, total_q, ix->f_K, filter_probe, probe_ids, ix->stream));
     }
     HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, max_q * filter_probe, d_q_off, q_uniform, n_queries,
-                                ix->f_bucket_off, ix->f_bucket_docs, ix->n_docs, lists, w.list_stride, cursor,
+                                ix->f_sub_off, ix->f_sub, ix->f_bucket_docs, ix->n_docs, lists, w.list_stride, cursor,
                                 ix->stream));
     HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
                               ix->n_docs ? ix->n_docs - 1 : 0, out_ids_dev, out_counts_dev, ix->stream));

@@ -247,13 +247,15 @@ __global__ __launch_bounds__(256) void filter_merge_kernel(const int64_t* __rest
 // ---------------------------------------------------------------------------
 // Inverted index.  One wave per document; a vector is the first of its document with its
 // centroid if no earlier vector of the document has the same one (a bucket holds a document
-// once).  FILL = false counts bucket sizes; FILL = true writes document ids at
-// offsets[c] + (atomic cursor), so the order inside a bucket is unspecified.
+// once).  A document goes to sub-bucket c*S + (doc >> sub_shift) of its centroid c.  FILL = false counts
+// sub-bucket sizes; FILL = true writes document ids at sub_off[...] + (atomic cursor), so the order inside
+// a sub-bucket is unspecified.
 template <bool FILL>
 __global__ __launch_bounds__(256) void filter_bucket_kernel(const uint32_t* __restrict__ assign,
                                                             const uint64_t* __restrict__ doc_off, uint64_t n_docs,
+                                                            uint32_t S, uint32_t sub_shift,
                                                             uint32_t* __restrict__ size_or_cursor,
-                                                            const uint32_t* __restrict__ bucket_off,
+                                                            const uint32_t* __restrict__ sub_off,
                                                             uint32_t* __restrict__ bucket_docs) {
     const uint32_t lane = threadIdx.x & 63;
     for (uint64_t doc = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6); doc < n_docs; doc += (uint64_t)gridDim.x * 4) {
@@ -271,8 +273,9 @@ __global__ __launch_bounds__(256) void filter_bucket_kernel(const uint32_t* __re
                 }
             }
             if (first) {
-                uint32_t pos = atomicAdd(&size_or_cursor[c], 1u);
-                if constexpr (FILL) bucket_docs[bucket_off[c] + pos] = (uint32_t)doc;
+                const uint32_t sub = c * S + (uint32_t)(doc >> sub_shift);
+                uint32_t pos = atomicAdd(&size_or_cursor[sub], 1u);
+                if constexpr (FILL) bucket_docs[sub_off[sub] + pos] = (uint32_t)doc;
             }
         }
     }
@@ -310,6 +313,13 @@ __global__ __launch_bounds__(1024) void filter_scan_kernel(uint32_t* __restrict_
     if (tid == 0) off[K] = carry;
 }
 
+// bucket_off[c] = sub_off[c*S] for c = 0..K: the caller-visible bucket starts
+__global__ void filter_bucket_starts_kernel(const uint32_t* __restrict__ sub_off, uint32_t K, uint32_t S,
+                                            uint32_t* __restrict__ bucket_off) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c <= K) bucket_off[c] = sub_off[(size_t)c * S];
+}
+
 // ---------------------------------------------------------------------------
 // Query side.
 struct DistKeys {  // key = (value + bias) above the centroid id: closest first, lower id first
@@ -340,13 +350,14 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
 // Bucket counting without global atomics.  Workgroup (slab, query set) owns the documents
 // [slab * slab_docs, +slab_docs) and keeps one counter per document in LDS (W bytes each, packed into
 // 32-bit words; a count never exceeds the number of probed buckets, which the host bounds by the
-// counter range).  It streams every bucket its query set probes, counts the ids that fall into its
-// slab, and appends one key per document hit, (count, id) in the top-k key format, to the query set's
+// counter range).  It streams, of every bucket its query set probes, the sub-buckets that overlap its slab,
+// counts the ids that fall into the slab, and appends one key per document hit, (count, id) in the top-k key format, to the query set's
 // list; cursor[b] ends as the number of distinct documents hit.  The order inside a list is unspecified.
 template <int W, int T>
 __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
                                                             const uint32_t* __restrict__ q_off, uint32_t q_uniform,
-                                                            const uint32_t* __restrict__ bucket_off,
+                                                            const uint32_t* __restrict__ sub_off, uint32_t S,
+                                                            uint32_t sub_shift,
                                                             const uint32_t* __restrict__ bucket_docs, uint64_t n_docs,
                                                             uint32_t slab_docs, uint32_t id_bits,
                                                             uint64_t* __restrict__ lists, uint64_t list_stride,
@@ -367,6 +378,10 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
     const uint32_t q_hi = q_uniform ? q_lo + q_uniform : q_off[b + 1];
     const uint32_t pairs = (q_hi - q_lo) * probe;
     const uint32_t* mine = probe_ids + (uint64_t)q_lo * probe;
+    // the sub-buckets that overlap this slab's document range (whole sub-buckets: ids outside the slab are skipped below)
+    const uint32_t s_lo = doc0 >> sub_shift;
+    uint32_t s_hi = (uint32_t)(((uint64_t)doc0 + here + ((1u << sub_shift) - 1)) >> sub_shift);
+    s_hi = s_hi < S ? s_hi : S;
     // one wave per probed bucket; a wave first fetches the bounds of up to 64 of its buckets (one per lane),
     // so the dependent loads id -> offsets are paid once, not once per bucket
     for (uint32_t p0 = wave; p0 < pairs; p0 += WAVES * 64) {
@@ -375,8 +390,8 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
         if (myp < pairs) {
             const uint32_t c = mine[myp];
             if (c != 0xFFFFFFFFu) {
-                lo_l = bucket_off[c];
-                hi_l = bucket_off[c + 1];
+                lo_l = sub_off[(size_t)c * S + s_lo];
+                hi_l = sub_off[(size_t)c * S + s_hi];
             }
         }
         const uint32_t left = (pairs - p0 + WAVES - 1) / WAVES;
@@ -592,17 +607,36 @@ hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, ui
     return hipGetLastError();
 }
 
+FilterSubPlan filter_sub_plan(uint64_t n_docs, uint32_t K) {
+    // ranges of 32768 documents (the smallest slab of the counting kernel), wider while K*S would pass 2^22 entries
+    FilterSubPlan sp{1, 15};
+    for (;;) {
+        const uint64_t S = n_docs ? ((n_docs - 1) >> sp.sub_shift) + 1 : 1;
+        if (S * K <= (1ull << 22) || sp.sub_shift >= 31) {
+            sp.S = (uint32_t)S;
+            return sp;
+        }
+        ++sp.sub_shift;
+    }
+}
+
 hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off, uint64_t n_docs, uint32_t K,
-                                 uint32_t* cursor, uint32_t* bucket_off, uint32_t* bucket_docs, hipStream_t stream) {
+                                 FilterSubPlan sp, uint32_t* cursor, uint32_t* sub_off, uint32_t* bucket_off,
+                                 uint32_t* bucket_docs, hipStream_t stream) {
     uint64_t blocks = (n_docs + 3) / 4;
     if (blocks > 65536) blocks = 65536;
     if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(filter_zero_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, (int32_t*)cursor, (uint64_t)K);
+    const uint64_t KS = (uint64_t)K * sp.S;
+    if (KS > 0x7fffffffull) return hipErrorInvalidValue;
+    uint64_t zb = (KS + 255) / 256;
+    if (zb > 65536) zb = 65536;
+    hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)zb), dim3(256), 0, stream, (int32_t*)cursor, KS);
     hipLaunchKernelGGL(filter_bucket_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, assign, doc_off, n_docs,
-                       cursor, bucket_off, bucket_docs);
-    hipLaunchKernelGGL(filter_scan_kernel, dim3(1), dim3(1024), 0, stream, cursor, K, bucket_off);
+                       sp.S, sp.sub_shift, cursor, sub_off, bucket_docs);
+    hipLaunchKernelGGL(filter_scan_kernel, dim3(1), dim3(1024), 0, stream, cursor, (uint32_t)KS, sub_off);
     hipLaunchKernelGGL(filter_bucket_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, assign, doc_off, n_docs,
-                       cursor, bucket_off, bucket_docs);
+                       sp.S, sp.sub_shift, cursor, sub_off, bucket_docs);
+    hipLaunchKernelGGL(filter_bucket_starts_kernel, dim3(K / 256 + 1), dim3(256), 0, stream, sub_off, K, sp.S, bucket_off);
     return hipGetLastError();
 }
 
@@ -622,9 +656,9 @@ constexpr uint32_t FILTER_SLAB_BYTES = 128 * 1024;  // LDS counters of one workg
 constexpr int FILTER_COUNT_THREADS = 1024;
 
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
-                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
-                               const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists, uint64_t list_stride,
-                               uint32_t* cursor, hipStream_t stream) {
+                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
+                               FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
+                               uint64_t list_stride, uint32_t* cursor, hipStream_t stream) {
     if (n_queries == 0) return hipSuccess;
     if (n_queries > 65535 || n_docs > 0xFFFFFFFEull) return hipErrorInvalidValue;
     hipLaunchKernelGGL(filter_zero_kernel, dim3((n_queries + 255) / 256), dim3(256), 0, stream, (int32_t*)cursor,
@@ -645,14 +679,14 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
     for (hipError_t e : attr)
         if (e != hipSuccess) return e;
     if (W == 1)
-        hipLaunchKernelGGL((filter_count_kernel<1, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
-                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
+        hipLaunchKernelGGL((filter_count_kernel<1, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
+                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
     else if (W == 2)
-        hipLaunchKernelGGL((filter_count_kernel<2, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
-                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
+        hipLaunchKernelGGL((filter_count_kernel<2, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
+                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
     else
-        hipLaunchKernelGGL((filter_count_kernel<4, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, bucket_off,
-                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
+        hipLaunchKernelGGL((filter_count_kernel<4, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
+                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
     return hipGetLastError();
 }
 

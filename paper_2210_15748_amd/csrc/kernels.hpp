@@ -90,17 +90,25 @@ FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe);
 hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                      uint32_t probe, const FilterProbePlan& plan, int64_t* lists, uint32_t* probe_ids,
                                      hipStream_t stream);
+// A bucket is stored as S sub-buckets by document range (sub-bucket s of centroid c holds the bucket's documents
+// with id >> sub_shift == s), so that a query-side workgroup that counts one range of documents reads only that
+// part of every bucket it probes.  sub_off [K*S+1] are the sub-bucket starts in bucket_docs; bucket_off[c] = sub_off[c*S].
+struct FilterSubPlan {
+    uint32_t S;          // sub-buckets per bucket
+    uint32_t sub_shift;  // log2 of the documents per sub-bucket range
+};
+FilterSubPlan filter_sub_plan(uint64_t n_docs, uint32_t K);
 hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off, uint64_t n_docs, uint32_t K,
-                                 uint32_t* cursor /*[K] scratch*/, uint32_t* bucket_off /*[K+1]*/, uint32_t* bucket_docs,
-                                 hipStream_t stream);
+                                 FilterSubPlan sp, uint32_t* cursor /*[K*S] scratch*/, uint32_t* sub_off /*[K*S+1]*/,
+                                 uint32_t* bucket_off /*[K+1]*/, uint32_t* bucket_docs, hipStream_t stream);
 hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K, uint32_t probe, uint32_t* probe_ids,
                                hipStream_t stream);
 // Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
 // max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
-                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* bucket_off,
-                               const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists, uint64_t list_stride,
-                               uint32_t* cursor /*[B], out*/, hipStream_t stream);
+                               const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
+                               FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
+                               uint64_t list_stride, uint32_t* cursor /*[B], out*/, hipStream_t stream);
 
 // ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
 struct TopkArgs {
