@@ -350,10 +350,16 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
 // Bucket counting without global atomics.  Workgroup (slab, query set) owns the documents
 // [slab * slab_docs, +slab_docs) and keeps one counter per document in LDS (W bytes each, packed into
 // 32-bit words; a count never exceeds the number of probed buckets, which the host bounds by the
-// counter range).  It streams, of every bucket its query set probes, the sub-buckets that overlap its slab,
-// counts the ids that fall into the slab, and appends one key per document hit, (count, id) in the top-k key format, to the query set's
-// list; cursor[b] ends as the number of distinct documents hit.  The order inside a list is unspecified.
-template <int W, int T>
+// counter range).  It reads, of every bucket its query set probes, the sub-buckets that overlap its slab
+// (a wave takes its buckets' ranges as one concatenated run, so all its loads are in flight together),
+// counts the ids that fall into the slab, and remembers each document at its first hit in a queue.  Then
+// one key (count, id) in the top-k key format per queued document goes to the query set's list;
+// cursor[b] ends as the number of distinct documents hit.  The order inside a list is unspecified.
+// Only if the queue overflows (more than FILTER_QUEUE distinct documents of one slab hit) are the counters
+// scanned instead.
+constexpr uint32_t FILTER_QUEUE = 4096;  // first-hit queue entries per workgroup (positions within the slab: QT = u16, or u32 for slabs over 65536 documents)
+
+template <int W, int T, typename QT>
 __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
                                                             const uint32_t* __restrict__ q_off, uint32_t q_uniform,
                                                             const uint32_t* __restrict__ sub_off, uint32_t S,
@@ -363,8 +369,9 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
                                                             uint64_t* __restrict__ lists, uint64_t list_stride,
                                                             uint32_t* __restrict__ cursor) {
     extern __shared__ uint32_t cnt[];
+    __shared__ QT queue[FILTER_QUEUE];
     __shared__ uint32_t wsum[16];
-    __shared__ uint32_t base_sh;
+    __shared__ uint32_t base_sh, q_count;
     constexpr uint32_t PER = 4 / W, BITS = 8 * W, WAVES = T / 64;
     constexpr uint32_t MASK = W == 4 ? 0xFFFFFFFFu : (1u << (BITS % 32)) - 1;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -372,8 +379,6 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
     const uint32_t doc0 = blockIdx.x * slab_docs;
     const uint32_t here = n_docs - doc0 < slab_docs ? (uint32_t)(n_docs - doc0) : slab_docs;
     const uint32_t words = (here + PER - 1) / PER;
-    for (uint32_t i = tid; i < words; i += T) cnt[i] = 0;
-    __syncthreads();
     const uint32_t q_lo = q_uniform ? b * q_uniform : q_off[b];
     const uint32_t q_hi = q_uniform ? q_lo + q_uniform : q_off[b + 1];
     const uint32_t pairs = (q_hi - q_lo) * probe;
@@ -382,38 +387,90 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
     const uint32_t s_lo = doc0 >> sub_shift;
     uint32_t s_hi = (uint32_t)(((uint64_t)doc0 + here + ((1u << sub_shift) - 1)) >> sub_shift);
     s_hi = s_hi < S ? s_hi : S;
-    // one wave per probed bucket; a wave first fetches the bounds of up to 64 of its buckets (one per lane),
-    // so the dependent loads id -> offsets are paid once, not once per bucket
-    for (uint32_t p0 = wave; p0 < pairs; p0 += WAVES * 64) {
+    // first batch of this wave's buckets: lane l takes pair wave + l*WAVES; its bounds are requested before the
+    // counters are cleared
+    auto bounds = [&](uint32_t p0, uint32_t& lo_l, uint32_t& n_l) {
         const uint32_t myp = p0 + lane * WAVES;
-        uint32_t lo_l = 0, hi_l = 0;
+        lo_l = n_l = 0;
         if (myp < pairs) {
             const uint32_t c = mine[myp];
             if (c != 0xFFFFFFFFu) {
                 lo_l = sub_off[(size_t)c * S + s_lo];
-                hi_l = sub_off[(size_t)c * S + s_hi];
+                n_l = sub_off[(size_t)c * S + s_hi] - lo_l;
             }
         }
+    };
+    uint32_t lo_l, n_l;
+    bounds(wave, lo_l, n_l);
+    for (uint32_t i = tid; i < words; i += T) cnt[i] = 0;
+    if (tid == 0) q_count = 0;
+    __syncthreads();
+    for (uint32_t p0 = wave; p0 < pairs; p0 += WAVES * 64) {
+        if (p0 != wave) bounds(p0, lo_l, n_l);
+        // concatenate the ranges: inclusive prefix of the sizes over the lanes
+        uint32_t incl = n_l;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t y = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += y;
+        }
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         const uint32_t left = (pairs - p0 + WAVES - 1) / WAVES;
-        const uint32_t cnt_here = left < 64 ? left : 64;
-        for (uint32_t j = 0; j < cnt_here; ++j) {
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)lo_l, (int)j);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)hi_l, (int)j);
-            constexpr int U = 16;  // loads in flight per lane: a bucket of up to 1024 documents is one round trip
-            for (uint32_t e = lo + lane; e < hi; e += 64 * U) {
-                uint32_t id[U];
+        const uint32_t n_ranges = left < 64 ? left : 64;
+        constexpr int U = 8;  // elements per lane per trip
+        for (uint32_t f0 = 0; f0 < total; f0 += 64 * U) {
+            uint32_t id[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) id[u] = e + 64 * u < hi ? bucket_docs[e + 64 * u] : 0xFFFFFFFFu;
+            for (int u = 0; u < U; ++u) {
+                // element f of the concatenated run: the range j with excl_j <= f < incl_j
+                const uint32_t f = f0 + u * 64 + lane;
+                uint32_t addr = 0xFFFFFFFFu;
+                if (f < total) {
+                    for (uint32_t j = 0; j < n_ranges; ++j) {
+                        const uint32_t in_j = (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)j);
+                        const uint32_t n_j = (uint32_t)__builtin_amdgcn_readlane((int)n_l, (int)j);
+                        if (addr == 0xFFFFFFFFu && f < in_j)
+                            addr = (uint32_t)__builtin_amdgcn_readlane((int)lo_l, (int)j) + (f - (in_j - n_j));
+                    }
+                }
+                id[u] = addr != 0xFFFFFFFFu ? bucket_docs[addr] : 0xFFFFFFFFu;
+            }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t local = id[u] - doc0;  // wraps to a large value for ids below the slab
-                    if (id[u] != 0xFFFFFFFFu && local < here)
-                        atomicAdd(&cnt[local / PER], 1u << ((local % PER) * BITS));
+            for (int u = 0; u < U; ++u) {
+                const uint32_t local = id[u] - doc0;  // wraps to a large value for ids below the slab
+                const bool hit = id[u] != 0xFFFFFFFFu && local < here;
+                bool first = false;
+                if (hit) {
+                    const uint32_t sh = (local % PER) * BITS;
+                    const uint32_t old = atomicAdd(&cnt[local / PER], 1u << sh);
+                    first = ((old >> sh) & MASK) == 0;
+                }
+                // documents hit for the first time go to the queue: one LDS atomic per wave
+                const uint64_t fm = __ballot(first);
+                if (fm) {
+                    uint32_t base = 0;
+                    if (lane == (uint32_t)__builtin_ctzll(fm)) base = atomicAdd(&q_count, (uint32_t)__builtin_popcountll(fm));
+                    base = (uint32_t)__builtin_amdgcn_readlane((int)base, __builtin_ctzll(fm));
+                    const uint32_t pos = base + (uint32_t)__builtin_popcountll(fm & ((1ull << lane) - 1));
+                    if (first && pos < FILTER_QUEUE) queue[pos] = (QT)local;
                 }
             }
         }
     }
     __syncthreads();
+    const uint32_t hits = q_count;
+    if (hits <= FILTER_QUEUE) {
+        if (tid == 0) base_sh = hits ? atomicAdd(&cursor[b], hits) : 0;
+        __syncthreads();
+        uint64_t* dst = lists + (uint64_t)b * list_stride + base_sh;
+        for (uint32_t i = tid; i < hits; i += T) {
+            const uint32_t local = queue[i];
+            const uint32_t c = (cnt[local / PER] >> ((local % PER) * BITS)) & MASK;
+            dst[i] = make_key((int32_t)c, doc0 + local, id_bits);
+        }
+        return;
+    }
+    // queue overflow: scan the counters
     uint32_t nz = 0;
     for (uint32_t i = tid; i < words; i += T) {
         const uint32_t x = cnt[i];
@@ -652,8 +709,20 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
     return hipGetLastError();
 }
 
-constexpr uint32_t FILTER_SLAB_BYTES = 128 * 1024;  // LDS counters of one workgroup
-constexpr int FILTER_COUNT_THREADS = 1024;
+constexpr uint32_t FILTER_SLAB_BYTES = 128 * 1024;  // most LDS counters one workgroup may hold (the queue takes up to 16 KB more)
+
+template <int W, int T, typename QT>
+static hipError_t launch_filter_count_t(dim3 grid, size_t lds, hipStream_t stream, const uint32_t* probe_ids, uint32_t probe,
+                                        const uint32_t* q_off, uint32_t q_uniform, const uint32_t* sub_off, FilterSubPlan sp,
+                                        const uint32_t* bucket_docs, uint64_t n_docs, uint32_t slab_docs, uint32_t id_bits,
+                                        uint64_t* lists, uint64_t list_stride, uint32_t* cursor) {
+    static hipError_t attr = hipFuncSetAttribute((const void*)filter_count_kernel<W, T, QT>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((filter_count_kernel<W, T, QT>), grid, dim3(T), lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
+                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, lists, list_stride, cursor);
+    return hipGetLastError();
+}
 
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
@@ -665,29 +734,30 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
                        (uint64_t)n_queries);
     if (n_docs == 0 || total_q == 0) return hipGetLastError();
     const uint32_t W = max_pairs <= 255 ? 1 : max_pairs <= 65535 ? 2 : 4;  // a count is at most the number of probed buckets
-    uint64_t slab_docs = FILTER_SLAB_BYTES / W;
+    // A slab is one sub-bucket range of documents when its counters fit (32768 documents: 32 KB of LDS with
+    // one-byte counters; four workgroups of 512 threads per CU overlap their phases), else as many documents as fit.
+    uint64_t slab_docs = 1ull << sp.sub_shift;
+    if (slab_docs * W > FILTER_SLAB_BYTES) slab_docs = FILTER_SLAB_BYTES / W;
     if (slab_docs > n_docs) slab_docs = (n_docs + 3) & ~3ull;
     const uint64_t slabs = (n_docs + slab_docs - 1) / slab_docs;
     if (slabs > 0x7fffffffull) return hipErrorInvalidValue;
     const size_t lds = (size_t)slab_docs * W;
     const uint32_t id_bits = bits_for(n_docs - 1);
-    const dim3 grid((unsigned)slabs, n_queries), block(FILTER_COUNT_THREADS);
-    static hipError_t attr[3] = {
-        hipFuncSetAttribute((const void*)filter_count_kernel<1, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES),
-        hipFuncSetAttribute((const void*)filter_count_kernel<2, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES),
-        hipFuncSetAttribute((const void*)filter_count_kernel<4, FILTER_COUNT_THREADS>, hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES)};
-    for (hipError_t e : attr)
-        if (e != hipSuccess) return e;
-    if (W == 1)
-        hipLaunchKernelGGL((filter_count_kernel<1, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
-    else if (W == 2)
-        hipLaunchKernelGGL((filter_count_kernel<2, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
-    else
-        hipLaunchKernelGGL((filter_count_kernel<4, FILTER_COUNT_THREADS>), grid, block, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                           sp.S, sp.sub_shift, bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, cursor);
-    return hipGetLastError();
+    const dim3 grid((unsigned)slabs, n_queries);
+#define DESSERT_COUNT_CASE(W_, T_)                                                                                          \
+    do {                                                                                                                    \
+        if (slab_docs <= 65536)                                                                                             \
+            return launch_filter_count_t<W_, T_, uint16_t>(grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp, \
+                                                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists,        \
+                                                           list_stride, cursor);                                            \
+        return launch_filter_count_t<W_, T_, uint32_t>(grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp,   \
+                                                       bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, \
+                                                       cursor);                                                             \
+    } while (0)
+    if (W == 1) DESSERT_COUNT_CASE(1, 512);
+    if (W == 2) DESSERT_COUNT_CASE(2, 512);
+    DESSERT_COUNT_CASE(4, 512);
+#undef DESSERT_COUNT_CASE
 }
 
 }  // namespace dessert
