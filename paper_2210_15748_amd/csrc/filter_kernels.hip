@@ -359,14 +359,14 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
 // scanned instead.
 constexpr uint32_t FILTER_QUEUE = 4096;  // first-hit queue entries per workgroup (positions within the slab: QT = u16, or u32 for slabs over 65536 documents)
 
-template <int W, int T, typename QT>
+template <int W, int T, typename QT, typename KT>
 __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
                                                             const uint32_t* __restrict__ q_off, uint32_t q_uniform,
                                                             const uint32_t* __restrict__ sub_off, uint32_t S,
                                                             uint32_t sub_shift,
                                                             const uint32_t* __restrict__ bucket_docs, uint64_t n_docs,
                                                             uint32_t slab_docs, uint32_t id_bits,
-                                                            uint64_t* __restrict__ lists, uint64_t list_stride,
+                                                            KT* __restrict__ lists, uint64_t list_stride,
                                                             uint32_t* __restrict__ cursor) {
     extern __shared__ uint32_t cnt[];
     __shared__ QT queue[FILTER_QUEUE];
@@ -462,11 +462,11 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
     if (hits <= FILTER_QUEUE) {
         if (tid == 0) base_sh = hits ? atomicAdd(&cursor[b], hits) : 0;
         __syncthreads();
-        uint64_t* dst = lists + (uint64_t)b * list_stride + base_sh;
+        KT* dst = lists + (uint64_t)b * list_stride + base_sh;
         for (uint32_t i = tid; i < hits; i += T) {
             const uint32_t local = queue[i];
             const uint32_t c = (cnt[local / PER] >> ((local % PER) * BITS)) & MASK;
-            dst[i] = make_key((int32_t)c, doc0 + local, id_bits);
+            dst[i] = (KT)make_key((int32_t)c, doc0 + local, id_bits);
         }
         return;
     }
@@ -495,14 +495,14 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
     uint32_t before = 0;
     for (uint32_t w = 0; w < wave; ++w) before += wsum[w];
     __syncthreads();
-    uint64_t* dst = lists + (uint64_t)b * list_stride + base_sh + before + incl - nz;
+    KT* dst = lists + (uint64_t)b * list_stride + base_sh + before + incl - nz;
     for (uint32_t i = tid; i < words; i += T) {
         const uint32_t x = cnt[i];
         if (x) {
 #pragma unroll
             for (uint32_t j = 0; j < PER; ++j) {
                 const uint32_t c = (x >> (j * BITS)) & MASK;
-                if (c) *dst++ = make_key((int32_t)c, doc0 + i * PER + j, id_bits);
+                if (c) *dst++ = (KT)make_key((int32_t)c, doc0 + i * PER + j, id_bits);
             }
         }
     }
@@ -711,16 +711,16 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
 
 constexpr uint32_t FILTER_SLAB_BYTES = 128 * 1024;  // most LDS counters one workgroup may hold (the queue takes up to 16 KB more)
 
-template <int W, int T, typename QT>
+template <int W, int T, typename QT, typename KT>
 static hipError_t launch_filter_count_t(dim3 grid, size_t lds, hipStream_t stream, const uint32_t* probe_ids, uint32_t probe,
                                         const uint32_t* q_off, uint32_t q_uniform, const uint32_t* sub_off, FilterSubPlan sp,
                                         const uint32_t* bucket_docs, uint64_t n_docs, uint32_t slab_docs, uint32_t id_bits,
                                         uint64_t* lists, uint64_t list_stride, uint32_t* cursor) {
-    static hipError_t attr = hipFuncSetAttribute((const void*)filter_count_kernel<W, T, QT>,
+    static hipError_t attr = hipFuncSetAttribute((const void*)filter_count_kernel<W, T, QT, KT>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((filter_count_kernel<W, T, QT>), grid, dim3(T), lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, lists, list_stride, cursor);
+    hipLaunchKernelGGL((filter_count_kernel<W, T, QT, KT>), grid, dim3(T), lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
+                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, (KT*)lists, list_stride, cursor);
     return hipGetLastError();
 }
 
@@ -744,19 +744,21 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
     const size_t lds = (size_t)slab_docs * W;
     const uint32_t id_bits = bits_for(n_docs - 1);
     const dim3 grid((unsigned)slabs, n_queries);
-#define DESSERT_COUNT_CASE(W_, T_)                                                                                          \
-    do {                                                                                                                    \
-        if (slab_docs <= 65536)                                                                                             \
-            return launch_filter_count_t<W_, T_, uint16_t>(grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp, \
-                                                           bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists,        \
-                                                           list_stride, cursor);                                            \
-        return launch_filter_count_t<W_, T_, uint32_t>(grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp,   \
-                                                       bucket_docs, n_docs, (uint32_t)slab_docs, id_bits, lists, list_stride, \
-                                                       cursor);                                                             \
+#define DESSERT_COUNT_ARGS grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp, bucket_docs, n_docs, \
+                           (uint32_t)slab_docs, id_bits, lists, list_stride, cursor
+#define DESSERT_COUNT_CASE(W_, T_)                                                                              \
+    do {                                                                                                        \
+        if (slab_docs <= 65536)                                                                                 \
+            return k32 ? launch_filter_count_t<W_, T_, uint16_t, uint32_t>(DESSERT_COUNT_ARGS)                    \
+                       : launch_filter_count_t<W_, T_, uint16_t, uint64_t>(DESSERT_COUNT_ARGS);                   \
+        return k32 ? launch_filter_count_t<W_, T_, uint32_t, uint32_t>(DESSERT_COUNT_ARGS)                        \
+                   : launch_filter_count_t<W_, T_, uint32_t, uint64_t>(DESSERT_COUNT_ARGS);                       \
     } while (0)
+    const bool k32 = keys_fit_32(max_pairs, n_docs - 1);  // the lists hold u32 keys then (launch_topk_lists reads them so)
     if (W == 1) DESSERT_COUNT_CASE(1, 512);
     if (W == 2) DESSERT_COUNT_CASE(2, 512);
     DESSERT_COUNT_CASE(4, 512);
+#undef DESSERT_COUNT_ARGS
 #undef DESSERT_COUNT_CASE
 }
 

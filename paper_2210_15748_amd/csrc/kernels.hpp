@@ -128,7 +128,8 @@ struct TopkArgs {
 uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 // k best of stored key lists: lists[b][0..counts[b]) (counts on the device), keys as built by make_key with
-// id_bits = bits of max_id; one workgroup per list.
+// id_bits = bits of max_id; one workgroup per list.  When the score and id fields fit 32 bits together the lists hold
+// u32 keys (list b starts list_stride u32 entries after list b-1); launch_filter_count writes them the same way.
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
                              uint32_t k, uint32_t max_score, uint64_t max_id, uint32_t* out_ids, int32_t* out_scores,
                              hipStream_t stream);

@@ -62,15 +62,21 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_merge_kernel(TopkArgs a, Ke
 // one workgroup per stored list whose length is read from device memory.  There are only as many workgroups
 // as lists, so each is wide and keeps many loads in flight: a pass over a list is a few round trips.
 constexpr uint32_t TOPK_LIST_THREADS = 1024;
-__global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const uint64_t* __restrict__ lists, uint64_t list_stride,
+template <typename KT>  // stored key type: uint64_t, or uint32_t when keys_fit_32
+__global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT* __restrict__ lists, uint64_t list_stride,
                                                                        const uint32_t* __restrict__ counts, uint32_t k,
                                                                        KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
                                                                        int32_t* __restrict__ out_scores) {
     extern __shared__ uint64_t sorted[];
     __shared__ SelectShared sh;
     const uint32_t b = blockIdx.x;
-    StoredKeys keys{lists + (size_t)b * list_stride};
-    block_select<TOPK_LIST_THREADS, StoredKeys, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+    if constexpr (sizeof(KT) == 8) {
+        StoredKeys keys{lists + (size_t)b * list_stride};
+        block_select<TOPK_LIST_THREADS, StoredKeys, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+    } else {
+        StoredKeys32 keys{lists + (size_t)b * list_stride};
+        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+    }
     for (uint32_t i = threadIdx.x; i < k; i += TOPK_LIST_THREADS)
         write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
 }
@@ -80,9 +86,11 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel,
+    static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint64_t>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    return a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3;
+    static hipError_t a4 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint32_t>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    return a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4;
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
@@ -98,8 +106,12 @@ hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const 
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(topk_lists_kernel, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists, list_stride, counts, k,
-                       plan, kpad, out_ids, out_scores);
+    if (keys_fit_32(max_score, max_id))
+        hipLaunchKernelGGL(topk_lists_kernel<uint32_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream,
+                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores);
+    else
+        hipLaunchKernelGGL(topk_lists_kernel<uint64_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists,
+                           list_stride, counts, k, plan, kpad, out_ids, out_scores);
     return hipGetLastError();
 }
 

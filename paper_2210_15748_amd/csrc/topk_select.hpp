@@ -33,21 +33,35 @@ inline uint32_t bits_for(uint64_t max_value) {
     return b;
 }
 
-// max_score: largest possible score; max_id: largest document id that can occur
+// max_score: largest possible score; max_id: largest document id that can occur.
+// The leading digit is exactly the score field when that is at most one digit wide (its histogram then has
+// few occupied bins and block_select merges the adds per wave); the id bits are spread evenly over the rest.
 inline KeyPlan make_key_plan(uint32_t max_score, uint64_t max_id) {
     KeyPlan p{};
     p.id_bits = (uint8_t)bits_for(max_id);
-    uint32_t total = p.id_bits + bits_for((uint64_t)max_score + 1);
-    uint32_t n = (total + TOPK_DIGIT_BITS - 1) / TOPK_DIGIT_BITS;
-    p.n_digits = (uint8_t)n;
-    uint32_t hi = total;
-    for (uint32_t i = 0; i < n; ++i) {
+    const uint32_t score_bits = bits_for((uint64_t)max_score + 1);
+    uint32_t hi = p.id_bits + score_bits;
+    uint32_t i = 0;
+    if (score_bits <= TOPK_DIGIT_BITS) {
+        p.width[0] = (uint8_t)score_bits;
+        p.shift[0] = p.id_bits;
+        hi = p.id_bits;
+        i = 1;
+    }
+    const uint32_t n = i + (hi + TOPK_DIGIT_BITS - 1) / TOPK_DIGIT_BITS;
+    for (; i < n; ++i) {
         uint32_t w = (hi + (n - i) - 1) / (n - i);  // spread the bits evenly over the remaining digits
         p.width[i] = (uint8_t)w;
         p.shift[i] = (uint8_t)(hi - w);
         hi -= w;
     }
+    p.n_digits = (uint8_t)n;
     return p;
+}
+
+// stored key lists use 32-bit keys when the score and id fields fit
+inline bool keys_fit_32(uint32_t max_score, uint64_t max_id) {
+    return bits_for(max_id) + bits_for((uint64_t)max_score + 1) <= 32;
 }
 
 __device__ inline uint64_t make_key(int32_t score, uint32_t id, uint32_t id_bits) {
@@ -104,6 +118,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             __syncthreads();
             const uint64_t prefix = sh.prefix;
             const uint32_t need = sh.need;
+            uint32_t run_bin = 0xFFFFFFFFu, run_len = 0;
             for (uint64_t i = tid; i < n; i += U * T) {  // U loads in flight per thread
                 uint64_t key[U];
 #pragma unroll
@@ -113,22 +128,23 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     const bool in = i + u * T < n && (key[u] >> (shift + width)) == prefix;
                     const uint32_t bin = (uint32_t)(key[u] >> shift) & dmask;
                     if (d == 0) {
-                        // the leading digit holds the score's top bits and few values occur: lanes with the same
-                        // bin add once (a few rounds of "first lane's bin, who else has it"), the rest singly
-                        uint64_t todo = __ballot(in);
-                        for (int r = 0; r < 4 && todo; ++r) {
-                            const uint32_t first = (uint32_t)__builtin_ctzll(todo);
-                            const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)bin, (int)first);
-                            const uint64_t same = __ballot(in && bin == v) & todo;
-                            if (lane == first) atomicAdd(&sh.hist[v], (uint32_t)__builtin_popcountll(same));
-                            todo &= ~same;
+                        // the leading digit holds the score's top bits and few values occur, mostly in runs: a thread
+                        // counts a run of equal bins in a register and adds it once
+                        if (in) {
+                            if (bin == run_bin) {
+                                ++run_len;
+                            } else {
+                                if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
+                                run_bin = bin;
+                                run_len = 1;
+                            }
                         }
-                        if (in && ((todo >> lane) & 1)) atomicAdd(&sh.hist[bin], 1u);
                     } else if (in) {
                         atomicAdd(&sh.hist[bin], 1u);
                     }
                 }
             }
+            if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
             __syncthreads();
             // digit D with  count(digits > D) < need <= count(digits >= D):
             // thread t owns bins [t*per, (t+1)*per); suffix sums over threads, then a short scan
@@ -179,7 +195,38 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         }
     }
     __syncthreads();
-    // bitonic sort, descending
+    // bitonic sort, descending.  Wave w owns the pairs of the run [w*seg, (w+1)*seg) of the array (seg = kpad / WAVES);
+    // a step whose pairs stay inside such a run (2*stride <= seg) touches only elements that the same wave wrote,
+    // and a wave's LDS operations execute in order, so those steps need no workgroup barrier: of the 78 steps of
+    // a 4096-key sort by 1024 threads, 68.
+    if (kpad >= 128u * WAVES) {
+        const uint32_t seg = kpad / WAVES;
+        for (uint32_t size = 2; size <= kpad; size <<= 1) {
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t m = lane; m < seg / 2; m += 64) {
+                    const uint32_t i = wave * (seg / 2) + m;
+                    uint32_t lo = 2 * i - (i & (stride - 1));
+                    uint32_t hi = lo + stride;
+                    bool desc = ((lo & size) == 0);
+                    uint64_t x = sorted[lo], y = sorted[hi];
+                    if ((x < y) == desc) {
+                        sorted[lo] = y;
+                        sorted[hi] = x;
+                    }
+                }
+                // no workgroup barrier between two steps that both stay inside the waves' own runs
+                const uint32_t next = stride > 1 ? stride >> 1 : size;  // stride of the following step
+                if (2 * stride > seg || 2 * next > seg) {
+                    __syncthreads();
+                } else {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        __syncthreads();
+        return;
+    }
     for (uint32_t size = 2; size <= kpad; size <<= 1) {
         for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
             for (uint32_t i = tid; i < kpad / 2; i += T) {
@@ -210,6 +257,11 @@ struct ScoreKeys {  // keys computed from a score array (+ optional candidate id
 
 struct StoredKeys {
     const uint64_t* keys;
+    __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
+};
+
+struct StoredKeys32 {  // keys of at most 32 bits (score and id fields together), stored as u32
+    const uint32_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
 };
 
