@@ -195,53 +195,65 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         }
     }
     __syncthreads();
-    // bitonic sort, descending.  Wave w owns the pairs of the run [w*seg, (w+1)*seg) of the array (seg = kpad / WAVES);
-    // a step whose pairs stay inside such a run (2*stride <= seg) touches only elements that the same wave wrote,
-    // and a wave's LDS operations execute in order, so those steps need no workgroup barrier: of the 78 steps of
-    // a 4096-key sort by 1024 threads, 68.
-    if (kpad >= 128u * WAVES) {
-        const uint32_t seg = kpad / WAVES;
-        for (uint32_t size = 2; size <= kpad; size <<= 1) {
-            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                for (uint32_t m = lane; m < seg / 2; m += 64) {
-                    const uint32_t i = wave * (seg / 2) + m;
-                    uint32_t lo = 2 * i - (i & (stride - 1));
-                    uint32_t hi = lo + stride;
-                    bool desc = ((lo & size) == 0);
-                    uint64_t x = sorted[lo], y = sorted[hi];
-                    if ((x < y) == desc) {
-                        sorted[lo] = y;
-                        sorted[hi] = x;
-                    }
-                }
-                // no workgroup barrier between two steps that both stay inside the waves' own runs
-                const uint32_t next = stride > 1 ? stride >> 1 : size;  // stride of the following step
-                if (2 * stride > seg || 2 * next > seg) {
-                    __syncthreads();
-                } else {
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                }
-            }
+    // bitonic sort, descending.  Two steps (strides s and s/2) per trip through LDS: a thread takes the four keys
+    // base, base+s/2, base+s, base+3s/2, which both steps pair among themselves, so the array is read and written
+    // once per two steps.  Wave w owns the groups of the run [w*seg, (w+1)*seg) of the array (seg = kpad / WAVES);
+    // a trip whose groups stay inside such a run touches only keys the same wave wrote, and a wave's LDS operations
+    // execute in order, so two such trips in a row need no workgroup barrier between them.
+    auto order = [](uint64_t& x, uint64_t& y, bool desc) {
+        if ((x < y) == desc) {
+            const uint64_t t = x;
+            x = y;
+            y = t;
         }
-        __syncthreads();
-        return;
-    }
+    };
+    const bool by_wave = kpad >= 256u * WAVES;   // every lane has at least one group of four in its wave's run
+    const uint32_t seg = by_wave ? kpad / WAVES : kpad;
+    bool prev_local = false;
     for (uint32_t size = 2; size <= kpad; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (uint32_t i = tid; i < kpad / 2; i += T) {
-                uint32_t lo = 2 * i - (i & (stride - 1));
-                uint32_t hi = lo + stride;
-                bool desc = ((lo & size) == 0);
-                uint64_t x = sorted[lo], y = sorted[hi];
-                if ((x < y) == desc) {
-                    sorted[lo] = y;
-                    sorted[hi] = x;
-                }
+        for (uint32_t stride = size >> 1; stride > 0;) {
+            const bool local = by_wave && 2 * stride <= seg;
+            if (!(local && prev_local)) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
             }
-            __syncthreads();
+            prev_local = local;
+            if (stride >= 2) {  // strides `stride` and `stride / 2` together
+                const uint32_t h = stride >> 1;
+                const uint32_t groups = kpad / 4;
+                const uint32_t g_lo = by_wave ? wave * (seg / 4) : 0, g_n = by_wave ? seg / 4 : groups;
+                for (uint32_t m = by_wave ? lane : tid; m < g_n; m += by_wave ? 64 : T) {
+                    const uint32_t g = g_lo + m;
+                    const uint32_t base = (g / h) * (2 * stride) + (g % h);
+                    const bool desc = ((base & size) == 0);
+                    uint64_t k0 = sorted[base], k1 = sorted[base + h], k2 = sorted[base + stride], k3 = sorted[base + stride + h];
+                    order(k0, k2, desc);
+                    order(k1, k3, desc);
+                    order(k0, k1, desc);
+                    order(k2, k3, desc);
+                    sorted[base] = k0;
+                    sorted[base + h] = k1;
+                    sorted[base + stride] = k2;
+                    sorted[base + stride + h] = k3;
+                }
+                stride >>= 2;
+            } else {  // stride 1 alone
+                const uint32_t p_lo = by_wave ? wave * (seg / 2) : 0, p_n = by_wave ? seg / 2 : kpad / 2;
+                for (uint32_t m = by_wave ? lane : tid; m < p_n; m += by_wave ? 64 : T) {
+                    const uint32_t lo = 2 * (p_lo + m);
+                    const bool desc = ((lo & size) == 0);
+                    uint64_t x = sorted[lo], y = sorted[lo + 1];
+                    order(x, y, desc);
+                    sorted[lo] = x;
+                    sorted[lo + 1] = y;
+                }
+                stride = 0;
+            }
         }
     }
+    __syncthreads();
 }
 
 struct ScoreKeys {  // keys computed from a score array (+ optional candidate ids)
