@@ -111,6 +111,9 @@ def main() -> int:
     ap.add_argument("--score-algo", type=int, default=0)
     ap.add_argument("--hash-algo", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--transform", type=int, default=0,
+                    help="score transform (0 raw counts: the metric; 1 = the paper's Eq. 1 remap before the sum; "
+                         "2-4 max of the other phi of Sec. 4.1); implies --no-cpu-baseline")
     ap.add_argument("--cpu-sample-queries", type=int, default=32)
     ap.add_argument("--graph", action="store_true",
                     help="capture the search step in a HIP graph and time replays (per-kernel times are then taken from "
@@ -151,6 +154,10 @@ def main() -> int:
                    proj_kind=dz.PROJ_RADEMACHER_I8 if p.proj_kind == "rademacher" else dz.PROJ_GAUSSIAN_F32,
                    proj=w.proj)
     dz.set_algo(ix, args.hash_algo, args.score_algo)
+    if args.transform:
+        dz.set_score_transform(ix, args.transform)
+        args.no_cpu_baseline = True
+        args.no_filter = True
     dz.enable_timing(ix, True)
 
     # ---- index build (H1-H3), timed on its own
@@ -377,6 +384,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": p.name, "n_docs": w.n_docs, "n_vectors": w.n_vectors, "d": p.d, "L": p.L, "C": p.C,
                    "query_sets": B, "q_len": p.q_len, "candidates_per_query": p.n_cand, "k": k,
+                   "score_transform": args.transform,
                    "step": "dessert_search: query hashing + scoring + top-k (index built once, before the timed region)"
                            + (", replayed from a captured HIP graph" if args.graph else "")},
         "kernel_ms": {"query_hash": round(qhash_ms, 5), "score": round(score_ms, 5), "topk": round(topk_ms, 5)},
