@@ -96,6 +96,9 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
                                                           int64_t* __restrict__ lists) {
     constexpr int D = KS * 32;
     constexpr int P = MODE > 0 ? MODE : 1;
+    // a list of one entry is an argmax: MODE = 1 keeps the 32-bit running key of MODE = 0 (no 64-bit list
+    // inserts in the loop) and forms its list entry at the end
+    constexpr bool ARGMAX = MODE == 0 || MODE == 1;
     __shared__ v4i sA[FILTER_TG * KS * 64];
     __shared__ v4i sT[FILTER_TG * 8];  // 32 ints per tile
     __shared__ uint32_t sP[FILTER_TG * 2];
@@ -172,9 +175,9 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
                     m = acc[nt][15] > m ? acc[nt][15] : m;
                     // a lane meets centroid ids in increasing tile order, so only a strictly larger value can
                     // replace what it holds, and no value of this tile exceeds 2 m + 1
-                    const int32_t bound = MODE == 0 ? best_key[nt] >> 4 : (int32_t)(best[nt][P - 1] >> 32);
+                    const int32_t bound = ARGMAX ? best_key[nt] >> 4 : (int32_t)(best[nt][P - 1] >> 32);
                     if (2 * m + 1 > bound) {
-                        if constexpr (MODE == 0) {
+                        if constexpr (ARGMAX) {
                             int32_t km = (int32_t)0x80000000;
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
@@ -214,6 +217,13 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
     } else if constexpr (MODE > 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
+            if constexpr (MODE == 1) {
+                const uint32_t cid = best_tile[nt] * 32 + tile_row(15 - (best_key[nt] & 15), g);
+                const int32_t val = best_key[nt] >> 4;
+                best[nt][0] = (best_key[nt] != (int32_t)0x80000000 && cid < K)
+                                  ? (int64_t)(((uint64_t)(uint32_t)val << 32) | (uint32_t)~cid)
+                                  : LIST_EMPTY;
+            }
             const uint64_t v = v0 + nt * 32 + col;
             if (v < n) {
                 int64_t* dst = lists + ((v * gridDim.y + blockIdx.y) * 2 + g) * P;
@@ -618,7 +628,9 @@ FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe) {
     if (probe == 0 || probe > FILTER_LIST_MAX || n == 0) return pl;  // ranges = 0: use the distance matrix
     const uint32_t tiles = filter_tiles(K);
     const uint32_t groups = (tiles + FILTER_TG - 1) / FILTER_TG;
-    const uint64_t blocks = (n + 127) / 128;
+    // more vectors per workgroup halve the centroid bytes staged through LDS per vector
+    pl.nt = n >= 4096 ? 2 : 1;
+    const uint64_t blocks = (n + 128 * pl.nt - 1) / (128 * pl.nt);
     uint64_t want = (2048 + blocks - 1) / blocks;  // aim at ~2048 workgroups
     if (want > groups) want = groups;
     if (want > 64) want = 64;
@@ -641,22 +653,26 @@ hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, ui
     const dim3 mgrid((unsigned)((n + 255) / 256)), mblock(256);
     switch (pl.width) {
         case 1:
-            e = launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
+                           : launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<1>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
         case 2:
-            e = launch_gemm<1, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
+                           : launch_gemm<1, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<2>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
         case 4:
-            e = launch_gemm<1, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
+                           : launch_gemm<1, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<4>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
         default:
-            e = launch_gemm<1, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
+                           : launch_gemm<1, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<8>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;

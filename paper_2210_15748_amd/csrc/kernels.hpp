@@ -84,6 +84,7 @@ hipError_t launch_kmeans_update(const int8_t* X, uint64_t n, uint32_t d, const u
 constexpr uint32_t FILTER_LIST_MAX = 8;
 struct FilterProbePlan {
     uint32_t ranges, tiles_per_range, width;
+    uint32_t nt;        // 32-vector column tiles per wave (2 when there are enough query vectors to fill the chip so)
     size_t list_bytes;  // int64 lists[n][ranges][2][width]
 };
 FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe);
