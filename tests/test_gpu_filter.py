@@ -64,8 +64,9 @@ def test_filter_build_assignments_and_buckets(d, K, n_docs, dup, max_len):
     (8, 4096, [12, 7], 1500, 12), (37, 50, [3, 3], 1500, 12),
     (37, 200, [10, 2], 1500, 12),            # counts up to 370: 16-bit counters
     (37, 16384, [1800, 5], 1500, 12),        # counts up to 66600: 32-bit counters
-    (2, 1000, [32, 9], 300_000, 3),          # three document slabs of 8-bit counters
-    (3, 777, [100, 30], 150_000, 3)])        # three document slabs of 16-bit counters
+    (2, 1000, [32, 9], 300_000, 3),          # ten document slabs of 8-bit counters, first-hit queues overflow
+    (3, 777, [100, 30], 150_000, 3),         # document slabs of 16-bit counters
+    (37, 2000, [1800, 5], 150_000, 3)])      # 32-bit counters over several slabs; count and id fields pass 32 bits: 64-bit list keys
 def test_filter_query_matches_oracle(probe, filter_k, q_lens, n_docs, max_len):
     say(f"filter query probe={probe} filter_k={filter_k} q_lens={q_lens} N={n_docs}")
     rng = np.random.default_rng(100 + probe)
