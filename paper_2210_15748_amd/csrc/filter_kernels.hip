@@ -234,6 +234,26 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
     }
 }
 
+// one probe per vector: one wave per vector, lanes stride over its per_vec entries, wave maximum
+__global__ __launch_bounds__(256) void filter_merge1_kernel(const int64_t* __restrict__ lists, uint64_t n,
+                                                            uint32_t per_vec, uint32_t* __restrict__ probe_ids) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t v = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int64_t* src = lists + v * per_vec;
+    int64_t best = LIST_EMPTY;
+    for (uint32_t i = lane; i < per_vec; i += 64) {
+        const int64_t e = src[i];
+        best = e > best ? e : best;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const int64_t other = __shfl_xor((long long)best, o, 64);
+        best = other > best ? other : best;
+    }
+    if (lane == 0) probe_ids[v] = best == LIST_EMPTY ? 0xFFFFFFFFu : ~(uint32_t)best;
+}
+
 // one thread per vector: the `probe` best entries of its per_vec list entries, closest first
 template <int P>
 __global__ __launch_bounds__(256) void filter_merge_kernel(const int64_t* __restrict__ lists, uint64_t n,
@@ -656,7 +676,7 @@ hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, ui
             e = pl.nt == 2 ? launch_gemm<2, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
                            : launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(filter_merge_kernel<1>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
+            hipLaunchKernelGGL(filter_merge1_kernel, dim3((unsigned)((n + 3) / 4)), mblock, 0, stream, lists, n, per_vec, probe_ids);
             break;
         case 2:
             e = pl.nt == 2 ? launch_gemm<2, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
