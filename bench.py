@@ -15,7 +15,9 @@ Prints ONE JSON line.  "value" = doc-set scores per second of the whole step wit
 "roofline" = the scoring kernel's algorithmic code bytes per launch over its measured duration, against the
 published HBM peak (plus the HBM traffic read from the rocprofv3 counter summary under profiles/ and what a plain
 streaming read achieves in the same run); "index_build" and "candidate_filter" = the build and the pre-filter timed
-on their own; "cpu_baseline" = the CPU oracle on a bounded sample of the same workload.
+on their own; "cpu_baseline" = the CPU oracle on a bounded sample of the same workload; "exhaustive_mid_scale" = the
+same metric on the exhaustive mid-scale preset (100 000 documents, 64 query sets, every document scored), measured by
+a child process after the timed regions of this one.
 
 Other presets (--config 2, 4, 5: every document scored for every query set) are parity-test workloads, not the
 metric; there the codes are shared by the query sets of a batch, the scoring kernel is bound by the vector ALU and
@@ -122,6 +124,8 @@ def main() -> int:
     ap.add_argument("--filter-centroids", type=int, default=65536)
     ap.add_argument("--kmeans-iters", type=int, default=4, help="Lloyd iterations for the filter's centroids (0: sampled vectors)")
     ap.add_argument("--kmeans-sample", type=int, default=1 << 20)
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the exhaustive mid-scale preset that the default run also measures (in a child process)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -396,6 +400,24 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    # The default run also measures the exhaustive mid-scale preset (every document scored for every query set): a
+    # second view of the same metric, ALU-bound instead of HBM-bound.  It runs as a child process after this one's
+    # timed regions; not part of "value".
+    if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None and not args.graph
+            and not args.transform and not args.no_cpu_baseline and not args.no_secondary):
+        import subprocess
+        torch.cuda.synchronize()
+        try:
+            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--config", "2", "--no-cpu-baseline",
+                                    "--steps", "20", "--warmup", "3", "--build-reps", "3"],
+                                   capture_output=True, text=True, timeout=240)
+            sub = json.loads(child.stdout.strip().splitlines()[-1])
+            line["exhaustive_mid_scale"] = {
+                "workload": sub["config"]["workload"], "value": sub["value"], "unit": sub["unit"],
+                "ms_per_step": sub["ms_per_step"], "kernel_ms": sub["kernel_ms"], "config": sub["config"],
+                "roofline": sub["roofline"], "index_build": sub["index_build"]}
+        except Exception as e:  # the metric line must come out whatever happens to the extra measurement
+            line["exhaustive_mid_scale"] = {"error": repr(e)}
     print(json.dumps(line), flush=True)
     return 0
 
