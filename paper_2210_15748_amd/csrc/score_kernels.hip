@@ -242,8 +242,11 @@ struct LutBlockMeta {
     uint32_t next;              // next unclaimed position in `order`
 };
 
-// G = lanes per document (8): a wave works on 64/G documents at a time, each lane looping over
-// every G-th vector of its document.  Documents of a block are ordered by length class
+// G = lanes per document: a wave works on 64/G documents at a time, each lane looping over
+// every G-th vector of its document.  G = 8, except the paired form with L <= 32 (G = 4): there the work is
+// vector-ALU arithmetic, and merging a document's lanes costs about as much as one round of the loop, so with
+// documents of some 70 vectors fewer lanes per document (two merge steps, less rounding up to whole rounds)
+// measured 4-6 % faster; with 64-byte rows (L = 64) it made no difference.  Documents of a block are ordered by length class
 // ceil(m/G) (counting sort in LDS) and waves claim runs of 64/G consecutive documents from that
 // order, so the documents sharing a wave need the same number of rounds and few lanes idle.
 //
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     constexpr int LW = L * CW / 4;  // dwords per code row
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
-    constexpr int G = 8;
+    constexpr int G = (W == 2 && L <= 32) ? 4 : 8;
     constexpr int DOCS_PER_WAVE = 64 / G;
     // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
