@@ -534,8 +534,9 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
             };
             // a round's G rows start on a 128-byte line of the code array (rows before the document's
             // first clamp to it), so the rows of one round are whole lines and no line is requested
-            // by two rounds
-            constexpr uint32_t ROWS_PER_LINE = 128 / (L * CW) < 1 ? 1 : (128 / (L * CW) > G ? G : 128 / (L * CW));
+            // by two rounds.  Not in the paired form: it streams the code array in order and is bound by
+            // arithmetic, so it starts at the document's first row and computes no clamped rows in front
+            constexpr uint32_t ROWS_PER_LINE = W == 2 ? 1 : 128 / (L * CW) < 1 ? 1 : (128 / (L * CW) > G ? G : 128 / (L * CW));
             int32_t j = (int32_t)sub - (int32_t)((uint32_t)lo & (ROWS_PER_LINE - 1));  // this lane's row in the round at hand
             const int32_t j_end = (int32_t)m + (int32_t)sub;  // rounds run while j - sub < m
             auto clamped = [&](int32_t jj) { return jj < (int32_t)last_j ? jj : (int32_t)last_j; };
