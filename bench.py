@@ -317,7 +317,9 @@ def main() -> int:
         roofline = {"bound": "alu", "kernel": "score_masklut_kernel", "achieved": round(achieved, 3), "peak": VALU_PEAK_TLOPS,
                     "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_TLOPS, 4), "traffic": None,
                     "lane_ops_per_vector_and_32_queries": ops_unit, "algorithmic_lane_ops_per_launch": lane_ops,
-                    "kernel_ms": round(score_ms, 5), "code_bytes_streamed_once": w.n_vectors * p.L * codes.element_size()}
+                    "kernel_ms": round(score_ms, 5), "code_bytes_streamed_once": w.n_vectors * p.L * codes.element_size(),
+                    # the same work in the method's own unit: table-code comparisons (document vector x query vector x table)
+                    "equality_tests_per_s": round(w.n_vectors * B * p.q_len * p.L / (score_ms * 1e-3), 1)}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     cpu = None
