@@ -708,7 +708,7 @@ FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total
     w.dist = p;      p += align_up(pl.ranges ? pl.list_bytes : (size_t)total_q * filter_tiles(ix->f_K) * 32 * 4, 256);
     w.probe_ids = p; p += align_up((size_t)total_q * probe * 4, 256);
     w.q_off = p;     p += align_up(((size_t)B + 1) * 4, 256);
-    w.cursor = p;    p += align_up((size_t)B * 4, 256);
+    w.cursor = p;    p += align_up(filter_cursor_words(B, max_q * probe, ix->n_docs) * 4, 256);  // list lengths + count histograms
     // a query set hits at most (its vectors * probe) buckets of at most f_max_bucket documents each
     uint64_t hit = (uint64_t)max_q * probe * ix->f_max_bucket;
     if (hit > ix->n_docs) hit = ix->n_docs;
@@ -778,8 +778,10 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, max_q * filter_probe, d_q_off, q_uniform, n_queries,
                                 ix->f_sub_off, ix->f_sub, ix->f_bucket_docs, ix->n_docs, lists, w.list_stride, cursor,
                                 ix->stream));
+    const uint32_t* hist0 = (ix->n_docs && total_q && filter_hist_bins(max_q * filter_probe, ix->n_docs))
+                                ? cursor + filter_hist_offset(n_queries) : nullptr;
     HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
-                              ix->n_docs ? ix->n_docs - 1 : 0, out_ids_dev, out_counts_dev, ix->stream));
+                              ix->n_docs ? ix->n_docs - 1 : 0, hist0, out_ids_dev, out_counts_dev, ix->stream));
     return DESSERT_OK;
 }
 

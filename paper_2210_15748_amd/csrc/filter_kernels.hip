@@ -355,7 +355,10 @@ __global__ void filter_bucket_starts_kernel(const uint32_t* __restrict__ sub_off
 struct DistKeys {  // key = (value + bias) above the centroid id: closest first, lower id first
     const int32_t* row;
     uint32_t id_bits;
+    static constexpr int VEC = 1;
+    using key_t = uint64_t;
     __device__ uint64_t operator()(uint64_t i) const { return make_key(row[i] + FILTER_BIAS, (uint32_t)i, id_bits); }
+    __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[1]) const { out[0] = i < n ? (*this)(i) : 0; }
 };
 
 // one workgroup per query vector: its `probe` closest centroids, closest first
@@ -397,7 +400,8 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
                                                             const uint32_t* __restrict__ bucket_docs, uint64_t n_docs,
                                                             uint32_t slab_docs, uint32_t id_bits,
                                                             KT* __restrict__ lists, uint64_t list_stride,
-                                                            uint32_t* __restrict__ cursor) {
+                                                            uint32_t* __restrict__ cursor, uint32_t* __restrict__ hist,
+                                                            uint32_t hist_bins) {
     extern __shared__ uint32_t cnt[];
     __shared__ QT queue[FILTER_QUEUE];
     __shared__ uint32_t wsum[16];
@@ -429,6 +433,29 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
                 n_l = sub_off[(size_t)c * S + s_hi] - lo_l;
             }
         }
+    };
+    // histogram of the emitted keys' score fields (bin = count + 1) for the selection that follows.  Nearly every
+    // document is hit once: a thread counts those in a register; the workgroup gathers its counts in a small LDS
+    // histogram and adds the occupied bins to the query set's histogram (a handful of global atomics per workgroup;
+    // one per key made this kernel four times slower: they all go to the same few addresses).
+    constexpr uint32_t HSMALL = 64;
+    __shared__ uint32_t hsmall[HSMALL];
+    uint32_t* my_hist = hist_bins ? hist + (size_t)b * hist_bins : nullptr;
+    uint32_t ones = 0;
+    if (tid < HSMALL) hsmall[tid] = 0;  // ordered before the first tally by the barriers of the counting phase
+    auto tally = [&](uint32_t c) {
+        if (!my_hist) return;
+        if (c == 1) ++ones;
+        else if (c + 1 < HSMALL) atomicAdd(&hsmall[c + 1], 1u);
+        else atomicAdd(&my_hist[c + 1], 1u);
+    };
+    auto flush_tally = [&]() {  // called by every thread of the workgroup
+        if (!my_hist) return;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ones += __shfl_down(ones, o, 64);
+        if (lane == 0 && ones) atomicAdd(&hsmall[2], ones);
+        __syncthreads();
+        if (tid < HSMALL && tid < hist_bins && hsmall[tid]) atomicAdd(&my_hist[tid], hsmall[tid]);
     };
     uint32_t lo_l, n_l;
     bounds(wave, lo_l, n_l);
@@ -497,7 +524,9 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
             const uint32_t local = queue[i];
             const uint32_t c = (cnt[local / PER] >> ((local % PER) * BITS)) & MASK;
             dst[i] = (KT)make_key((int32_t)c, doc0 + local, id_bits);
+            tally(c);
         }
+        flush_tally();
         return;
     }
     // queue overflow: scan the counters
@@ -532,10 +561,14 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
 #pragma unroll
             for (uint32_t j = 0; j < PER; ++j) {
                 const uint32_t c = (x >> (j * BITS)) & MASK;
-                if (c) *dst++ = (KT)make_key((int32_t)c, doc0 + i * PER + j, id_bits);
+                if (c) {
+                    *dst++ = (KT)make_key((int32_t)c, doc0 + i * PER + j, id_bits);
+                    tally(c);
+                }
             }
         }
     }
+    flush_tally();
 }
 
 // ---------------------------------------------------------------------------
@@ -751,13 +784,18 @@ template <int W, int T, typename QT, typename KT>
 static hipError_t launch_filter_count_t(dim3 grid, size_t lds, hipStream_t stream, const uint32_t* probe_ids, uint32_t probe,
                                         const uint32_t* q_off, uint32_t q_uniform, const uint32_t* sub_off, FilterSubPlan sp,
                                         const uint32_t* bucket_docs, uint64_t n_docs, uint32_t slab_docs, uint32_t id_bits,
-                                        uint64_t* lists, uint64_t list_stride, uint32_t* cursor) {
+                                        uint64_t* lists, uint64_t list_stride, uint32_t* cursor, uint32_t* hist,
+                                        uint32_t hist_bins) {
     static hipError_t attr = hipFuncSetAttribute((const void*)filter_count_kernel<W, T, QT, KT>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((filter_count_kernel<W, T, QT, KT>), grid, dim3(T), lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, (KT*)lists, list_stride, cursor);
+                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, (KT*)lists, list_stride, cursor, hist, hist_bins);
     return hipGetLastError();
+}
+
+uint32_t filter_hist_bins(uint32_t max_pairs, uint64_t n_docs) {
+    return n_docs ? leading_score_bins(max_pairs, n_docs - 1) : 0;
 }
 
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
@@ -766,8 +804,12 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
                                uint64_t list_stride, uint32_t* cursor, hipStream_t stream) {
     if (n_queries == 0) return hipSuccess;
     if (n_queries > 65535 || n_docs > 0xFFFFFFFEull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(filter_zero_kernel, dim3((n_queries + 255) / 256), dim3(256), 0, stream, (int32_t*)cursor,
-                       (uint64_t)n_queries);
+    const uint32_t hist_bins = filter_hist_bins(max_pairs, n_docs);
+    uint32_t* hist = hist_bins ? cursor + filter_hist_offset(n_queries) : nullptr;
+    const uint64_t zero_words = filter_cursor_words(n_queries, max_pairs, n_docs);
+    uint64_t zb = (zero_words + 1023) / 1024;
+    hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, (int32_t*)cursor,
+                       zero_words);
     if (n_docs == 0 || total_q == 0) return hipGetLastError();
     const uint32_t W = max_pairs <= 255 ? 1 : max_pairs <= 65535 ? 2 : 4;  // a count is at most the number of probed buckets
     // A slab is one sub-bucket range of documents when its counters fit (32768 documents: 32 KB of LDS with
@@ -781,7 +823,7 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
     const uint32_t id_bits = bits_for(n_docs - 1);
     const dim3 grid((unsigned)slabs, n_queries);
 #define DESSERT_COUNT_ARGS grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp, bucket_docs, n_docs, \
-                           (uint32_t)slab_docs, id_bits, lists, list_stride, cursor
+                           (uint32_t)slab_docs, id_bits, lists, list_stride, cursor, hist, hist_bins
 #define DESSERT_COUNT_CASE(W_, T_)                                                                              \
     do {                                                                                                        \
         if (slab_docs <= 65536)                                                                                 \

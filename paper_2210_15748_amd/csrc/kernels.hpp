@@ -106,10 +106,17 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
                                hipStream_t stream);
 // Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
 // max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.
+// cursor: [filter_cursor_words(B, max_pairs, n_docs)] u32: the B list lengths, then (from word filter_hist_offset(B) on,
+// when filter_hist_bins() != 0) per query set the histogram of its keys' score fields, which launch_topk_lists takes as hist0.
+uint32_t filter_hist_bins(uint32_t max_pairs, uint64_t n_docs);
+inline size_t filter_hist_offset(uint32_t n_queries) { return ((size_t)n_queries + 63) / 64 * 64; }
+inline size_t filter_cursor_words(uint32_t n_queries, uint32_t max_pairs, uint64_t n_docs) {
+    return filter_hist_offset(n_queries) + (size_t)n_queries * filter_hist_bins(max_pairs, n_docs);
+}
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
                                FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
-                               uint64_t list_stride, uint32_t* cursor /*[B], out*/, hipStream_t stream);
+                               uint64_t list_stride, uint32_t* cursor /*out*/, hipStream_t stream);
 
 // ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
 struct TopkArgs {
@@ -131,8 +138,11 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 // k best of stored key lists: lists[b][0..counts[b]) (counts on the device), keys as built by make_key with
 // id_bits = bits of max_id; one workgroup per list.  When the score and id fields fit 32 bits together the lists hold
 // u32 keys (list b starts list_stride u32 entries after list b-1); launch_filter_count writes them the same way.
+// lists must be 16-byte aligned and list_stride a multiple of 4 (the lists are read 16 bytes at a time).
+// hist0: nullptr, or per list the histogram of its keys' score fields ([n_queries][bins], bin = score + 1, bins as
+// filter_hist_bins gives them): the selection then skips its first pass over the list.
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
-                             uint32_t k, uint32_t max_score, uint64_t max_id, uint32_t* out_ids, int32_t* out_scores,
-                             hipStream_t stream);
+                             uint32_t k, uint32_t max_score, uint64_t max_id, const uint32_t* hist0, uint32_t* out_ids,
+                             int32_t* out_scores, hipStream_t stream);
 
 }  // namespace dessert

@@ -66,16 +66,18 @@ template <typename KT>  // stored key type: uint64_t, or uint32_t when keys_fit_
 __global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT* __restrict__ lists, uint64_t list_stride,
                                                                        const uint32_t* __restrict__ counts, uint32_t k,
                                                                        KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
-                                                                       int32_t* __restrict__ out_scores) {
+                                                                       int32_t* __restrict__ out_scores,
+                                                                       const uint32_t* __restrict__ hist0, uint32_t hist_bins) {
     extern __shared__ uint64_t sorted[];
     __shared__ SelectShared sh;
     const uint32_t b = blockIdx.x;
+    const uint32_t* first_hist = hist0 ? hist0 + (size_t)b * hist_bins : nullptr;
     if constexpr (sizeof(KT) == 8) {
-        StoredKeys keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeys, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+        StoredKeysPairs keys{lists + (size_t)b * list_stride};
+        block_select<TOPK_LIST_THREADS, StoredKeysPairs, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist);
     } else {
         StoredKeys32 keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan);
+        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist);
     }
     for (uint32_t i = threadIdx.x; i < k; i += TOPK_LIST_THREADS)
         write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
@@ -94,10 +96,12 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
-                             uint32_t k, uint32_t max_score, uint64_t max_id, uint32_t* out_ids, int32_t* out_scores,
-                             hipStream_t stream) {
+                             uint32_t k, uint32_t max_score, uint64_t max_id, const uint32_t* hist0, uint32_t* out_ids,
+                             int32_t* out_scores, hipStream_t stream) {
     if (n_queries == 0 || k == 0) return hipSuccess;
     if (k > TOPK_KMAX) return hipErrorInvalidValue;
+    // the lists are read 16 bytes at a time
+    if ((uintptr_t)lists % 16 || list_stride % 4) return hipErrorInvalidValue;
     uint32_t kpad = 2;
     while (kpad < k) kpad <<= 1;
     const KeyPlan plan = make_key_plan(max_score, max_id);
@@ -106,12 +110,14 @@ hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const 
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
+    const uint32_t hist_bins = leading_score_bins(max_score, max_id);
+    if (hist0 && !hist_bins) return hipErrorInvalidValue;
     if (keys_fit_32(max_score, max_id))
         hipLaunchKernelGGL(topk_lists_kernel<uint32_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream,
-                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores);
+                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins);
     else
         hipLaunchKernelGGL(topk_lists_kernel<uint64_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists,
-                           list_stride, counts, k, plan, kpad, out_ids, out_scores);
+                           list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins);
     return hipGetLastError();
 }
 

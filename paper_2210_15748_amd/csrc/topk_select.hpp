@@ -1,5 +1,5 @@
 // Exact block-level top-k selection for gfx950 (device code shared by the stand-alone
-// top-k kernels and by the scoring kernel's fused finish).
+// top-k kernels and the candidate filter's probe and list selections).
 //
 // Alg. 2's last line returns the argmax; here the k best are returned, ordered by score
 // descending and, among equal scores, by ascending document id.  Every scored document
@@ -9,7 +9,7 @@
 // fixes the k-th largest key by most-significant-digit radix selection (digits of up to 11
 // bits, one histogram pass each, the digit chosen by a parallel suffix scan of the
 // histogram), emits the keys above it plus as many copies of it as are still needed, and
-// sorts those k keys in LDS with a bitonic network.
+// sorts those k keys with a bitonic network (in registers when a thread holds 1 to 16 of them, else in LDS).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -59,6 +59,14 @@ inline KeyPlan make_key_plan(uint32_t max_score, uint64_t max_id) {
     return p;
 }
 
+// Bins of the leading digit when that digit is exactly the score field (bin = score + 1), else 0.  A producer of
+// stored key lists that knows the scores can then hand block_select the leading digit's histogram (first_hist)
+// and save it the first pass over the list.
+inline uint32_t leading_score_bins(uint32_t max_score, uint64_t max_id) {
+    const KeyPlan p = make_key_plan(max_score, max_id);
+    return (p.n_digits > 1 && p.shift[0] == p.id_bits && p.width[0] == bits_for((uint64_t)max_score + 1)) ? 1u << p.width[0] : 0;
+}
+
 // stored key lists use 32-bit keys when the score and id fields fit
 inline bool keys_fit_32(uint32_t max_score, uint64_t max_id) {
     return bits_for(max_id) + bits_for((uint64_t)max_score + 1) <= 32;
@@ -90,16 +98,96 @@ struct SelectShared {
     uint32_t eq_taken;
 };
 
+constexpr int ilog2_floor(int x) { return x <= 1 ? 0 : 1 + ilog2_floor(x / 2); }
+
+// Bitonic sort (descending) of sorted[0 .. R*T) with the keys in registers: thread `tid` holds elements
+// R*tid .. R*tid+R-1, so a compare-exchange at stride < R pairs two of a thread's own registers, at stride < 64*R
+// two lanes of a wave (one shuffle per key, no barrier), and only strides >= 64*R cross waves.  Those go through
+// LDS, all strides >= 64*R of a merge in one trip: the T/64 elements that differ only in the wave bits form a
+// column which one thread loads, orders over all those strides, and stores.  A sort of 4096 keys by 1024 threads
+// makes 4 trips through LDS with a barrier pair each (sizes 512 .. 4096) instead of one per stride.
+// KS = uint32_t when every key is below 2^32: half the shuffles, and the exchanges are v_min / v_max.
+template <int T, int R, typename KS>
+__device__ void bitonic_sort_regs(uint64_t* sorted) {
+    constexpr int WAVES = T / 64, LOG_WAVES = ilog2_floor(WAVES);
+    constexpr uint32_t KPAD = (uint32_t)R * T, COLS = 64u * R;
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    auto order = [](KS& x, KS& y, bool desc) {  // desc: larger first
+        const KS lo = x < y ? x : y, hi = x < y ? y : x;
+        x = desc ? hi : lo;
+        y = desc ? lo : hi;
+    };
+    KS key[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) key[r] = (KS)sorted[R * tid + r];
+    for (uint32_t size = 2; size <= KPAD; size <<= 1) {
+        uint32_t stride = size >> 1;
+        if (stride >= COLS) {  // strides that cross waves
+            // (a thread's own slots: nobody else reads them between the trips)
+#pragma unroll
+            for (int r = 0; r < R; ++r) sorted[R * tid + r] = key[r];
+            __syncthreads();
+            for (uint32_t c = tid; c < COLS; c += T) {
+                KS col[WAVES];
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) col[w] = (KS)sorted[c + COLS * w];
+#pragma unroll
+                for (int sb = LOG_WAVES - 1; sb >= 0; --sb) {
+                    if ((COLS << sb) > stride) continue;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w)
+                        if ((w & (1 << sb)) == 0) order(col[w], col[w | (1 << sb)], ((COLS * w) & size) == 0);
+                }
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) sorted[c + COLS * w] = col[w];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < R; ++r) key[r] = (KS)sorted[R * tid + r];
+            stride = COLS >> 1;
+        }
+        for (; stride >= (uint32_t)R; stride >>= 1) {  // strides between lanes of a wave
+            const uint32_t lx = stride / R;
+            // this thread keeps the larger key of a pair when it holds the pair's lower element in a descending run
+            const bool keep_max = ((lane & lx) == 0) == (((R * tid) & size) == 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                KS o;
+                if constexpr (sizeof(KS) == 8) o = __shfl_xor((unsigned long long)key[r], (int)lx, 64);
+                else o = __shfl_xor((unsigned int)key[r], (int)lx, 64);
+                const KS lo = key[r] < o ? key[r] : o, hi = key[r] < o ? o : key[r];
+                key[r] = keep_max ? hi : lo;
+            }
+        }
+#pragma unroll
+        for (int st = R / 2; st >= 1; st >>= 1) {  // strides inside a thread
+            if ((uint32_t)st > stride) continue;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if ((r & st) == 0) order(key[r], key[r | st], ((R * tid + r) & size) == 0);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) sorted[R * tid + r] = key[r];
+    __syncthreads();
+}
+
 // Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
 // T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
-// U = key loads a thread keeps in flight while it scans the list (a pass over n keys is n / (T*U) round trips).
+// U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
+// lists: 16 bytes), so a pass over n keys is n / (T * U * VEC) round trips - a workgroup scanning one list is bound
+// by those round trips, not by bytes.
 // sorted: kpad = next power of two >= max(k, 2) entries of LDS.
+// first_hist: optional, leading_score_bins() counters (see there).
 template <int T, typename Keys, int U = 4>
 __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
-                             SelectShared& sh, const KeyPlan& plan) {
+                             SelectShared& sh, const KeyPlan& plan, const uint32_t* first_hist = nullptr) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
     constexpr int WAVES = T / 64;
+    constexpr int V = Keys::VEC;
+    using K = typename Keys::key_t;  // arithmetic on the keys of a pass is done in the stored width
     for (uint32_t i = tid; i < kpad; i += T) sorted[i] = 0;
     if (tid == 0) {
         sh.count = 0;
@@ -108,43 +196,64 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         sh.eq_taken = 0;
     }
     __syncthreads();
+    // f(key) for every key of the list.  Only a thread's last, partial trip checks indices key by key.
+    auto scan = [&](auto&& f) {
+        for (uint64_t i = (uint64_t)tid * V; i < n; i += (uint64_t)U * T * V) {  // U loads in flight per thread
+            K key[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) keys.load(i + (uint64_t)u * T * V, n, key[u]);
+            if (i + (uint64_t)(U - 1) * T * V + V <= n) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) f(key[u][v]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        if (i + (uint64_t)u * T * V + v < n) f(key[u][v]);
+            }
+        }
+    };
     if (n <= k) {
         for (uint64_t i = tid; i < n; i += T) sorted[i] = keys(i);
     } else {
         for (uint32_t d = 0; d < plan.n_digits; ++d) {
             const uint32_t shift = plan.shift[d], width = plan.width[d];
             const uint32_t nbins = 1u << width, dmask = nbins - 1;
-            for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = 0;
+            // first_hist: the leading digit's histogram over all n keys, counted by whoever wrote the list
+            const bool given = d == 0 && first_hist != nullptr;
+            for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = given ? first_hist[i] : 0;
             __syncthreads();
             const uint64_t prefix = sh.prefix;
             const uint32_t need = sh.need;
-            uint32_t run_bin = 0xFFFFFFFFu, run_len = 0;
-            for (uint64_t i = tid; i < n; i += U * T) {  // U loads in flight per thread
-                uint64_t key[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool in = i + u * T < n && (key[u] >> (shift + width)) == prefix;
-                    const uint32_t bin = (uint32_t)(key[u] >> shift) & dmask;
-                    if (d == 0) {
-                        // the leading digit holds the score's top bits and few values occur, mostly in runs: a thread
-                        // counts a run of equal bins in a register and adds it once
-                        if (in) {
-                            if (bin == run_bin) {
-                                ++run_len;
-                            } else {
-                                if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
-                                run_bin = bin;
-                                run_len = 1;
-                            }
-                        }
-                    } else if (in) {
-                        atomicAdd(&sh.hist[bin], 1u);
+            // a key takes part in this pass when its bits above the digit equal the digits fixed so far
+            const uint32_t above_bits = shift + width;
+            const K hi_mask = above_bits >= 8 * sizeof(K) ? K(0) : (K)(~K(0) << above_bits);
+            const K hi_value = above_bits >= 8 * sizeof(K) ? K(0) : (K)((K)prefix << above_bits);
+            if (given) {
+            } else if (d == 0) {
+                // the leading digit holds the score's top bits and few values occur, mostly in runs: a thread
+                // counts a run of equal bins in a register and adds it once
+                uint32_t run_bin = 0xFFFFFFFFu, run_len = 0;
+                scan([&](K key) {
+                    if ((key & hi_mask) != hi_value) return;
+                    const uint32_t bin = (uint32_t)(key >> shift) & dmask;
+                    if (bin == run_bin) {
+                        ++run_len;
+                    } else {
+                        if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
+                        run_bin = bin;
+                        run_len = 1;
                     }
-                }
+                });
+                if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
+            } else {
+                scan([&](K key) {
+                    if ((key & hi_mask) == hi_value) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & dmask], 1u);
+                });
             }
-            if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
             __syncthreads();
             // digit D with  count(digits > D) < need <= count(digits >= D):
             // thread t owns bins [t*per, (t+1)*per); suffix sums over threads, then a short scan
@@ -177,25 +286,59 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             }
             __syncthreads();
         }
-        const uint64_t kth = sh.prefix;   // the k-th largest key
+        const K kth = (K)sh.prefix;        // the k-th largest key
         const uint32_t need_eq = sh.need;  // copies of it that belong to the result
-        for (uint64_t i = tid; i < n; i += U * T) {
-            uint64_t key[U];
+        // Emit the keys above the k-th and need_eq copies of it.  Per trip a thread marks which of its keys go out,
+        // the wave adds the counts up (prefix sum over lanes) and takes its slots with one atomic: a few round trips
+        // per pass instead of one per key.  Every lane of the workgroup makes every trip.
+        static_assert(U * V <= 32, "one flag bit per key of a trip");
+        const uint64_t per_trip = (uint64_t)U * T * V;
+        for (uint64_t t0 = 0; t0 < n; t0 += per_trip) {
+            const uint64_t i = t0 + (uint64_t)tid * V;
+            K key[U][V];
 #pragma unroll
-            for (int u = 0; u < U; ++u) key[u] = i + u * T < n ? keys(i + u * T) : 0;
+            for (int u = 0; u < U; ++u) keys.load(i + (uint64_t)u * T * V, n, key[u]);
+            uint32_t flags = 0;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (i + u * T >= n) continue;
-                if (key[u] > kth) {
-                    sorted[atomicAdd(&sh.count, 1u)] = key[u];
-                } else if (key[u] == kth) {
-                    if (atomicAdd(&sh.eq_taken, 1u) < need_eq) sorted[atomicAdd(&sh.count, 1u)] = key[u];
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const bool have = i + (uint64_t)u * T * V + v < n;
+                    bool take = have && key[u][v] > kth;
+                    if (have && key[u][v] == kth) take = atomicAdd(&sh.eq_taken, 1u) < need_eq;
+                    flags |= (take ? 1u : 0u) << (u * V + v);
                 }
+            const uint32_t cnt = (uint32_t)__builtin_popcount(flags);
+            uint32_t incl = cnt;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t o = __shfl_up(incl, off, 64);
+                if ((int)lane >= off) incl += o;
             }
+            uint32_t base = 0;
+            if (lane == 63 && incl) base = atomicAdd(&sh.count, incl);
+            base = __shfl(base, 63, 64);
+            uint32_t pos = base + incl - cnt;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    if ((flags >> (u * V + v)) & 1u) sorted[pos++] = key[u][v];
         }
     }
     __syncthreads();
-    // bitonic sort, descending.  Two steps (strides s and s/2) per trip through LDS: a thread takes the four keys
+    // 1 to 16 keys per thread: sort in registers
+    if (kpad >= (uint32_t)T && kpad <= 16u * T) {
+        switch (kpad / T) {
+            case 1: bitonic_sort_regs<T, 1, K>(sorted); break;
+            case 2: bitonic_sort_regs<T, 2, K>(sorted); break;
+            case 4: bitonic_sort_regs<T, 4, K>(sorted); break;
+            case 8: bitonic_sort_regs<T, 8, K>(sorted); break;
+            default: bitonic_sort_regs<T, 16, K>(sorted); break;
+        }
+        return;
+    }
+    // otherwise in LDS.  Two steps (strides s and s/2) per trip through LDS: a thread takes the four keys
     // base, base+s/2, base+s, base+3s/2, which both steps pair among themselves, so the array is read and written
     // once per two steps.  Wave w owns the groups of the run [w*seg, (w+1)*seg) of the array (seg = kpad / WAVES);
     // a trip whose groups stay inside such a run touches only keys the same wave wrote, and a wave's LDS operations
@@ -256,7 +399,11 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
     __syncthreads();
 }
 
+// Key sources.  operator()(i) = key i; load(i, n, out) = the VEC keys i .. i+VEC-1 (i a multiple of VEC; entries at or
+// past n are unspecified and the caller ignores them; nothing is read when i >= n).
 struct ScoreKeys {  // keys computed from a score array (+ optional candidate ids)
+    static constexpr int VEC = 1;
+    using key_t = uint64_t;
     const int32_t* scores;
     const uint32_t* ids;  // nullptr: id = first_id + i
     uint64_t first_id;
@@ -265,16 +412,49 @@ struct ScoreKeys {  // keys computed from a score array (+ optional candidate id
         uint32_t id = ids ? ids[i] : (uint32_t)(first_id + i);
         return make_key(scores[i], id, id_bits);
     }
+    __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[1]) const { out[0] = i < n ? (*this)(i) : 0; }
 };
 
-struct StoredKeys {
+struct StoredKeys {  // 64-bit keys at any 8-byte aligned address
+    static constexpr int VEC = 1;
+    using key_t = uint64_t;
     const uint64_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
+    __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[1]) const { out[0] = i < n ? keys[i] : 0; }
+};
+
+// The two list forms below need lists that start 16-byte aligned and are allocated up to a multiple of 16 bytes, so
+// that a vector load which begins below n stays inside the list's allocation.
+struct StoredKeysPairs {
+    static constexpr int VEC = 2;
+    using key_t = uint64_t;
+    const uint64_t* keys;
+    __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
+    __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[2]) const {
+        out[0] = out[1] = 0;
+        if (i < n) {
+            const ulonglong2 v = *(const ulonglong2*)(keys + i);
+            out[0] = v.x;
+            out[1] = v.y;
+        }
+    }
 };
 
 struct StoredKeys32 {  // keys of at most 32 bits (score and id fields together), stored as u32
+    static constexpr int VEC = 4;
+    using key_t = uint32_t;
     const uint32_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
+    __device__ void load(uint64_t i, uint64_t n, uint32_t (&out)[4]) const {
+        out[0] = out[1] = out[2] = out[3] = 0;
+        if (i < n) {
+            const uint4 v = *(const uint4*)(keys + i);
+            out[0] = v.x;
+            out[1] = v.y;
+            out[2] = v.z;
+            out[3] = v.w;
+        }
+    }
 };
 
 }  // namespace dessert

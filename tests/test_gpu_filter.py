@@ -61,7 +61,7 @@ def test_filter_build_assignments_and_buckets(d, K, n_docs, dup, max_len):
 
 @pytest.mark.parametrize("probe,filter_k,q_lens,n_docs,max_len", [
     (1, 64, [32, 32, 32], 1500, 12), (2, 300, [5, 40, 1], 1500, 12), (4, 16, [32], 1500, 12),
-    (8, 4096, [12, 7], 1500, 12), (37, 50, [3, 3], 1500, 12),
+    (8, 4096, [12, 7], 1500, 12), (37, 50, [3, 3], 1500, 12), (8, 5000, [12, 7], 30_000, 3),
     (37, 200, [10, 2], 1500, 12),            # counts up to 370: 16-bit counters
     (37, 16384, [1800, 5], 1500, 12),        # counts up to 66600: 32-bit counters
     (2, 1000, [32, 9], 300_000, 3),          # ten document slabs of 8-bit counters, first-hit queues overflow

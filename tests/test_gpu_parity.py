@@ -415,6 +415,34 @@ def test_search_eq1_cfg3_reduced_changes_ranking_but_matches_oracle():
 
 
 # ------------------------------------------------------------------ randomized sweep over configurations
+@pytest.mark.parametrize("k", [512, 1000, 3000, 8192, 16384])
+def test_search_large_k_full_order(k):
+    """k from one key per thread of the selecting workgroup up to the largest allowed: the whole result order."""
+    say(f"search: large k={k}")
+    rng = np.random.default_rng(77)
+    d, L, Cb, N = 64, 16, 5, 20_000
+    lens = rng.integers(1, 5, N)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (40, d))
+    X = np.clip(pool[rng.integers(0, 40, V)] + rng.integers(-50, 51, (V, d)), -127, 127).astype(np.int8)
+    Q = np.clip(pool[rng.integers(0, 40, 9)] + rng.integers(-50, 51, (9, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    cand = rng.choice(N, 9000, replace=False).astype(np.int32)
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), [4, 5], k)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    want_ids, want_sc, _ = orc.search(dc, off, [qc[:4], qc[4:]], k)
+    assert np.array_equal(sc.cpu().numpy(), want_sc)
+    assert np.array_equal(ids.cpu().numpy(), want_ids)
+    # a candidate list shorter than k: the tail is padding
+    ids, sc = dz.search(ix, torch.from_numpy(Q[:4]).to(DEV), [4], k, cand_ids=torch.from_numpy(cand).to(DEV), cand_offsets=[0, 9000])
+    s_all = orc.scores(dc, off, qc[:4], cand)
+    w_ids, w_sc = orc.topk(s_all, k, cand)
+    assert np.array_equal(sc.cpu().numpy()[0], w_sc) and np.array_equal(ids.cpu().numpy()[0], w_ids)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_end_to_end(seed):
     """Random (d, L, C, lengths, query lengths, candidates, k, transform) through the default kernel choice."""
