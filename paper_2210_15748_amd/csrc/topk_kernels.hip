@@ -21,6 +21,9 @@ uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries) {
 }
 
 // grid (slices, B).  slices == 1: final results; else per-slice keys to a.partial.
+// KT: the width the keys are computed in (uint32_t when keys_fit_32).  Eight loads in flight per thread; a slice of
+// at most 4096 scores stays in registers for all passes.
+template <typename KT>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, KeyPlan plan, uint32_t slices,
                                                                    uint32_t kpad) {
     extern __shared__ uint64_t sorted[];
@@ -37,8 +40,8 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, K
     const uint64_t per = (count + slices - 1) / slices;
     const uint64_t lo = (uint64_t)s * per < count ? (uint64_t)s * per : count;
     const uint64_t hi = lo + per < count ? lo + per : count;
-    ScoreKeys keys{a.scores + base + lo, a.cand_ids ? a.cand_ids + base + lo : nullptr, lo, plan.id_bits};
-    block_select<TOPK_THREADS>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
+    ScoreKeysT<KT> keys{a.scores + base + lo, a.cand_ids ? a.cand_ids + base + lo : nullptr, lo, plan.id_bits};
+    block_select<TOPK_THREADS, ScoreKeysT<KT>, 8>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
     if (slices == 1) {
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
             write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
@@ -84,7 +87,9 @@ __global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT*
 }
 
 static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the selection state is another 8.3 KB)
-    static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel,
+    static hipError_t a0 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint32_t>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint64_t>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
@@ -92,7 +97,7 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a4 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint32_t>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    return a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4;
+    return a0 != hipSuccess ? a0 : a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4;
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
@@ -133,8 +138,12 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(topk_scores_kernel, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices,
-                       kpad);
+    if (keys_fit_32(a.max_score, a.n_docs ? a.n_docs - 1 : 0))
+        hipLaunchKernelGGL(topk_scores_kernel<uint32_t>, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a,
+                           plan, slices, kpad);
+    else
+        hipLaunchKernelGGL(topk_scores_kernel<uint64_t>, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a,
+                           plan, slices, kpad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
     hipLaunchKernelGGL(topk_merge_kernel, dim3(a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices, kpad);

@@ -196,8 +196,23 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         sh.eq_taken = 0;
     }
     __syncthreads();
+    // A list of at most T*U*V keys is loaded once and kept in registers for all passes.
+    const bool cached = n <= (uint64_t)T * U * V;
+    K cache[U][V];
+    if (cached) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) keys.load((uint64_t)tid * V + (uint64_t)u * T * V, n, cache[u]);
+    }
     // f(key) for every key of the list.  Only a thread's last, partial trip checks indices key by key.
     auto scan = [&](auto&& f) {
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    if ((uint64_t)tid * V + (uint64_t)u * T * V + v < n) f(cache[u][v]);
+            return;
+        }
         for (uint64_t i = (uint64_t)tid * V; i < n; i += (uint64_t)U * T * V) {  // U loads in flight per thread
             K key[U][V];
 #pragma unroll
@@ -297,7 +312,14 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             const uint64_t i = t0 + (uint64_t)tid * V;
             K key[U][V];
 #pragma unroll
-            for (int u = 0; u < U; ++u) keys.load(i + (uint64_t)u * T * V, n, key[u]);
+            for (int u = 0; u < U; ++u) {
+                if (cached) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) key[u][v] = cache[u][v];
+                } else {
+                    keys.load(i + (uint64_t)u * T * V, n, key[u]);
+                }
+            }
             uint32_t flags = 0;
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -401,9 +423,10 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
 
 // Key sources.  operator()(i) = key i; load(i, n, out) = the VEC keys i .. i+VEC-1 (i a multiple of VEC; entries at or
 // past n are unspecified and the caller ignores them; nothing is read when i >= n).
-struct ScoreKeys {  // keys computed from a score array (+ optional candidate ids)
+template <typename KT>  // uint64_t, or uint32_t when keys_fit_32
+struct ScoreKeysT {  // keys computed from a score array (+ optional candidate ids)
     static constexpr int VEC = 1;
-    using key_t = uint64_t;
+    using key_t = KT;
     const int32_t* scores;
     const uint32_t* ids;  // nullptr: id = first_id + i
     uint64_t first_id;
@@ -412,8 +435,9 @@ struct ScoreKeys {  // keys computed from a score array (+ optional candidate id
         uint32_t id = ids ? ids[i] : (uint32_t)(first_id + i);
         return make_key(scores[i], id, id_bits);
     }
-    __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[1]) const { out[0] = i < n ? (*this)(i) : 0; }
+    __device__ void load(uint64_t i, uint64_t n, KT (&out)[1]) const { out[0] = i < n ? (KT)(*this)(i) : KT(0); }
 };
+using ScoreKeys = ScoreKeysT<uint64_t>;
 
 struct StoredKeys {  // 64-bit keys at any 8-byte aligned address
     static constexpr int VEC = 1;
