@@ -390,7 +390,9 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
 // cursor[b] ends as the number of distinct documents hit.  The order inside a list is unspecified.
 // Only if the queue overflows (more than FILTER_QUEUE distinct documents of one slab hit) are the counters
 // scanned instead.
-constexpr uint32_t FILTER_QUEUE = 4096;  // first-hit queue entries per workgroup (positions within the slab: QT = u16, or u32 for slabs over 65536 documents)
+// first-hit queue entries per workgroup (positions within the slab: QT = u16, or u32 for slabs over 65536 documents).
+// 3840: with a slab of 32768 one-byte counters the workgroup then needs just under 40 KB of LDS and four fit a CU.
+constexpr uint32_t FILTER_QUEUE = 3840;
 
 template <int W, int T, typename QT, typename KT>
 __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
