@@ -443,6 +443,45 @@ def test_search_large_k_full_order(k):
     assert np.array_equal(sc.cpu().numpy()[0], w_sc) and np.array_equal(ids.cpu().numpy()[0], w_ids)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_search_random_list_lengths_and_k_with_heavy_ties(seed):
+    """The selection alone under stress: few tables (scores tie in large groups), candidate lists of random length with
+    repeated ids, k from 1 to the largest allowed, lists shorter than, equal to and longer than k."""
+    rng = np.random.default_rng(4000 + seed)
+    d, L, Cb, N = 64, 4, int(rng.integers(1, 4)), 30_000
+    lens = rng.integers(1, 3, N)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (12, d))
+    X = np.clip(pool[rng.integers(0, 12, V)] + rng.integers(-40, 41, (V, d)), -127, 127).astype(np.int8)
+    B = int(rng.integers(1, 4))
+    q_lens = rng.integers(1, 6, B)
+    nq = int(q_lens.sum())
+    Q = np.clip(pool[rng.integers(0, 12, nq)] + rng.integers(-40, 41, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    k = int(rng.choice([1, 7, 64, 500, 512, 513, 2048, 5000, 16384]))
+    n_cand = [int(rng.choice([1, 63, 500, 4096, 4097, 9000, 20_000])) for _ in range(B)]
+    say(f"selection stress seed={seed} C={Cb} B={B} q_lens={q_lens.tolist()} k={k} lists={n_cand}")
+    cands = [rng.integers(0, N, n).astype(np.int32) for n in n_cand]      # with replacement: repeated ids
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    c_off = np.concatenate([[0], np.cumsum(n_cand)])
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, k, cand_ids=torch.from_numpy(np.concatenate(cands)).to(DEV),
+                        cand_offsets=c_off)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    q_off = np.concatenate([[0], np.cumsum(q_lens)])
+    for b in range(B):
+        s_all = orc.scores(dc, off, qc[q_off[b]:q_off[b + 1]], cands[b])
+        w_ids, w_sc = orc.topk(s_all, k, cands[b])
+        assert np.array_equal(sc[b], w_sc), f"scores differ for query set {b}"
+        assert np.array_equal(ids[b], w_ids), f"ids differ for query set {b}"
+    # every document for every query set, same k
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, k)
+    want_ids, want_sc, _ = orc.search(dc, off, [qc[q_off[b]:q_off[b + 1]] for b in range(B)], k)
+    assert np.array_equal(sc.cpu().numpy(), want_sc) and np.array_equal(ids.cpu().numpy(), want_ids)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_end_to_end(seed):
     """Random (d, L, C, lengths, query lengths, candidates, k, transform) through the default kernel choice."""
