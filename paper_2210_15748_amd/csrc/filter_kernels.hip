@@ -13,7 +13,7 @@ namespace dessert {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int FILTER_TG = 8;           // centroid tiles staged in LDS per step
+constexpr int FILTER_TG = 8;           // centroid tiles per LDS group (the kernel may take half of it)
 constexpr int32_t FILTER_BIAS = 1 << 24;  // 2 x.c - |c|^2 lies in (-2^24, 2^24) for int8 vectors up to d = 256
 
 // accumulator register r of lane half g holds tile row 8*(r/4) + 4*g + r%4
@@ -62,8 +62,8 @@ __global__ void filter_prep_kernel(const int8_t* __restrict__ Cn, uint32_t K, ui
 
 // ---------------------------------------------------------------------------
 // vectors x centroids.  Each wave keeps 32*NT vectors as MFMA B fragments in registers and walks
-// over a range of centroid tiles (blockIdx.y selects the range); the workgroup stages FILTER_TG
-// tiles of centroids (and their key constants) in LDS at a time.  Three epilogues:
+// over a range of centroid tiles (blockIdx.y selects the range); the workgroup keeps two groups of TG
+// tiles of centroids (and their key constants) in LDS, one being multiplied, one being filled.  Three epilogues:
 //   MODE = 0      closest centroid of every vector (running max of the keys; the two lane halves
 //                 of a column are merged at the end); one tile range only.
 //   MODE = P > 0  the P best centroids each lane has seen, as sorted lists of 64-bit entries
@@ -99,9 +99,15 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
     // a list of one entry is an argmax: MODE = 1 keeps the 32-bit running key of MODE = 0 (no 64-bit list
     // inserts in the loop) and forms its list entry at the end
     constexpr bool ARGMAX = MODE == 0 || MODE == 1;
-    __shared__ v4i sA[FILTER_TG * KS * 64];
-    __shared__ v4i sT[FILTER_TG * 8];  // 32 ints per tile
-    __shared__ uint32_t sP[FILTER_TG * 2];
+    // centroid tiles per group: 8 for the build's assignment (long ranges, d <= 128), 4 on the query side and for
+    // d = 256, where two buffers of 8 tiles would leave a CU with fewer workgroups than the registers allow
+    constexpr int TG = (MODE == 0 && KS <= 4) ? FILTER_TG : FILTER_TG / 2;
+    // two groups of centroid tiles in LDS: while the waves multiply one, the next is copied from global memory
+    // straight into the other buffer (global_load ... lds: no staging registers; a wave's 64 lanes fill
+    // consecutive LDS), one barrier per group
+    __shared__ v4i sA[2][TG * KS * 64];
+    __shared__ v4i sT[2][TG * 8];  // 32 ints per tile
+    __shared__ uint32_t sP[2][64];        // TG * 2 in use; a wave's copy lands at lane * 4 bytes
     const uint32_t* PAR = (const uint32_t*)T2 + (size_t)tiles * 32;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
@@ -130,26 +136,39 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
         for (int i = 0; i < P; ++i) best[nt][i] = LIST_EMPTY;
     }
 
-    for (uint32_t t0 = t_begin; t0 < t_end; t0 += FILTER_TG) {
-        const uint32_t tg = t_end - t0 < FILTER_TG ? t_end - t0 : FILTER_TG;
-        __syncthreads();
-        for (uint32_t i = threadIdx.x; i < tg * KS * 64; i += 256) sA[i] = Cp[(size_t)t0 * KS * 64 + i];
-        for (uint32_t i = threadIdx.x; i < tg * 8; i += 256) sT[i] = T2[(size_t)t0 * 8 + i];
-        for (uint32_t i = threadIdx.x; i < tg * 2; i += 256) sP[i] = PAR[(size_t)t0 * 2 + i];
-        __syncthreads();
+    static_assert(TG * 8 <= 64 && TG * 2 <= 64, "the key constants of a group are one wave's copy");
+    auto stage = [&](uint32_t t0, int buf) {  // every copy instruction is issued by whole waves (exec masks the tail)
+        const uint32_t tg = t_end - t0 < TG ? t_end - t0 : TG;
+        for (uint32_t i = threadIdx.x; i < tg * KS * 64; i += 256)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Cp + (size_t)t0 * KS * 64 + i),
+                                             (__attribute__((address_space(3))) void*)&sA[buf][i - lane], 16, 0, 0);
+        if (wave == 0 && (uint32_t)lane < tg * 8)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(T2 + (size_t)t0 * 8 + lane),
+                                             (__attribute__((address_space(3))) void*)&sT[buf][0], 16, 0, 0);
+        if (wave == 1 && (uint32_t)lane < tg * 2)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(PAR + (size_t)t0 * 2 + lane),
+                                             (__attribute__((address_space(3))) void*)&sP[buf][0], 4, 0, 0);
+    };
+    if (t_begin < t_end) stage(t_begin, 0);
+    int buf = 0;
+    for (uint32_t t0 = t_begin; t0 < t_end; t0 += TG, buf ^= 1) {
+        const uint32_t tg = t_end - t0 < TG ? t_end - t0 : TG;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's copies into sA[buf] have landed
+        __syncthreads();                                   // everyone's have, and everyone is done with the other buffer
+        if (t0 + TG < t_end) stage(t0 + TG, buf ^ 1);
 #pragma unroll 1
         for (uint32_t tt = 0; tt < tg; ++tt) {
             v16i init;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                v4i t = sT[tt * 8 + g * 4 + q];
+                v4i t = sT[buf][tt * 8 + g * 4 + q];
                 init[4 * q] = t.x; init[4 * q + 1] = t.y; init[4 * q + 2] = t.z; init[4 * q + 3] = t.w;
             }
-            const uint32_t par = sP[tt * 2 + g];
+            const uint32_t par = sP[buf][tt * 2 + g];
             v16i acc[NT];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                v4i a = sA[(tt * KS + ks) * 64 + lane];
+                v4i a = sA[buf][(tt * KS + ks) * 64 + lane];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     acc[nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[nt][ks], ks == 0 ? init : acc[nt], 0, 0, 0);
@@ -666,7 +685,7 @@ static hipError_t launch_gemm(const int8_t* X, uint64_t n, uint32_t d, uint32_t 
 
 hipError_t launch_filter_assign(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                 uint32_t* assign, hipStream_t stream) {
-    return launch_gemm<2, 0>(X, n, d, K, Cp, T2, 1, filter_tiles(K), assign, nullptr, nullptr, stream);
+    return launch_gemm<4, 0>(X, n, d, K, Cp, T2, 1, filter_tiles(K), assign, nullptr, nullptr, stream);
 }
 
 hipError_t launch_filter_distances(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
