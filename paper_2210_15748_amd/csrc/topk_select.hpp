@@ -10,6 +10,8 @@
 // bits, one histogram pass each, the digit chosen by a parallel suffix scan of the
 // histogram), emits the keys above it plus as many copies of it as are still needed, and
 // sorts those k keys with a bitonic network (in registers when a thread holds 1 to 16 of them, else in LDS).
+// Shortcut after the first digit: when at most 1024 keys lie at or above its threshold bin they are gathered
+// and sorted in LDS, and the remaining passes are skipped.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -173,6 +175,72 @@ __device__ void bitonic_sort_regs(uint64_t* sorted) {
     __syncthreads();
 }
 
+// Bitonic sort (descending) of a[0 .. npad) in LDS, npad a power of two >= 2; the array must be complete (a workgroup
+// barrier behind its last write) on entry and is complete on return.  Two steps (strides s and s/2) per trip through
+// LDS: a thread takes the four keys base, base+s/2, base+s, base+3s/2, which both steps pair among themselves, so the
+// array is read and written once per two steps.  Wave w owns the groups of the run [w*seg, (w+1)*seg) of the array
+// (seg = npad / WAVES); a trip whose groups stay inside such a run touches only keys the same wave wrote, and a wave's
+// LDS operations execute in order, so two such trips in a row need no workgroup barrier between them.
+template <int T>
+__device__ void bitonic_sort_lds(uint64_t* a, uint32_t npad) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int WAVES = T / 64;
+    auto order = [](uint64_t& x, uint64_t& y, bool desc) {
+        if ((x < y) == desc) {
+            const uint64_t t = x;
+            x = y;
+            y = t;
+        }
+    };
+    const bool by_wave = npad >= 256u * WAVES;   // every lane has at least one group of four in its wave's run
+    const uint32_t seg = by_wave ? npad / WAVES : npad;
+    bool prev_local = false;
+    for (uint32_t size = 2; size <= npad; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0;) {
+            const bool local = by_wave && 2 * stride <= seg;
+            if (!(local && prev_local)) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+            prev_local = local;
+            if (stride >= 2) {  // strides `stride` and `stride / 2` together
+                const uint32_t h = stride >> 1;
+                const uint32_t groups = npad / 4;
+                const uint32_t g_lo = by_wave ? wave * (seg / 4) : 0, g_n = by_wave ? seg / 4 : groups;
+                for (uint32_t m = by_wave ? lane : tid; m < g_n; m += by_wave ? 64 : T) {
+                    const uint32_t g = g_lo + m;
+                    const uint32_t base = (g / h) * (2 * stride) + (g % h);
+                    const bool desc = ((base & size) == 0);
+                    uint64_t k0 = a[base], k1 = a[base + h], k2 = a[base + stride], k3 = a[base + stride + h];
+                    order(k0, k2, desc);
+                    order(k1, k3, desc);
+                    order(k0, k1, desc);
+                    order(k2, k3, desc);
+                    a[base] = k0;
+                    a[base + h] = k1;
+                    a[base + stride] = k2;
+                    a[base + stride + h] = k3;
+                }
+                stride >>= 2;
+            } else {  // stride 1 alone
+                const uint32_t p_lo = by_wave ? wave * (seg / 2) : 0, p_n = by_wave ? seg / 2 : npad / 2;
+                for (uint32_t m = by_wave ? lane : tid; m < p_n; m += by_wave ? 64 : T) {
+                    const uint32_t lo = 2 * (p_lo + m);
+                    const bool desc = ((lo & size) == 0);
+                    uint64_t x = a[lo], y = a[lo + 1];
+                    order(x, y, desc);
+                    a[lo] = x;
+                    a[lo + 1] = y;
+                }
+                stride = 0;
+            }
+        }
+    }
+    __syncthreads();
+}
+
 // Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
 // T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
 // U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
@@ -229,6 +297,50 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     for (int v = 0; v < V; ++v)
                         if (i + (uint64_t)u * T * V + v < n) f(key[u][v]);
             }
+        }
+    };
+    // dst[sh.count++] = key for every key of the list with take(key).  Per trip a thread marks which of its keys go
+    // out, the wave adds the counts up (prefix sum over lanes) and takes its slots with one atomic: a few round trips
+    // per pass instead of one per key.  Every lane of the workgroup makes every trip.
+    static_assert(U * V <= 32, "one flag bit per key of a trip");
+    auto append_pass = [&](uint64_t* dst, auto&& take) {
+        const uint64_t per_trip = (uint64_t)U * T * V;
+        for (uint64_t t0 = 0; t0 < n; t0 += per_trip) {
+            const uint64_t i = t0 + (uint64_t)tid * V;
+            K key[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (cached) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) key[u][v] = cache[u][v];
+                } else {
+                    keys.load(i + (uint64_t)u * T * V, n, key[u]);
+                }
+            }
+            uint32_t flags = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const bool have = i + (uint64_t)u * T * V + v < n;
+                    flags |= ((have && take(key[u][v])) ? 1u : 0u) << (u * V + v);
+                }
+            const uint32_t cnt = (uint32_t)__builtin_popcount(flags);
+            uint32_t incl = cnt;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t o = __shfl_up(incl, off, 64);
+                if ((int)lane >= off) incl += o;
+            }
+            uint32_t base = 0;
+            if (lane == 63 && incl) base = atomicAdd(&sh.count, incl);
+            base = __shfl(base, 63, 64);
+            uint32_t pos = base + incl - cnt;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    if ((flags >> (u * V + v)) & 1u) dst[pos++] = key[u][v];
         }
     };
     if (n <= k) {
@@ -300,53 +412,36 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                 }
             }
             __syncthreads();
+            // Few keys left at or above the threshold bin of the leading digit (the usual case when that digit is
+            // the score and k is small): gather them in LDS (the histogram's space), sort them there and take the
+            // first k, instead of one more pass over the list per remaining digit plus the emit.
+            if (d == 0 && plan.n_digits > 1) {
+                constexpr uint32_t CAP = TOPK_HIST / 2;  // 64-bit keys that fit the histogram
+                const uint32_t bin0 = (uint32_t)sh.prefix;
+                const uint32_t at_or_above = (k - sh.need) + sh.hist[bin0];  // >= k
+                __syncthreads();  // everyone has read the histogram
+                if (at_or_above <= CAP) {
+                    uint64_t* gathered = reinterpret_cast<uint64_t*>(sh.hist);
+                    const K lowest = (K)((K)bin0 << shift);
+                    append_pass(gathered, [&](K key) { return key >= lowest; });
+                    uint32_t gpad = 2;
+                    while (gpad < at_or_above) gpad <<= 1;
+                    for (uint32_t i = at_or_above + tid; i < gpad; i += T) gathered[i] = 0;
+                    __syncthreads();
+                    bitonic_sort_lds<T>(gathered, gpad);
+                    for (uint32_t i = tid; i < k; i += T) sorted[i] = gathered[i];
+                    __syncthreads();
+                    return;
+                }
+            }
         }
         const K kth = (K)sh.prefix;        // the k-th largest key
         const uint32_t need_eq = sh.need;  // copies of it that belong to the result
-        // Emit the keys above the k-th and need_eq copies of it.  Per trip a thread marks which of its keys go out,
-        // the wave adds the counts up (prefix sum over lanes) and takes its slots with one atomic: a few round trips
-        // per pass instead of one per key.  Every lane of the workgroup makes every trip.
-        static_assert(U * V <= 32, "one flag bit per key of a trip");
-        const uint64_t per_trip = (uint64_t)U * T * V;
-        for (uint64_t t0 = 0; t0 < n; t0 += per_trip) {
-            const uint64_t i = t0 + (uint64_t)tid * V;
-            K key[U][V];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (cached) {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) key[u][v] = cache[u][v];
-                } else {
-                    keys.load(i + (uint64_t)u * T * V, n, key[u]);
-                }
-            }
-            uint32_t flags = 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const bool have = i + (uint64_t)u * T * V + v < n;
-                    bool take = have && key[u][v] > kth;
-                    if (have && key[u][v] == kth) take = atomicAdd(&sh.eq_taken, 1u) < need_eq;
-                    flags |= (take ? 1u : 0u) << (u * V + v);
-                }
-            const uint32_t cnt = (uint32_t)__builtin_popcount(flags);
-            uint32_t incl = cnt;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t o = __shfl_up(incl, off, 64);
-                if ((int)lane >= off) incl += o;
-            }
-            uint32_t base = 0;
-            if (lane == 63 && incl) base = atomicAdd(&sh.count, incl);
-            base = __shfl(base, 63, 64);
-            uint32_t pos = base + incl - cnt;
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    if ((flags >> (u * V + v)) & 1u) sorted[pos++] = key[u][v];
-        }
+        append_pass(sorted, [&](K key) {
+            bool take = key > kth;
+            if (key == kth) take = atomicAdd(&sh.eq_taken, 1u) < need_eq;
+            return take;
+        });
     }
     __syncthreads();
     // 1 to 16 keys per thread: sort in registers
@@ -360,65 +455,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         }
         return;
     }
-    // otherwise in LDS.  Two steps (strides s and s/2) per trip through LDS: a thread takes the four keys
-    // base, base+s/2, base+s, base+3s/2, which both steps pair among themselves, so the array is read and written
-    // once per two steps.  Wave w owns the groups of the run [w*seg, (w+1)*seg) of the array (seg = kpad / WAVES);
-    // a trip whose groups stay inside such a run touches only keys the same wave wrote, and a wave's LDS operations
-    // execute in order, so two such trips in a row need no workgroup barrier between them.
-    auto order = [](uint64_t& x, uint64_t& y, bool desc) {
-        if ((x < y) == desc) {
-            const uint64_t t = x;
-            x = y;
-            y = t;
-        }
-    };
-    const bool by_wave = kpad >= 256u * WAVES;   // every lane has at least one group of four in its wave's run
-    const uint32_t seg = by_wave ? kpad / WAVES : kpad;
-    bool prev_local = false;
-    for (uint32_t size = 2; size <= kpad; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0;) {
-            const bool local = by_wave && 2 * stride <= seg;
-            if (!(local && prev_local)) {
-                __syncthreads();
-            } else {
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-            prev_local = local;
-            if (stride >= 2) {  // strides `stride` and `stride / 2` together
-                const uint32_t h = stride >> 1;
-                const uint32_t groups = kpad / 4;
-                const uint32_t g_lo = by_wave ? wave * (seg / 4) : 0, g_n = by_wave ? seg / 4 : groups;
-                for (uint32_t m = by_wave ? lane : tid; m < g_n; m += by_wave ? 64 : T) {
-                    const uint32_t g = g_lo + m;
-                    const uint32_t base = (g / h) * (2 * stride) + (g % h);
-                    const bool desc = ((base & size) == 0);
-                    uint64_t k0 = sorted[base], k1 = sorted[base + h], k2 = sorted[base + stride], k3 = sorted[base + stride + h];
-                    order(k0, k2, desc);
-                    order(k1, k3, desc);
-                    order(k0, k1, desc);
-                    order(k2, k3, desc);
-                    sorted[base] = k0;
-                    sorted[base + h] = k1;
-                    sorted[base + stride] = k2;
-                    sorted[base + stride + h] = k3;
-                }
-                stride >>= 2;
-            } else {  // stride 1 alone
-                const uint32_t p_lo = by_wave ? wave * (seg / 2) : 0, p_n = by_wave ? seg / 2 : kpad / 2;
-                for (uint32_t m = by_wave ? lane : tid; m < p_n; m += by_wave ? 64 : T) {
-                    const uint32_t lo = 2 * (p_lo + m);
-                    const bool desc = ((lo & size) == 0);
-                    uint64_t x = sorted[lo], y = sorted[lo + 1];
-                    order(x, y, desc);
-                    sorted[lo] = x;
-                    sorted[lo + 1] = y;
-                }
-                stride = 0;
-            }
-        }
-    }
-    __syncthreads();
+    bitonic_sort_lds<T>(sorted, kpad);
 }
 
 // Key sources.  operator()(i) = key i; load(i, n, out) = the VEC keys i .. i+VEC-1 (i a multiple of VEC; entries at or
