@@ -177,6 +177,30 @@ struct Batch {
     uint64_t cand_uniform = 0;   // common candidate-list length, 0 if they differ (or no candidates)
 };
 
+// Asynchronous upload of a small host array through one of the handle's pinned staging slots (a slot is reused
+// only after the copy that read it has finished).
+dessert_status_t upload_small(dessert_index* ix, const void* src, size_t bytes, void* dst_dev) {
+    dessert_index::MetaSlot& ms = ix->meta[ix->meta_next++ % dessert_index::kMetaSlots];
+    if (ms.pending) {
+        HIP_TRY(hipEventSynchronize(ms.done));
+        ms.pending = false;
+    }
+    if (ms.cap < bytes) {
+        if (ms.host) (void)hipHostFree(ms.host);
+        ms.host = nullptr;
+        ms.cap = 0;
+        hipError_t e = hipHostMalloc((void**)&ms.host, 2 * bytes, hipHostMallocDefault);
+        if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipHostMalloc(batch offsets): %s", hipGetErrorString(e));
+        ms.cap = 2 * bytes;
+    }
+    if (!ms.done) HIP_TRY(hipEventCreateWithFlags(&ms.done, hipEventDisableTiming));
+    memcpy(ms.host, src, bytes);
+    HIP_TRY(hipMemcpyAsync(dst_dev, ms.host, bytes, hipMemcpyHostToDevice, ix->stream));
+    HIP_TRY(hipEventRecord(ms.done, ix->stream));
+    ms.pending = true;
+    return DESSERT_OK;
+}
+
 dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, const uint32_t* q_lengths, uint32_t B,
                              const uint32_t* cand_ids, const uint64_t* cand_off, Batch* out) {
     if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
@@ -340,7 +364,10 @@ dessert_status_t dessert_probe_read_bandwidth(const void* buf_dev, size_t bytes,
     if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", device);
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
-    HIP_TRY(hipEventCreate(&e1));
+    if (hipError_t ec = hipEventCreate(&e1); ec != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(DESSERT_EHIP, "hipEventCreate: %s", hipGetErrorString(ec));
+    }
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = launch_read_probe(buf_dev, bytes, st);  // warm-up
     if (e == hipSuccess) e = hipEventRecord(e0, st);
@@ -708,7 +735,7 @@ FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total
     w.dist = p;      p += align_up(pl.ranges ? pl.list_bytes : (size_t)total_q * filter_tiles(ix->f_K) * 32 * 4, 256);
     w.probe_ids = p; p += align_up((size_t)total_q * probe * 4, 256);
     w.q_off = p;     p += align_up(((size_t)B + 1) * 4, 256);
-    w.cursor = p;    p += align_up(filter_cursor_words(B, max_q * probe, ix->n_docs) * 4, 256);  // list lengths + count histograms
+    w.cursor = p;    p += align_up(filter_hist_plan(B, max_q * probe, ix->n_docs, ix->f_sub).words * 4, 256);  // list lengths + count histograms
     // a query set hits at most (its vectors * probe) buckets of at most f_max_bucket documents each
     uint64_t hit = (uint64_t)max_q * probe * ix->f_max_bucket;
     if (hit > ix->n_docs) hit = ix->n_docs;
@@ -764,8 +791,10 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     uint32_t* d_q_off = (uint32_t*)(ws + w.q_off);
     uint32_t* cursor = (uint32_t*)(ws + w.cursor);
     uint64_t* lists = (uint64_t*)(ws + w.lists);
-    if (!q_uniform)  // pageable source: the runtime stages it before returning
-        HIP_TRY(hipMemcpyAsync(d_q_off, q_off.data(), ((size_t)n_queries + 1) * 4, hipMemcpyHostToDevice, ix->stream));
+    if (!q_uniform) {
+        dessert_status_t st = upload_small(ix, q_off.data(), ((size_t)n_queries + 1) * 4, d_q_off);
+        if (st != DESSERT_OK) return st;
+    }
     const FilterProbePlan pl = filter_probe_plan(total_q, ix->f_K, filter_probe);
     if (pl.ranges) {
         HIP_TRY(launch_filter_probe_lists((const int8_t*)q_vectors_dev, total_q, ix->cfg.d, ix->f_K, ix->f_cent,
@@ -778,10 +807,10 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     HIP_TRY(launch_filter_count(probe_ids, total_q, filter_probe, max_q * filter_probe, d_q_off, q_uniform, n_queries,
                                 ix->f_sub_off, ix->f_sub, ix->f_bucket_docs, ix->n_docs, lists, w.list_stride, cursor,
                                 ix->stream));
-    const uint32_t* hist0 = (ix->n_docs && total_q && filter_hist_bins(max_q * filter_probe, ix->n_docs))
-                                ? cursor + filter_hist_offset(n_queries) : nullptr;
+    const FilterHistPlan hp = filter_hist_plan(n_queries, max_q * filter_probe, ix->n_docs, ix->f_sub);
     HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
-                              ix->n_docs ? ix->n_docs - 1 : 0, hist0, out_ids_dev, out_counts_dev, ix->stream));
+                              ix->n_docs ? ix->n_docs - 1 : 0, (ix->n_docs && total_q) ? &hp : nullptr, out_ids_dev,
+                              out_counts_dev, ix->stream));
     return DESSERT_OK;
 }
 

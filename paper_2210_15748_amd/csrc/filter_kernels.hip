@@ -375,6 +375,7 @@ struct DistKeys {  // key = (value + bias) above the centroid id: closest first,
     const int32_t* row;
     uint32_t id_bits;
     static constexpr int VEC = 1;
+    static constexpr bool SEGMENTS = false;
     using key_t = uint64_t;
     __device__ uint64_t operator()(uint64_t i) const { return make_key(row[i] + FILTER_BIAS, (uint32_t)i, id_bits); }
     __device__ void load(uint64_t i, uint64_t n, uint64_t (&out)[1]) const { out[0] = i < n ? (*this)(i) : 0; }
@@ -410,8 +411,10 @@ __global__ void filter_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
 // Only if the queue overflows (more than FILTER_QUEUE distinct documents of one slab hit) are the counters
 // scanned instead.
 // first-hit queue entries per workgroup (positions within the slab: QT = u16, or u32 for slabs over 65536 documents).
-// 3840: with a slab of 32768 one-byte counters the workgroup then needs just under 40 KB of LDS and four fit a CU.
-constexpr uint32_t FILTER_QUEUE = 3840;
+// 3712: with a slab of 32768 one-byte counters and the 128-bin histogram the workgroup then needs just under 40 KB
+// of LDS and four fit a CU.
+constexpr uint32_t FILTER_QUEUE = 3712;
+constexpr uint32_t FILTER_HSMALL = 128;  // bins of the per-workgroup histogram of counts
 
 template <int W, int T, typename QT, typename KT>
 __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restrict__ probe_ids, uint32_t probe,
@@ -422,7 +425,7 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
                                                             uint32_t slab_docs, uint32_t id_bits,
                                                             KT* __restrict__ lists, uint64_t list_stride,
                                                             uint32_t* __restrict__ cursor, uint32_t* __restrict__ hist,
-                                                            uint32_t hist_bins) {
+                                                            uint32_t hist_bins, uint32_t* __restrict__ segs) {
     extern __shared__ uint32_t cnt[];
     __shared__ QT queue[FILTER_QUEUE];
     __shared__ uint32_t wsum[16];
@@ -455,28 +458,41 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
             }
         }
     };
-    // histogram of the emitted keys' score fields (bin = count + 1) for the selection that follows.  Nearly every
+    // Histogram of the emitted keys' score fields (bin = count + 1) for the selection that follows.  Nearly every
     // document is hit once: a thread counts those in a register; the workgroup gathers its counts in a small LDS
-    // histogram and adds the occupied bins to the query set's histogram (a handful of global atomics per workgroup;
-    // one per key made this kernel four times slower: they all go to the same few addresses).
-    constexpr uint32_t HSMALL = 64;
-    __shared__ uint32_t hsmall[HSMALL];
-    uint32_t* my_hist = hist_bins ? hist + (size_t)b * hist_bins : nullptr;
+    // histogram.  segs != nullptr: this workgroup's histogram and the run of the list it writes are stored as they
+    // are, hist[b][slab][bins] and segs[b][slab][2] (at most FILTER_HSMALL bins).  Else the occupied bins are added to
+    // the query set's histogram hist[b][bins] (a handful of global atomics per workgroup; one per key made this kernel
+    // four times slower: they all go to the same few addresses).
+    __shared__ uint32_t hsmall[FILTER_HSMALL];
+    const bool tallying = hist_bins != 0;
+    uint32_t* my_hist = !tallying ? nullptr
+                        : segs    ? hist + ((size_t)b * gridDim.x + blockIdx.x) * hist_bins
+                                  : hist + (size_t)b * hist_bins;
     uint32_t ones = 0;
-    if (tid < HSMALL) hsmall[tid] = 0;  // ordered before the first tally by the barriers of the counting phase
+    if (tid < FILTER_HSMALL) hsmall[tid] = 0;  // ordered before the first tally by the barriers of the counting phase
     auto tally = [&](uint32_t c) {
-        if (!my_hist) return;
+        if (!tallying) return;
         if (c == 1) ++ones;
-        else if (c + 1 < HSMALL) atomicAdd(&hsmall[c + 1], 1u);
-        else atomicAdd(&my_hist[c + 1], 1u);
+        else if (c + 1 < FILTER_HSMALL) atomicAdd(&hsmall[c + 1], 1u);
+        else atomicAdd(&my_hist[c + 1], 1u);  // not with segs: the host gives rows only to histograms that fit hsmall
     };
-    auto flush_tally = [&]() {  // called by every thread of the workgroup
-        if (!my_hist) return;
+    auto flush_tally = [&](uint32_t list_start, uint32_t list_len) {  // called by every thread of the workgroup
+        if (!tallying) return;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) ones += __shfl_down(ones, o, 64);
         if (lane == 0 && ones) atomicAdd(&hsmall[2], ones);
         __syncthreads();
-        if (tid < HSMALL && tid < hist_bins && hsmall[tid]) atomicAdd(&my_hist[tid], hsmall[tid]);
+        if (segs) {
+            if (tid < hist_bins) my_hist[tid] = hsmall[tid];
+            if (tid == 0) {
+                uint32_t* sg = segs + ((size_t)b * gridDim.x + blockIdx.x) * 2;
+                sg[0] = list_start;
+                sg[1] = list_len;
+            }
+        } else if (tid < FILTER_HSMALL && tid < hist_bins && hsmall[tid]) {
+            atomicAdd(&my_hist[tid], hsmall[tid]);
+        }
     };
     uint32_t lo_l, n_l;
     bounds(wave, lo_l, n_l);
@@ -547,7 +563,7 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
             dst[i] = (KT)make_key((int32_t)c, doc0 + local, id_bits);
             tally(c);
         }
-        flush_tally();
+        flush_tally(base_sh, hits);
         return;
     }
     // queue overflow: scan the counters
@@ -589,7 +605,7 @@ __global__ __launch_bounds__(T) void filter_count_kernel(const uint32_t* __restr
             }
         }
     }
-    flush_tally();
+    flush_tally(base_sh, hits);  // as many keys as first hits
 }
 
 // ---------------------------------------------------------------------------
@@ -806,17 +822,33 @@ static hipError_t launch_filter_count_t(dim3 grid, size_t lds, hipStream_t strea
                                         const uint32_t* q_off, uint32_t q_uniform, const uint32_t* sub_off, FilterSubPlan sp,
                                         const uint32_t* bucket_docs, uint64_t n_docs, uint32_t slab_docs, uint32_t id_bits,
                                         uint64_t* lists, uint64_t list_stride, uint32_t* cursor, uint32_t* hist,
-                                        uint32_t hist_bins) {
+                                        uint32_t hist_bins, uint32_t* segs) {
     static hipError_t attr = hipFuncSetAttribute((const void*)filter_count_kernel<W, T, QT, KT>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, FILTER_SLAB_BYTES);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((filter_count_kernel<W, T, QT, KT>), grid, dim3(T), lds, stream, probe_ids, probe, q_off, q_uniform, sub_off,
-                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, (KT*)lists, list_stride, cursor, hist, hist_bins);
+                       sp.S, sp.sub_shift, bucket_docs, n_docs, slab_docs, id_bits, (KT*)lists, list_stride, cursor, hist, hist_bins, segs);
     return hipGetLastError();
 }
 
-uint32_t filter_hist_bins(uint32_t max_pairs, uint64_t n_docs) {
-    return n_docs ? leading_score_bins(max_pairs, n_docs - 1) : 0;
+FilterHistPlan filter_hist_plan(uint32_t n_queries, uint32_t max_pairs, uint64_t n_docs, FilterSubPlan sp) {
+    FilterHistPlan hp{};
+    hp.counter_bytes = max_pairs <= 255 ? 1 : max_pairs <= 65535 ? 2 : 4;  // a count is at most the number of probed buckets
+    // A slab is one sub-bucket range of documents when its counters fit (32768 documents: 32 KB of LDS with
+    // one-byte counters; four workgroups of 512 threads per CU overlap their phases), else as many documents as fit.
+    uint64_t slab_docs = 1ull << sp.sub_shift;
+    if (slab_docs * hp.counter_bytes > FILTER_SLAB_BYTES) slab_docs = FILTER_SLAB_BYTES / hp.counter_bytes;
+    if (slab_docs > n_docs) slab_docs = (n_docs + 3) & ~3ull;
+    hp.slab_docs = (uint32_t)slab_docs;
+    const uint64_t slabs = slab_docs ? (n_docs + slab_docs - 1) / slab_docs : 0;
+    hp.slabs = slabs > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)slabs;
+    hp.bins = n_docs ? leading_score_bins(max_pairs, n_docs - 1) : 0;
+    hp.rows = hp.bins != 0 && hp.bins <= FILTER_HSMALL && hp.slabs <= 1024;  // one thread per slab in the selection
+    hp.hist_off = ((size_t)n_queries + 63) / 64 * 64;
+    const size_t hist_words = hp.rows ? (size_t)n_queries * hp.slabs * hp.bins : (size_t)n_queries * hp.bins;
+    hp.seg_off = hp.hist_off + hist_words;
+    hp.words = hp.seg_off + (hp.rows ? (size_t)n_queries * hp.slabs * 2 : 0);
+    return hp;
 }
 
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
@@ -825,26 +857,25 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
                                uint64_t list_stride, uint32_t* cursor, hipStream_t stream) {
     if (n_queries == 0) return hipSuccess;
     if (n_queries > 65535 || n_docs > 0xFFFFFFFEull) return hipErrorInvalidValue;
-    const uint32_t hist_bins = filter_hist_bins(max_pairs, n_docs);
-    uint32_t* hist = hist_bins ? cursor + filter_hist_offset(n_queries) : nullptr;
-    const uint64_t zero_words = filter_cursor_words(n_queries, max_pairs, n_docs);
+    const FilterHistPlan hp = filter_hist_plan(n_queries, max_pairs, n_docs, sp);
+    const uint32_t hist_bins = hp.bins;
+    uint32_t* hist = hist_bins ? cursor + hp.hist_off : nullptr;
+    uint32_t* segs = hp.rows ? cursor + hp.seg_off : nullptr;
+    // the list lengths start from zero, and so does a histogram that is added up with atomics (rows are stored)
+    const uint64_t zero_words = hp.rows ? n_queries : hp.seg_off;
     uint64_t zb = (zero_words + 1023) / 1024;
     hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, (int32_t*)cursor,
                        zero_words);
     if (n_docs == 0 || total_q == 0) return hipGetLastError();
-    const uint32_t W = max_pairs <= 255 ? 1 : max_pairs <= 65535 ? 2 : 4;  // a count is at most the number of probed buckets
-    // A slab is one sub-bucket range of documents when its counters fit (32768 documents: 32 KB of LDS with
-    // one-byte counters; four workgroups of 512 threads per CU overlap their phases), else as many documents as fit.
-    uint64_t slab_docs = 1ull << sp.sub_shift;
-    if (slab_docs * W > FILTER_SLAB_BYTES) slab_docs = FILTER_SLAB_BYTES / W;
-    if (slab_docs > n_docs) slab_docs = (n_docs + 3) & ~3ull;
-    const uint64_t slabs = (n_docs + slab_docs - 1) / slab_docs;
+    const uint32_t W = hp.counter_bytes;
+    const uint64_t slab_docs = hp.slab_docs;
+    const uint64_t slabs = hp.slabs;
     if (slabs > 0x7fffffffull) return hipErrorInvalidValue;
     const size_t lds = (size_t)slab_docs * W;
     const uint32_t id_bits = bits_for(n_docs - 1);
     const dim3 grid((unsigned)slabs, n_queries);
 #define DESSERT_COUNT_ARGS grid, lds, stream, probe_ids, probe, q_off, q_uniform, sub_off, sp, bucket_docs, n_docs, \
-                           (uint32_t)slab_docs, id_bits, lists, list_stride, cursor, hist, hist_bins
+                           (uint32_t)slab_docs, id_bits, lists, list_stride, cursor, hist, hist_bins, segs
 #define DESSERT_COUNT_CASE(W_, T_)                                                                              \
     do {                                                                                                        \
         if (slab_docs <= 65536)                                                                                 \

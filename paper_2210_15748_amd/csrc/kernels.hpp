@@ -106,13 +106,20 @@ hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K
                                hipStream_t stream);
 // Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
 // max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.
-// cursor: [filter_cursor_words(B, max_pairs, n_docs)] u32: the B list lengths, then (from word filter_hist_offset(B) on,
-// when filter_hist_bins() != 0) per query set the histogram of its keys' score fields, which launch_topk_lists takes as hist0.
-uint32_t filter_hist_bins(uint32_t max_pairs, uint64_t n_docs);
-inline size_t filter_hist_offset(uint32_t n_queries) { return ((size_t)n_queries + 63) / 64 * 64; }
-inline size_t filter_cursor_words(uint32_t n_queries, uint32_t max_pairs, uint64_t n_docs) {
-    return filter_hist_offset(n_queries) + (size_t)n_queries * filter_hist_bins(max_pairs, n_docs);
-}
+// Layout of the counting kernel's small outputs, one u32 array ("cursor"): the B list lengths, then what lets the
+// selection that follows skip passes over the lists (launch_topk_lists takes the same plan):
+//   rows: per (query set, slab of documents) the histogram of the slab's keys by score field [B][slabs][bins] and the
+//         slab's run within the list [B][slabs][2] (plain stores by the workgroup that owns the slab); or
+//   one histogram per query set [B][bins], added up with atomics (more than 128 bins or very many slabs); or nothing
+//   (score field wider than a digit of the selection).
+struct FilterHistPlan {
+    uint32_t bins;    // 0: no histogram
+    uint32_t slabs;   // document slabs of the counting kernel (its grid.x)
+    uint32_t slab_docs, counter_bytes;
+    bool rows;
+    size_t hist_off, seg_off, words;  // in u32 words from the start of the array
+};
+FilterHistPlan filter_hist_plan(uint32_t n_queries, uint32_t max_pairs, uint64_t n_docs, FilterSubPlan sp);
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
                                FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
@@ -139,10 +146,11 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 // id_bits = bits of max_id; one workgroup per list.  When the score and id fields fit 32 bits together the lists hold
 // u32 keys (list b starts list_stride u32 entries after list b-1); launch_filter_count writes them the same way.
 // lists must be 16-byte aligned and list_stride a multiple of 4 (the lists are read 16 bytes at a time).
-// hist0: nullptr, or per list the histogram of its keys' score fields ([n_queries][bins], bin = score + 1, bins as
-// filter_hist_bins gives them): the selection then skips its first pass over the list.
+// hp: nullptr, or the plan by which launch_filter_count laid out its histograms behind the counts (counts = the
+// start of that array): the selection then skips its first pass over a list and, with rows, decides the id digits
+// inside one slab's run.
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
-                             uint32_t k, uint32_t max_score, uint64_t max_id, const uint32_t* hist0, uint32_t* out_ids,
+                             uint32_t k, uint32_t max_score, uint64_t max_id, const FilterHistPlan* hp, uint32_t* out_ids,
                              int32_t* out_scores, hipStream_t stream);
 
 }  // namespace dessert

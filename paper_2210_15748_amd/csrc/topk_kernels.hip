@@ -41,7 +41,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, K
     const uint64_t lo = (uint64_t)s * per < count ? (uint64_t)s * per : count;
     const uint64_t hi = lo + per < count ? lo + per : count;
     ScoreKeysT<KT> keys{a.scores + base + lo, a.cand_ids ? a.cand_ids + base + lo : nullptr, lo, plan.id_bits};
-    block_select<TOPK_THREADS, ScoreKeysT<KT>, 8>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
+    block_select<TOPK_THREADS, ScoreKeysT<KT>, 8, true>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
     if (slices == 1) {
         for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
             write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
@@ -70,17 +70,22 @@ __global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT*
                                                                        const uint32_t* __restrict__ counts, uint32_t k,
                                                                        KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
                                                                        int32_t* __restrict__ out_scores,
-                                                                       const uint32_t* __restrict__ hist0, uint32_t hist_bins) {
+                                                                       const uint32_t* __restrict__ hist0, uint32_t hist_bins,
+                                                                       const uint32_t* __restrict__ segs, uint32_t slabs) {
     extern __shared__ uint64_t sorted[];
     __shared__ SelectShared sh;
     const uint32_t b = blockIdx.x;
-    const uint32_t* first_hist = hist0 ? hist0 + (size_t)b * hist_bins : nullptr;
+    // segs != nullptr: hist0 holds rows per slab (see SlabDirectory); else one histogram per list, or nothing
+    const uint32_t* first_hist = (hist0 && !segs) ? hist0 + (size_t)b * hist_bins : nullptr;
+    SlabDirectory directory{nullptr, nullptr, 0, 0};
+    if (segs) directory = SlabDirectory{hist0 + (size_t)b * slabs * hist_bins, segs + (size_t)b * slabs * 2, slabs, hist_bins};
+    const SlabDirectory* dir = segs ? &directory : nullptr;
     if constexpr (sizeof(KT) == 8) {
         StoredKeysPairs keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeysPairs, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist);
+        block_select<TOPK_LIST_THREADS, StoredKeysPairs, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
     } else {
         StoredKeys32 keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist);
+        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
     }
     for (uint32_t i = threadIdx.x; i < k; i += TOPK_LIST_THREADS)
         write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
@@ -101,7 +106,7 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
-                             uint32_t k, uint32_t max_score, uint64_t max_id, const uint32_t* hist0, uint32_t* out_ids,
+                             uint32_t k, uint32_t max_score, uint64_t max_id, const FilterHistPlan* hp, uint32_t* out_ids,
                              int32_t* out_scores, hipStream_t stream) {
     if (n_queries == 0 || k == 0) return hipSuccess;
     if (k > TOPK_KMAX) return hipErrorInvalidValue;
@@ -115,14 +120,18 @@ hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const 
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
-    const uint32_t hist_bins = leading_score_bins(max_score, max_id);
-    if (hist0 && !hist_bins) return hipErrorInvalidValue;
+    const uint32_t hist_bins = (hp && hp->bins) ? hp->bins : 0;
+    if (hist_bins && hist_bins != leading_score_bins(max_score, max_id)) return hipErrorInvalidValue;
+    if (hist_bins && hp->rows && hp->slabs > TOPK_LIST_THREADS) return hipErrorInvalidValue;
+    const uint32_t* hist0 = hist_bins ? counts + hp->hist_off : nullptr;
+    const uint32_t* segs = (hist_bins && hp->rows) ? counts + hp->seg_off : nullptr;
+    const uint32_t slabs = hist_bins ? hp->slabs : 0;
     if (keys_fit_32(max_score, max_id))
         hipLaunchKernelGGL(topk_lists_kernel<uint32_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream,
-                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins);
+                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins, segs, slabs);
     else
         hipLaunchKernelGGL(topk_lists_kernel<uint64_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists,
-                           list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins);
+                           list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins, segs, slabs);
     return hipGetLastError();
 }
 

@@ -91,6 +91,16 @@ __device__ inline void write_result(uint64_t key, uint32_t id_bits, uint32_t* id
     }
 }
 
+// Optional description of a stored key list whose producer wrote its keys slab by slab: slab s holds the keys of an
+// id range below that of slab s+1 (so, for equal scores, all its keys rank before those of later slabs) as one
+// run of the list.  With the leading digit = the score field, block_select then finds the k-th key inside one slab's
+// run instead of scanning the whole list once per id digit.
+struct SlabDirectory {
+    const uint32_t* rows;      // [slabs][bins]: per slab the histogram of its keys' leading digit (bin = score + 1)
+    const uint32_t* segments;  // [slabs][2]: start and length of the slab's run within the list
+    uint32_t slabs, bins;      // bins = leading_score_bins(); at most T slabs
+};
+
 struct SelectShared {
     uint32_t hist[TOPK_HIST];
     uint32_t wave_sum[16];
@@ -98,6 +108,7 @@ struct SelectShared {
     uint32_t need;
     uint32_t count;
     uint32_t eq_taken;
+    uint32_t sub_slab;
 };
 
 constexpr int ilog2_floor(int x) { return x <= 1 ? 0 : 1 + ilog2_floor(x / 2); }
@@ -114,10 +125,24 @@ __device__ void bitonic_sort_regs(uint64_t* sorted) {
     constexpr int WAVES = T / 64, LOG_WAVES = ilog2_floor(WAVES);
     constexpr uint32_t KPAD = (uint32_t)R * T, COLS = 64u * R;
     const uint32_t tid = threadIdx.x, lane = tid & 63;
-    auto order = [](KS& x, KS& y, bool desc) {  // desc: larger first
-        const KS lo = x < y ? x : y, hi = x < y ? y : x;
-        x = desc ? hi : lo;
-        y = desc ? lo : hi;
+    // 32-bit keys: the median of (x, y, 0) is their minimum and the median of (x, y, 2^32-1) their maximum, so one
+    // v_med3_u32 with a per-lane third operand picks the side a lane keeps
+    auto med3 = [](uint32_t x, uint32_t y, uint32_t z) {
+        uint32_t r;
+        asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+        return r;
+    };
+    auto order = [&](KS& x, KS& y, bool desc) {  // desc: larger first
+        if constexpr (sizeof(KS) == 4) {
+            const uint32_t top = desc ? 0xFFFFFFFFu : 0u;
+            const uint32_t nx = med3(x, y, top), ny = med3(x, y, ~top);
+            x = nx;
+            y = ny;
+        } else {
+            const KS lo = x < y ? x : y, hi = x < y ? y : x;
+            x = desc ? hi : lo;
+            y = desc ? lo : hi;
+        }
     };
     KS key[R];
 #pragma unroll
@@ -154,11 +179,14 @@ __device__ void bitonic_sort_regs(uint64_t* sorted) {
             const bool keep_max = ((lane & lx) == 0) == (((R * tid) & size) == 0);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                KS o;
-                if constexpr (sizeof(KS) == 8) o = __shfl_xor((unsigned long long)key[r], (int)lx, 64);
-                else o = __shfl_xor((unsigned int)key[r], (int)lx, 64);
-                const KS lo = key[r] < o ? key[r] : o, hi = key[r] < o ? o : key[r];
-                key[r] = keep_max ? hi : lo;
+                if constexpr (sizeof(KS) == 8) {
+                    const KS o = __shfl_xor((unsigned long long)key[r], (int)lx, 64);
+                    const KS lo = key[r] < o ? key[r] : o, hi = key[r] < o ? o : key[r];
+                    key[r] = keep_max ? hi : lo;
+                } else {
+                    const uint32_t o = __shfl_xor((unsigned int)key[r], (int)lx, 64);
+                    key[r] = med3(key[r], o, keep_max ? 0xFFFFFFFFu : 0u);
+                }
             }
         }
 #pragma unroll
@@ -243,14 +271,16 @@ __device__ void bitonic_sort_lds(uint64_t* a, uint32_t npad) {
 
 // Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
 // T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
-// U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
+// CACHE: see below.  U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
 // lists: 16 bytes), so a pass over n keys is n / (T * U * VEC) round trips - a workgroup scanning one list is bound
 // by those round trips, not by bytes.
 // sorted: kpad = next power of two >= max(k, 2) entries of LDS.
-// first_hist: optional, leading_score_bins() counters (see there).
-template <int T, typename Keys, int U = 4>
+// first_hist: optional, leading_score_bins() counters (see there).  dir: optional, see SlabDirectory (key sources
+// with SEGMENTS only); it replaces first_hist.
+template <int T, typename Keys, int U = 4, bool CACHE = false>
 __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
-                             SelectShared& sh, const KeyPlan& plan, const uint32_t* first_hist = nullptr) {
+                             SelectShared& sh, const KeyPlan& plan, const uint32_t* first_hist = nullptr,
+                             const SlabDirectory* dir = nullptr) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
     constexpr int WAVES = T / 64;
@@ -264,22 +294,27 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         sh.eq_taken = 0;
     }
     __syncthreads();
-    // A list of at most T*U*V keys is loaded once and kept in registers for all passes.
-    const bool cached = n <= (uint64_t)T * U * V;
-    K cache[U][V];
-    if (cached) {
+    // CACHE: a list of at most T*U*V keys is loaded once and kept in registers for all passes (U*V more live
+    // registers: for kernels whose lists are usually that short).
+    const bool cached = CACHE && n <= (uint64_t)T * U * V;
+    K cache[CACHE ? U : 1][CACHE ? V : 1];
+    if constexpr (CACHE) {
+        if (cached) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) keys.load((uint64_t)tid * V + (uint64_t)u * T * V, n, cache[u]);
+            for (int u = 0; u < U; ++u) keys.load((uint64_t)tid * V + (uint64_t)u * T * V, n, cache[u]);
+        }
     }
     // f(key) for every key of the list.  Only a thread's last, partial trip checks indices key by key.
     auto scan = [&](auto&& f) {
-        if (cached) {
+        if constexpr (CACHE) {
+            if (cached) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int v = 0; v < V; ++v)
-                    if ((uint64_t)tid * V + (uint64_t)u * T * V + v < n) f(cache[u][v]);
-            return;
+                    for (int v = 0; v < V; ++v)
+                        if ((uint64_t)tid * V + (uint64_t)u * T * V + v < n) f(cache[u][v]);
+                return;
+            }
         }
         for (uint64_t i = (uint64_t)tid * V; i < n; i += (uint64_t)U * T * V) {  // U loads in flight per thread
             K key[U][V];
@@ -299,6 +334,21 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             }
         }
     };
+    // the digits after the first may be decided on one slab's run of the list (see SlabDirectory)
+    uint64_t sub_start = 0, n_sub = 0;
+    bool use_sub = false;
+    auto scan_sub = [&](auto&& f) {
+        if constexpr (Keys::SEGMENTS) {
+            for (uint64_t i = tid; i < n_sub; i += 4 * T) {
+                K key[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) key[u] = i + (uint64_t)u * T < n_sub ? (K)keys(sub_start + i + (uint64_t)u * T) : K(0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i + (uint64_t)u * T < n_sub) f(key[u]);
+            }
+        }
+    };
     // dst[sh.count++] = key for every key of the list with take(key).  Per trip a thread marks which of its keys go
     // out, the wave adds the counts up (prefix sum over lanes) and takes its slots with one atomic: a few round trips
     // per pass instead of one per key.  Every lane of the workgroup makes every trip.
@@ -310,12 +360,14 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             K key[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (cached) {
+                if constexpr (CACHE) {
+                    if (cached) {
 #pragma unroll
-                    for (int v = 0; v < V; ++v) key[u][v] = cache[u][v];
-                } else {
-                    keys.load(i + (uint64_t)u * T * V, n, key[u]);
+                        for (int v = 0; v < V; ++v) key[u][v] = cache[u][v];
+                        continue;
+                    }
                 }
+                keys.load(i + (uint64_t)u * T * V, n, key[u]);
             }
             uint32_t flags = 0;
 #pragma unroll
@@ -350,8 +402,19 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             const uint32_t shift = plan.shift[d], width = plan.width[d];
             const uint32_t nbins = 1u << width, dmask = nbins - 1;
             // first_hist: the leading digit's histogram over all n keys, counted by whoever wrote the list
-            const bool given = d == 0 && first_hist != nullptr;
-            for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = given ? first_hist[i] : 0;
+            const bool by_dir = Keys::SEGMENTS && dir != nullptr && dir->bins == nbins && dir->slabs <= (uint32_t)T;
+            const bool given = d == 0 && (first_hist != nullptr || by_dir);
+            if (d == 0 && by_dir) {  // the list's histogram is the sum of its slabs' rows (all loads in flight together)
+                for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = 0;
+                __syncthreads();
+                const uint32_t cells = dir->slabs * nbins;
+                for (uint32_t i = tid; i < cells; i += T) {
+                    const uint32_t c = dir->rows[i];
+                    if (c) atomicAdd(&sh.hist[i & dmask], c);
+                }
+            } else {
+                for (uint32_t i = tid; i < nbins; i += T) sh.hist[i] = given ? first_hist[i] : 0;
+            }
             __syncthreads();
             const uint64_t prefix = sh.prefix;
             const uint32_t need = sh.need;
@@ -376,6 +439,10 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     }
                 });
                 if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
+            } else if (use_sub) {
+                scan_sub([&](K key) {
+                    if ((key & hi_mask) == hi_value) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & dmask], 1u);
+                });
             } else {
                 scan([&](K key) {
                     if ((key & hi_mask) == hi_value) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & dmask], 1u);
@@ -433,6 +500,33 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     __syncthreads();
                     return;
                 }
+                if (by_dir) {
+                    // The keys of the threshold bin rank slab by slab: thread s takes slab s's count of them, an
+                    // inclusive prefix sum over the slabs finds the slab that holds the need-th, and the remaining
+                    // digits are decided among that slab's keys alone.
+                    const uint32_t need0 = sh.need;
+                    const uint32_t mine = tid < dir->slabs ? dir->rows[(size_t)tid * nbins + bin0] : 0;
+                    uint32_t incl = mine;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const uint32_t o = __shfl_up(incl, off, 64);
+                        if ((int)lane >= off) incl += o;
+                    }
+                    if (lane == 63) sh.wave_sum[wave] = incl;
+                    __syncthreads();
+                    uint32_t before = 0;
+                    for (uint32_t w2 = 0; w2 < wave; ++w2) before += sh.wave_sum[w2];
+                    incl += before;
+                    __syncthreads();  // wave_sum is reused by the digit loop
+                    if (incl - mine < need0 && need0 <= incl) {  // exactly one thread
+                        sh.sub_slab = tid;
+                        sh.need = need0 - (incl - mine);
+                    }
+                    __syncthreads();
+                    sub_start = dir->segments[2 * sh.sub_slab];
+                    n_sub = dir->segments[2 * sh.sub_slab + 1];
+                    use_sub = true;
+                }
             }
         }
         const K kth = (K)sh.prefix;        // the k-th largest key
@@ -463,6 +557,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
 template <typename KT>  // uint64_t, or uint32_t when keys_fit_32
 struct ScoreKeysT {  // keys computed from a score array (+ optional candidate ids)
     static constexpr int VEC = 1;
+    static constexpr bool SEGMENTS = false;
     using key_t = KT;
     const int32_t* scores;
     const uint32_t* ids;  // nullptr: id = first_id + i
@@ -478,6 +573,7 @@ using ScoreKeys = ScoreKeysT<uint64_t>;
 
 struct StoredKeys {  // 64-bit keys at any 8-byte aligned address
     static constexpr int VEC = 1;
+    static constexpr bool SEGMENTS = false;
     using key_t = uint64_t;
     const uint64_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
@@ -488,6 +584,7 @@ struct StoredKeys {  // 64-bit keys at any 8-byte aligned address
 // that a vector load which begins below n stays inside the list's allocation.
 struct StoredKeysPairs {
     static constexpr int VEC = 2;
+    static constexpr bool SEGMENTS = true;
     using key_t = uint64_t;
     const uint64_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
@@ -503,6 +600,7 @@ struct StoredKeysPairs {
 
 struct StoredKeys32 {  // keys of at most 32 bits (score and id fields together), stored as u32
     static constexpr int VEC = 4;
+    static constexpr bool SEGMENTS = true;
     using key_t = uint32_t;
     const uint32_t* keys;
     __device__ uint64_t operator()(uint64_t i) const { return keys[i]; }
