@@ -66,7 +66,10 @@ def test_filter_build_assignments_and_buckets(d, K, n_docs, dup, max_len):
     (37, 16384, [1800, 5], 1500, 12),        # counts up to 66600: 32-bit counters
     (2, 1000, [32, 9], 300_000, 3),          # ten document slabs of 8-bit counters, first-hit queues overflow
     (3, 777, [100, 30], 150_000, 3),         # document slabs of 16-bit counters
-    (37, 2000, [1800, 5], 150_000, 3)])      # 32-bit counters over several slabs; count and id fields pass 32 bits: 64-bit list keys
+    (37, 2000, [1800, 5], 150_000, 3),       # 32-bit counters over several slabs; count and id fields pass 32 bits: 64-bit list keys
+    (1, 4096, [32, 32], 200_000, 3),         # seven slabs, one probe: the k-th key is found inside one slab's run of the list
+    (1, 50, [32], 200_000, 3),               # same lists, small k: few keys above the threshold count
+    (3, 5000, [20, 32, 7], 100_000, 3)])     # counts up to 96: the widest per-slab histograms (128 bins)
 def test_filter_query_matches_oracle(probe, filter_k, q_lens, n_docs, max_len):
     say(f"filter query probe={probe} filter_k={filter_k} q_lens={q_lens} N={n_docs}")
     rng = np.random.default_rng(100 + probe)
