@@ -104,8 +104,6 @@ hipError_t launch_filter_buckets(const uint32_t* assign, const uint64_t* doc_off
                                  uint32_t* bucket_off /*[K+1]*/, uint32_t* bucket_docs, hipStream_t stream);
 hipError_t launch_filter_probe(const int32_t* dist, uint64_t total_q, uint32_t K, uint32_t probe, uint32_t* probe_ids,
                                hipStream_t stream);
-// Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
-// max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.
 // Layout of the counting kernel's small outputs, one u32 array ("cursor"): the B list lengths, then what lets the
 // selection that follows skip passes over the lists (launch_topk_lists takes the same plan):
 //   rows: per (query set, slab of documents) the histogram of the slab's keys by score field [B][slabs][bins] and the
@@ -120,6 +118,9 @@ struct FilterHistPlan {
     size_t hist_off, seg_off, words;  // in u32 words from the start of the array
 };
 FilterHistPlan filter_hist_plan(uint32_t n_queries, uint32_t max_pairs, uint64_t n_docs, FilterSubPlan sp);
+// Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
+// max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.  cursor: filter_hist_plan().words
+// u32 words (see above).
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
                                FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
