@@ -119,7 +119,7 @@ constexpr int ilog2_floor(int x) { return x <= 1 ? 0 : 1 + ilog2_floor(x / 2); }
 // LDS, all strides >= 64*R of a merge in one trip: the T/64 elements that differ only in the wave bits form a
 // column which one thread loads, orders over all those strides, and stores.  A sort of 4096 keys by 1024 threads
 // makes 4 trips through LDS with a barrier pair each (sizes 512 .. 4096) instead of one per stride.
-// KS = uint32_t when every key is below 2^32: half the shuffles, and the exchanges are v_min / v_max.
+// KS = uint32_t when every key is below 2^32: half the shuffles, and an exchange is one or two v_med3_u32.
 template <int T, int R, typename KS>
 __device__ void bitonic_sort_regs(uint64_t* sorted) {
     constexpr int WAVES = T / 64, LOG_WAVES = ilog2_floor(WAVES);
