@@ -271,9 +271,8 @@ __device__ void bitonic_sort_lds(uint64_t* a, uint32_t npad) {
 
 // Select the k largest of keys(0..n-1) into sorted[0..kpad) (descending, zero padded).
 // T = workgroup size (multiple of 64, at most 1024); every thread of the workgroup calls this.
-// CACHE: see below.  U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
-// lists: 16 bytes), so a pass over n keys is n / (T * U * VEC) round trips - a workgroup scanning one list is bound
-// by those round trips, not by bytes.
+// U = key loads a thread keeps in flight while it scans the list; a load brings Keys::VEC consecutive keys (stored
+// lists: 16 bytes), so a pass over n keys is n / (T * U * VEC) round trips.  CACHE: see below.
 // sorted: kpad = next power of two >= max(k, 2) entries of LDS.
 // first_hist: optional, leading_score_bins() counters (see there).  dir: optional, see SlabDirectory (key sources
 // with SEGMENTS only); it replaces first_hist.
