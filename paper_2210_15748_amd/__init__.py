@@ -346,7 +346,8 @@ def filter_query(ix: Index, q_vectors: torch.Tensor, q_lengths, filter_probe: in
     return ids, counts
 
 
-def enable_timing(ix: Index, enable: bool = True) -> None:
+def enable_timing(ix: Index, enable=True) -> None:
+    """dessert_enable_timing: False/0 off, True/1 every call, n > 1 every n-th call."""
     _check(lib().dessert_enable_timing(ix.handle, int(enable)))
 
 

@@ -102,8 +102,11 @@ struct dessert_index {
     };
     static constexpr unsigned kTimingSlots = 64;
     bool timing = false;
+    uint32_t timing_period = 1;   // events are recorded on every timing_period-th call
+    uint64_t timing_seen = 0;     // calls since timing was enabled
     TimingSlot slots[kTimingSlots];
     uint64_t timed_calls = 0;
+    bool timed_now() { return timing && (timing_seen++ % timing_period) == 0; }
     TimingSlot& begin_timed() {
         TimingSlot& s = slots[timed_calls % kTimingSlots];
         s.hash = s.score = s.topk = s.any = false;
@@ -151,8 +154,14 @@ dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, ui
 
 // Workspace layout for a search batch (all regions 256-byte aligned).
 struct Workspace {
-    size_t qcodes, q_off, cand_off, scores, partial, total;
+    size_t qcodes, q_off, cand_off, scores, order, partial, total;
 };
+
+// The workspace holds room for the id-range order of the candidate slots unless the batch scores as many pairs as
+// "every document for every query set" (then there are no candidate lists, or lists that cover everything).
+bool order_space(const dessert_index* ix, uint32_t B, uint64_t total_scored) {
+    return total_scored < (uint64_t)B * ix->n_docs;
+}
 
 Workspace carve(const dessert_index* ix, uint32_t B, uint64_t total_q, uint64_t total_scored, uint64_t max_scored, uint32_t k,
                 bool own_scores) {
@@ -162,6 +171,8 @@ Workspace carve(const dessert_index* ix, uint32_t B, uint64_t total_q, uint64_t 
     w.q_off = p;    p += align_up(((size_t)B + 1) * 4, 256);
     w.cand_off = p; p += align_up(((size_t)B + 1) * 8, 256);
     w.scores = p;   if (own_scores) p += align_up((size_t)total_scored * 4, 256);
+    // candidate slots by id range (see order_space)
+    w.order = p;    if (order_space(ix, B, total_scored)) p += align_up((size_t)total_scored * 4, 256);
     w.partial = p;
     uint32_t slices = topk_slices(max_scored, B);
     if (k && slices > 1) p += align_up((size_t)B * slices * k * 8, 256);
@@ -273,8 +284,9 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     uint64_t* d_cand_off = (uint64_t*)(ws + w.cand_off);
     int32_t* scores = own_scores ? (int32_t*)(ws + w.scores) : scores_out;
 
+    const bool timed = ix->timed_now();
     dessert_index::TimingSlot& ts = ix->begin_timed();
-    if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
+    if (timed) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
     // Offset arrays are uploaded only when the lengths differ (equal lengths travel as kernel
     // arguments); they go through a pinned slot so that the uploads never block the host.
     const bool need_q = bt.q_uniform == 0, need_c = cand_ids && bt.cand_uniform == 0;
@@ -308,7 +320,6 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
 
     st = run_hash(ix, q_vectors, bt.total_q, qcodes);
     if (st != DESSERT_OK) return st;
-    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
 
     ScoreArgs sa{};
     sa.codes = ix->codes; sa.offsets = ix->offsets; sa.n_docs = ix->n_docs;
@@ -325,6 +336,16 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
         algo = (score_masklut_supported(ix->cfg.L, ix->cfg.C) && ix->n_vectors) ? DESSERT_SCORE_MASKLUT
                                                                                 : DESSERT_SCORE_BYTECMP;
+    // Query preparation ends here for the timing: the query codes and, for the mask-table kernel with long candidate
+    // lists, each list's slots grouped by document id range.
+    if (algo == DESSERT_SCORE_MASKLUT && !sa.sigma_mean && score_masklut_supported(ix->cfg.L, ix->cfg.C) && cand_ids &&
+        bt.max_scored >= score_order_min() &&
+        bt.max_scored <= 0xFFFFFFFFull && order_space(ix, B, bt.total_scored)) {
+        uint32_t* order = (uint32_t*)(ws + w.order);
+        HIP_TRY(launch_cand_order(cand_ids, sa.cand_off, sa.cand_uniform, B, bt.max_scored, ix->n_docs, order, ix->stream));
+        sa.order = order;
+    }
+    if (timed) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
     if (algo == DESSERT_SCORE_MASKLUT) {
         if (sa.sigma_mean) return fail(DESSERT_EINVAL, "the MEAN score transforms run on the code-compare kernel only");
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
@@ -336,7 +357,7 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     } else {
         return fail(DESSERT_EINVAL, "unknown scoring algorithm %d", algo);
     }
-    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[2], ix->stream)); ts.score = true; }
+    if (timed) { HIP_TRY(hipEventRecord(ts.ev[2], ix->stream)); ts.score = true; }
 
     if (k) {
         TopkArgs ta{};
@@ -344,9 +365,9 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
         ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = sa.remap ? bt.max_q_len * ix->remap_max : bt.max_q_len * ix->cfg.L;
         ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
         HIP_TRY(launch_topk(ta, ix->stream));
-        if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
+        if (timed) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
     }
-    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    if (timed) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
     return DESSERT_OK;
 }
 
@@ -554,8 +575,9 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     DeviceGuard guard(ix->cfg.device);
     if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
     ix->built = false;
+    const bool timed = ix->timed_now();
     dessert_index::TimingSlot& ts = ix->begin_timed();
-    if (ix->timing) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
+    if (timed) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
     // The code layout does not depend on document boundaries, so hashing starts first, the host
     // scans the lengths while the GPU works, and the offsets go up on the library's own stream
     // beside the hash kernel: after whatever the caller's stream held at entry (it may still read
@@ -563,7 +585,7 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     HIP_TRY(hipEventRecord(ix->build_entry, ix->stream));
     dessert_status_t st = run_hash(ix, vectors_dev, n_vectors, codes_dev);
     if (st != DESSERT_OK) return st;
-    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
+    if (timed) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
     // the staging buffer may still feed the previous build's upload (enqueued before this hash launch)
     if (ix->upload_pending) {
         HIP_TRY(hipEventSynchronize(ix->upload_done));
@@ -588,7 +610,7 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     HIP_TRY(hipEventRecord(ix->upload_done, ix->copy_stream));
     HIP_TRY(hipStreamWaitEvent(ix->stream, ix->upload_done, 0));
     ix->upload_pending = true;
-    if (ix->timing) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    if (timed) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
     ix->codes = codes_dev;
     ix->offsets = offsets_dev;
     ix->n_docs = n_docs;
@@ -821,6 +843,8 @@ dessert_status_t dessert_enable_timing(dessert_index_t* ix, int enable) {
         for (auto& slot : ix->slots)
             for (auto& ev : slot.ev) HIP_TRY(hipEventCreate(&ev));
     ix->timing = enable != 0;
+    ix->timing_period = enable > 1 ? (uint32_t)enable : 1;
+    ix->timing_seen = 0;
     ix->timed_calls = 0;
     for (auto& slot : ix->slots) slot.any = false;
     return DESSERT_OK;

@@ -48,6 +48,8 @@ struct ScoreArgs {
     const uint32_t* cand_ids;   // dev or nullptr
     const uint64_t* cand_off;   // dev [B+1] (candidate mode); unused when cand_uniform != 0
     uint64_t cand_uniform;      // != 0: every candidate list has this many ids
+    const uint32_t* order;      // dev [total_cand] or nullptr: per list, its slots grouped by document id range
+                                // (launch_cand_order); the mask-table kernel then takes a list's slots in that order
     uint64_t max_scored;        // largest number of documents scored by one query set
     uint64_t total_scored;      // all output slots (candidate mode: sum of the list lengths)
     uint64_t n_vectors;         // vectors in the index (launch heuristics only)
@@ -62,6 +64,13 @@ __device__ inline uint64_t cand_begin(const ScoreArgs& a, uint32_t b) {
     return a.cand_uniform ? (uint64_t)b * a.cand_uniform : a.cand_off[b];
 }
 hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
+// Candidate lists gathered from all over the code array: order[list start + p] = the slots of a list grouped by
+// range of document id (a counting sort over the leading id bits; the order inside a range is unspecified).
+// Workgroups that take the same run of positions of different lists then read neighbouring parts of the code array
+// at about the same time.  Worth it from score_order_min() candidates per list on.
+uint64_t score_order_min();
+hipError_t launch_cand_order(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
+                             uint64_t max_scored, uint64_t n_docs, uint32_t* order, hipStream_t stream);
 bool score_masklut_supported(uint32_t L, uint32_t C);
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
 

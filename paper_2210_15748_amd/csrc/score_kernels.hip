@@ -237,6 +237,7 @@ constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
 struct LutBlockMeta {
     uint64_t lo[LUT_DOCS];      // first code row of each document of the block
     uint32_t m[LUT_DOCS];       // its length
+    uint32_t slot[LUT_DOCS];    // its slot within the query set's candidate list (= output position)
     uint16_t order[LUT_DOCS];   // documents ordered longest class first
     uint32_t bin[LUT_BINS];     // counting sort by length class
     uint32_t next;              // next unclaimed position in `order`
@@ -350,9 +351,11 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     };
     const bool have_doc = threadIdx.x < ndocs;
     uint64_t my_id = 0;
+    uint32_t my_slot = 0;
     if (have_doc) {
         const uint64_t pos = first + threadIdx.x;
-        my_id = a.cand_ids ? a.cand_ids[sp.base + pos] : pos;
+        my_slot = (uint32_t)(a.order ? a.order[sp.base + pos] : pos);  // a.order: candidate mode only
+        my_id = a.cand_ids ? a.cand_ids[sp.base + my_slot] : pos;
     }
     constexpr int QPT = (32 * L + T - 1) / T;  // table entries per thread and query set
     uint32_t qh[W][QPT];
@@ -391,6 +394,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
         const uint32_t m = (uint32_t)(my_hi - my_lo);  // 0 for an empty slot
         meta.lo[threadIdx.x] = my_lo;
         meta.m[threadIdx.x] = m;
+        meta.slot[threadIdx.x] = a.order ? my_slot : (uint32_t)(first + threadIdx.x);
         uint32_t rounds = (m + G - 1) / G;
         my_class = rounds < LUT_BINS ? LUT_BINS - 1 - rounds : 0;  // class 0 = longest
         atomicAdd(&meta.bin[my_class], 1u);
@@ -623,7 +627,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
                 }
                 if (valid && sub == 0 && b0 + w < a.n_queries && c0 < q_len[w]) {
                     // W > 1 implies every set scores every document: set b0+w starts at (b0+w)*n_docs
-                    int32_t* dst = a.scores + (W == 1 ? sp.base : (uint64_t)(b0 + w) * a.n_docs) + first + doc;
+                    int32_t* dst = a.scores + (W == 1 ? sp.base + meta.slot[doc] : (uint64_t)(b0 + w) * a.n_docs + first + doc);
                     if (W == 1 && m == 0 && meta.lo[doc] == ~0ull) {
                         if (c0 == 0) *dst = -1;  // empty candidate slot
                     } else if (SPLIT) {
@@ -637,6 +641,94 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
             }
         }
     }
+}
+
+// Counting sort of a candidate list's slots by range of document id: one workgroup per list, ranges = the leading
+// bits of the id (about 128 candidates per range when the ids are spread evenly), two passes over the ids.
+constexpr uint32_t ORDER_THREADS = 512, ORDER_MAX_RANGES = 4096;
+__global__ __launch_bounds__(ORDER_THREADS) void cand_order_kernel(const uint32_t* __restrict__ cand_ids,
+                                                                   const uint64_t* __restrict__ cand_off, uint64_t cand_uniform,
+                                                                   uint32_t shift, uint32_t ranges,
+                                                                   uint32_t* __restrict__ order) {
+    __shared__ uint32_t bin[ORDER_MAX_RANGES];
+    __shared__ uint32_t wave_sum[ORDER_THREADS / 64];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint64_t base = cand_uniform ? (uint64_t)b * cand_uniform : cand_off[b];
+    const uint64_t n = cand_uniform ? cand_uniform : cand_off[b + 1] - base;
+    const uint32_t* ids = cand_ids + base;
+    uint32_t* out = order + base;
+    auto range_of = [&](uint32_t id) {  // empty slots (id 0xFFFFFFFF) and anything past the end go to the last range
+        const uint32_t r = shift < 32 ? id >> shift : 0;
+        return r < ranges ? r : ranges - 1;
+    };
+    for (uint32_t i = tid; i < ranges; i += ORDER_THREADS) bin[i] = 0;
+    __syncthreads();
+    // eight loads in flight per thread; a list of up to 4096 ids stays in registers for the second pass
+    constexpr int U = 8;
+    const bool cached = n <= (uint64_t)U * ORDER_THREADS;
+    uint32_t held[U];
+    for (uint64_t i0 = 0; i0 < n; i0 += (uint64_t)U * ORDER_THREADS) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
+            held[u] = i < n ? ids[i] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + tid + (uint64_t)u * ORDER_THREADS < n) atomicAdd(&bin[range_of(held[u])], 1u);
+    }
+    __syncthreads();
+    // exclusive prefix sum of the bins: thread t owns bins [t*per, (t+1)*per)
+    const uint32_t per = (ranges + ORDER_THREADS - 1) / ORDER_THREADS;
+    uint32_t mine = 0;
+    for (uint32_t j = 0; j < per; ++j)
+        if (tid * per + j < ranges) mine += bin[tid * per + j];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off, 64);
+        if ((int)lane >= off) incl += o;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t run = incl - mine;
+    for (uint32_t w2 = 0; w2 < wave; ++w2) run += wave_sum[w2];
+    for (uint32_t j = 0; j < per; ++j)
+        if (tid * per + j < ranges) {
+            const uint32_t c = bin[tid * per + j];
+            bin[tid * per + j] = run;
+            run += c;
+        }
+    __syncthreads();
+    for (uint64_t i0 = 0; i0 < n; i0 += (uint64_t)U * ORDER_THREADS) {
+        if (!cached) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
+                held[u] = i < n ? ids[i] : 0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
+            if (i < n) out[atomicAdd(&bin[range_of(held[u])], 1u)] = (uint32_t)i;
+        }
+    }
+}
+
+uint64_t score_order_min() { return 1024; }
+
+hipError_t launch_cand_order(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
+                             uint64_t max_scored, uint64_t n_docs, uint32_t* order, hipStream_t stream) {
+    if (n_queries == 0 || max_scored == 0) return hipSuccess;
+    if (max_scored > 0xFFFFFFFFull) return hipErrorInvalidValue;  // slots are 32-bit
+    uint32_t id_bits = 1;
+    while (id_bits < 32 && ((n_docs ? n_docs - 1 : 0) >> id_bits)) ++id_bits;
+    uint32_t log_ranges = 0;
+    while ((128ull << log_ranges) < max_scored && (1u << log_ranges) < ORDER_MAX_RANGES && log_ranges < id_bits) ++log_ranges;
+    hipLaunchKernelGGL(cand_order_kernel, dim3(n_queries), dim3(ORDER_THREADS), 0, stream, cand_ids, cand_off, cand_uniform,
+                       id_bits - log_ranges, 1u << log_ranges, order);
+    return hipGetLastError();
 }
 
 __global__ void fill_zero_kernel(int32_t* __restrict__ p, uint64_t n) {
@@ -695,10 +787,11 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
         hipError_t e = launch_fill_zero(a.scores, n, stream);
         if (e != hipSuccess) return e;
     }
-    // exhaustive mode: linear grid with the XCD-aware decode (document blocks rounded up to 8)
+    // exhaustive mode, and candidate lists ordered by id range: linear grid with the XCD-aware decode (document
+    // blocks rounded up to 8), so that the workgroups of one block of positions run back to back for all query sets
     dim3 grid((unsigned)bx, (unsigned)gyz);
     uint32_t gy_linear = 0;
-    if (a.cand_ids == nullptr) {
+    if (a.cand_ids == nullptr || a.order != nullptr) {
         const uint64_t total = (bx + 7) / 8 * 8 * gyz;
         if (total <= 0x7fffffffull) {
             grid = dim3((unsigned)total);

@@ -189,6 +189,55 @@ def test_scores_edge_lengths_and_ragged_queries(algo):
         assert np.array_equal(got[co[b]:co[b + 1]], orc.scores(dc, off, qc[qo[b]:qo[b + 1]], c)), b
 
 
+@pytest.mark.parametrize("L,Cb,eq1", [(32, 7, False), (64, 8, True), (8, 11, False)])
+def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1):
+    """Lists long enough for the mask-table kernel to take them grouped by document id range: uniform ids, ids all
+    from one narrow range (one range gets nearly everything), descending ids, empty slots and repeats, lists of unequal
+    length, one too short for the grouping.  Every score must land in its own slot."""
+    say(f"long candidate lists L={L} C={Cb} eq1={eq1}")
+    rng = np.random.default_rng(L + Cb)
+    d, N = 64, 50_000
+    lens = rng.integers(0, 6, N)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (30, d))
+    X = np.clip(pool[rng.integers(0, 30, V)] + rng.integers(-40, 41, (V, d)), -127, 127).astype(np.int8)
+    q_lens = np.array([5, 33, 2, 9, 4], dtype=np.int64)
+    nq = int(q_lens.sum())
+    Q = np.clip(pool[rng.integers(0, 30, nq)] + rng.integers(-40, 41, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    if eq1:
+        dz.set_score_transform(ix, dz.SCORE_EQ1_Q16)
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    EMPTY = 0xFFFFFFFF
+    with_gaps = rng.integers(0, N, 3000).astype(np.int64)
+    with_gaps[::7] = EMPTY
+    cands = [rng.integers(0, N, 5000).astype(np.int64),                     # uniform, with repeats
+             rng.integers(20_000, 20_040, 2500).astype(np.int64),           # one narrow range
+             np.arange(N - 1, N - 1 - 1500, -1).astype(np.int64),           # descending
+             with_gaps,                                                     # empty slots
+             rng.integers(0, N, 700).astype(np.int64)]                      # shorter than the others
+    co = np.concatenate([[0], np.cumsum([len(c) for c in cands])])
+    flat = torch.from_numpy(np.concatenate(cands).astype(np.uint32).view(np.int32)).to(DEV)
+    got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens, cand_ids=flat, cand_offsets=co).cpu().numpy()
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    for b, c in enumerate(cands):
+        real = c != EMPTY
+        q = qc[qo[b]:qo[b + 1]]
+        want_real = orc.scores_eq1(dc, off, q, Cb, c[real]) if eq1 else orc.scores(dc, off, q, c[real])
+        want = np.full(len(c), -1, dtype=np.int64)
+        want[real] = want_real
+        assert np.array_equal(got[co[b]:co[b + 1]].astype(np.int64), want), b
+    # the same lists through the top-k
+    ids, sc = dz.search(ix, torch.from_numpy(Q).to(DEV), q_lens, 50, cand_ids=flat, cand_offsets=co)
+    for b, c in enumerate(cands):
+        real = c != EMPTY
+        w_ids, w_sc = orc.topk(got[co[b]:co[b + 1]][real], 50, c[real])
+        assert np.array_equal(sc.cpu().numpy()[b], w_sc) and np.array_equal(ids.cpu().numpy()[b], w_ids), b
+
+
 @pytest.mark.parametrize("L,Cb", [(16, 6), (64, 8), (128, 5), (16, 8)])
 def test_scores_masklut_other_shapes(L, Cb):
     say(f"scores masklut L={L} C={Cb}")
