@@ -338,8 +338,9 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
                                                                                 : DESSERT_SCORE_BYTECMP;
     // Query preparation ends here for the timing: the query codes and, for the mask-table kernel with long candidate
     // lists, each list's slots grouped by document id range.
+    // (with fewer than 8 lists the one workgroup per list of the ordering costs more than the scoring gains)
     if (algo == DESSERT_SCORE_MASKLUT && !sa.sigma_mean && score_masklut_supported(ix->cfg.L, ix->cfg.C) && cand_ids &&
-        bt.max_scored >= score_order_min() &&
+        B >= 8 && bt.max_scored >= score_order_min() &&
         bt.max_scored <= 0xFFFFFFFFull && order_space(ix, B, bt.total_scored)) {
         uint32_t* order = (uint32_t*)(ws + w.order);
         HIP_TRY(launch_cand_order(cand_ids, sa.cand_off, sa.cand_uniform, B, bt.max_scored, ix->n_docs, order, ix->stream));

@@ -201,7 +201,7 @@ def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1):
     V = int(lens.sum())
     pool = rng.integers(-127, 128, (30, d))
     X = np.clip(pool[rng.integers(0, 30, V)] + rng.integers(-40, 41, (V, d)), -127, 127).astype(np.int8)
-    q_lens = np.array([5, 33, 2, 9, 4], dtype=np.int64)
+    q_lens = np.array([5, 33, 2, 9, 4, 1, 12, 7], dtype=np.int64)  # eight lists or more are grouped
     nq = int(q_lens.sum())
     Q = np.clip(pool[rng.integers(0, 30, nq)] + rng.integers(-40, 41, (nq, d)), -127, 127).astype(np.int8)
     R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
@@ -216,7 +216,10 @@ def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1):
              rng.integers(20_000, 20_040, 2500).astype(np.int64),           # one narrow range
              np.arange(N - 1, N - 1 - 1500, -1).astype(np.int64),           # descending
              with_gaps,                                                     # empty slots
-             rng.integers(0, N, 700).astype(np.int64)]                      # shorter than the others
+             rng.integers(0, N, 700).astype(np.int64),                      # shorter than the others
+             np.sort(rng.integers(0, N, 1024)).astype(np.int64),            # ascending
+             np.full(1100, 31_337, dtype=np.int64),                         # one document over and over
+             rng.integers(N - 300, N, 2048).astype(np.int64)]               # the top of the id range
     co = np.concatenate([[0], np.cumsum([len(c) for c in cands])])
     flat = torch.from_numpy(np.concatenate(cands).astype(np.uint32).view(np.int32)).to(DEV)
     got = dz.scores(ix, torch.from_numpy(Q).to(DEV), q_lens, cand_ids=flat, cand_offsets=co).cpu().numpy()
