@@ -128,7 +128,11 @@ bool is_f16_mfma(const dessert_config_t& c) {
 }
 bool use_mfma(const dessert_index* ix) { return ix->proj_mfma && (is_i8_mfma(ix->cfg) || is_f16_mfma(ix->cfg)); }
 
-dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, uint8_t* codes) {
+// fused / fused_done: a candidate grouping to carry along in the hashing launch when that is the int8 MFMA kernel;
+// *fused_done tells whether it was.
+dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, uint8_t* codes,
+                          const CandOrderArgs* fused = nullptr, bool* fused_done = nullptr) {
+    if (fused_done) *fused_done = false;
     if (n == 0) return DESSERT_OK;
     int algo = ix->hash_algo;
     bool aligned = ((uintptr_t)X % 16 == 0) && ((uintptr_t)codes % 16 == 0);
@@ -139,8 +143,12 @@ dessert_status_t run_hash(const dessert_index* ix, const void* X, uint64_t n, ui
                                         "Gaussian projections, d in {64,128,256}, L in {16,32,64} (int8 also L = 8, and 16-bit codes with "
                                         "L in {8,16,32})");
         if (!aligned) return fail(DESSERT_EINVAL, "MFMA hashing needs 16-byte aligned vectors and codes");
-        if (ix->cfg.dtype == DESSERT_I8)
-            HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
+        if (ix->cfg.dtype == DESSERT_I8) {
+            const bool fuse = fused && fused->ranges <= hash_mfma_fused_ranges(ix->cfg.d, ix->cfg.L, ix->cfg.C);
+            HIP_TRY(launch_hash_mfma_i8((const int8_t*)X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes,
+                                        fuse ? fused : nullptr, ix->stream));
+            if (fuse && fused_done) *fused_done = true;
+        }
         else
             HIP_TRY(launch_hash_mfma_f16(X, n, ix->cfg.d, ix->cfg.L, ix->cfg.C, ix->proj_mfma, codes, ix->stream));
     } else if (algo == DESSERT_HASH_SCALAR) {
@@ -318,9 +326,6 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
         ms.pending = true;
     }
 
-    st = run_hash(ix, q_vectors, bt.total_q, qcodes);
-    if (st != DESSERT_OK) return st;
-
     ScoreArgs sa{};
     sa.codes = ix->codes; sa.offsets = ix->offsets; sa.n_docs = ix->n_docs;
     sa.L = ix->cfg.L; sa.C = ix->cfg.C; sa.code_bytes = code_width(ix->cfg);
@@ -336,16 +341,22 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
         algo = (score_masklut_supported(ix->cfg.L, ix->cfg.C) && ix->n_vectors) ? DESSERT_SCORE_MASKLUT
                                                                                 : DESSERT_SCORE_BYTECMP;
-    // Query preparation ends here for the timing: the query codes and, for the mask-table kernel with long candidate
-    // lists, each list's slots grouped by document id range.
-    // (with fewer than 8 lists the one workgroup per list of the ordering costs more than the scoring gains)
-    if (algo == DESSERT_SCORE_MASKLUT && !sa.sigma_mean && score_masklut_supported(ix->cfg.L, ix->cfg.C) && cand_ids &&
-        B >= 8 && bt.max_scored >= score_order_min() &&
-        bt.max_scored <= 0xFFFFFFFFull && order_space(ix, B, bt.total_scored)) {
-        uint32_t* order = (uint32_t*)(ws + w.order);
-        HIP_TRY(launch_cand_order(cand_ids, sa.cand_off, sa.cand_uniform, B, bt.max_scored, ix->n_docs, order, ix->stream));
-        sa.order = order;
+    // Query preparation: the query codes and, for the mask-table kernel with long candidate lists, each list's slots
+    // grouped by document id range (with fewer than 8 lists the one workgroup per list of the grouping costs more
+    // than the scoring gains).  The grouping rides in the hashing launch when that is the int8 MFMA kernel.
+    CandOrderArgs oa{};
+    bool grouping = algo == DESSERT_SCORE_MASKLUT && !sa.sigma_mean && score_masklut_supported(ix->cfg.L, ix->cfg.C) &&
+                    cand_ids && B >= 8 && bt.max_scored >= score_order_min() && order_space(ix, B, bt.total_scored);
+    if (grouping) {
+        const uint32_t fused_ranges = hash_mfma_fused_ranges(ix->cfg.d, ix->cfg.L, ix->cfg.C);
+        grouping = cand_order_plan(cand_ids, sa.cand_off, sa.cand_uniform, B, bt.max_scored, ix->n_docs,
+                                   fused_ranges >= 32 ? fused_ranges : 4096, (uint32_t*)(ws + w.order), &oa);
     }
+    bool grouped = false;
+    st = run_hash(ix, q_vectors, bt.total_q, qcodes, grouping ? &oa : nullptr, &grouped);
+    if (st != DESSERT_OK) return st;
+    if (grouping && !grouped) HIP_TRY(launch_cand_order(oa, ix->stream));
+    if (grouping) sa.order = oa.order;
     if (timed) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
     if (algo == DESSERT_SCORE_MASKLUT) {
         if (sa.sigma_mean) return fail(DESSERT_EINVAL, "the MEAN score transforms run on the code-compare kernel only");

@@ -119,14 +119,24 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
 // 8; register r of lane-half g is bit r of table g*(L/2) + mt, so a lane's 16 accumulators of one
 // M-tile make one code.  A code row is LT*4 bytes either way (LT = L/4 M-tiles, or L/2 when WIDE)
 // and lane-half g owns the g-th half of it.
-template <int KS, int LT, int NT, bool WIDE>
+// FUSED: the workgroups from hash_blocks on do not hash; workgroup hash_blocks + b groups candidate list b by
+// document id range (cand_order.hpp), with the LDS that holds R otherwise as its bins.
+template <int KS, int LT, int NT, bool WIDE, bool FUSED>
 __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restrict__ X, uint64_t n,
                                                            const v4i* __restrict__ Rp, uint32_t cmask,
-                                                           uint8_t* __restrict__ codes) {
+                                                           uint8_t* __restrict__ codes, uint32_t hash_blocks,
+                                                           CandOrderArgs fused) {
     constexpr int D = KS * 32;
     constexpr int L = LT * 4;   // bytes per code row
     constexpr int OW = LT / 2;  // output dwords per lane (half a code row)
     extern __shared__ v4i sR[];
+    if constexpr (FUSED) {
+        if (blockIdx.x >= hash_blocks) {
+            __shared__ uint32_t wave_sum[4];
+            cand_order_body<256>(fused, blockIdx.x - hash_blocks, reinterpret_cast<uint32_t*>(sR), wave_sum);
+            return;
+        }
+    }
     for (int i = threadIdx.x; i < LT * KS * 64; i += 256) sR[i] = Rp[i];
     __syncthreads();
 
@@ -136,7 +146,7 @@ __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restr
     const int g = lane >> 5;
     const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
 
-    for (uint64_t tile = (uint64_t)blockIdx.x * 4 + wave; tile < n_tiles; tile += (uint64_t)gridDim.x * 4) {
+    for (uint64_t tile = (uint64_t)blockIdx.x * 4 + wave; tile < n_tiles; tile += (uint64_t)hash_blocks * 4) {
         const uint64_t v0 = tile * (32 * NT);
         v4i b[NT][KS];
 #pragma unroll
@@ -278,31 +288,49 @@ hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32
 
 template <int KS, int LT>
 static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
-                                hipStream_t stream) {
+                                const CandOrderArgs* fused, hipStream_t stream) {
     constexpr int NT = 2;
     const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
     uint64_t blocks = (n_tiles + 3) / 4;
     if (blocks > 1024) blocks = 1024;  // persistent waves: 256 CUs x 4 workgroups
     size_t lds = (size_t)LT * KS * 64 * 16;
-    if (C <= 8) {
-        auto kern = hash_mfma_i8_kernel<KS, LT, NT, false>;
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
-                           codes);
-    } else {
-        auto kern = hash_mfma_i8_kernel<KS, LT, NT, true>;
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, stream, X, n, (const v4i*)Rp, (1u << C) - 1u,
-                           codes);
+    const uint32_t cmask = (1u << C) - 1u;
+    if (fused) {
+        if ((size_t)fused->ranges * 4 > lds || blocks + fused->n_lists > 0x7fffffffull) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)(blocks + fused->n_lists));
+        if (C <= 8)
+            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, true>), grid, dim3(256), lds, stream, X, n,
+                               (const v4i*)Rp, cmask, codes, (uint32_t)blocks, *fused);
+        else
+            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, true>), grid, dim3(256), lds, stream, X, n,
+                               (const v4i*)Rp, cmask, codes, (uint32_t)blocks, *fused);
+        return hipGetLastError();
     }
+    if (C <= 8)
+        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, false>), dim3((unsigned)blocks), dim3(256), lds, stream, X,
+                           n, (const v4i*)Rp, cmask, codes, (uint32_t)blocks, CandOrderArgs{});
+    else
+        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, false>), dim3((unsigned)blocks), dim3(256), lds, stream, X,
+                           n, (const v4i*)Rp, cmask, codes, (uint32_t)blocks, CandOrderArgs{});
     return hipGetLastError();
 }
 
+// ranges the fused grouping may use: the bins live in the LDS that holds R in the hashing workgroups
+uint32_t hash_mfma_fused_ranges(uint32_t d, uint32_t L, uint32_t C) {
+    if (!hash_mfma_supported(d, L, C)) return 0;
+    const size_t words = (size_t)mfma_tiles(L, C) * (d / 32) * 64 * 4;
+    uint32_t r = 1;
+    while ((size_t)r * 2 <= words && r < 4096) r *= 2;
+    return r;
+}
+
 hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
-                               uint8_t* codes, hipStream_t stream) {
+                               uint8_t* codes, const CandOrderArgs* fused, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
     const uint32_t lt = mfma_tiles(L, C);
 #define DESSERT_MFMA_CASE(KS_, LT_) \
-    if (d == KS_ * 32 && lt == LT_) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, stream);
+    if (d == KS_ * 32 && lt == LT_) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, fused, stream);
     DESSERT_MFMA_CASE(2, 2)
     DESSERT_MFMA_CASE(2, 4)
     DESSERT_MFMA_CASE(2, 8)

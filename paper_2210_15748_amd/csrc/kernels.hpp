@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "cand_order.hpp"
+
 namespace dessert {
 
 // ---- hashing (Sec. 3 SRP family, Sec. 5 concatenation trick) ----------------
@@ -15,8 +17,12 @@ hipError_t launch_rademacher(uint64_t seed, uint32_t P, uint32_t d, int8_t* R, h
 size_t mfma_proj_bytes(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream);
 bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C);
+// fused: nullptr, or a candidate grouping (cand_order_plan with max_ranges = hash_mfma_fused_ranges) that extra
+// workgroups of the same launch carry out beside the hashing (a search hashes few vectors: both are short, latency-bound
+// jobs, and one launch instead of two saves a kernel boundary on the stream).
+uint32_t hash_mfma_fused_ranges(uint32_t d, uint32_t L, uint32_t C);
 hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t L, uint32_t C, const void* Rp,
-                               uint8_t* codes, hipStream_t stream);
+                               uint8_t* codes, const CandOrderArgs* fused, hipStream_t stream);
 
 // fp16 vectors x fp32 Gaussian projections on fp16 MFMA (projection matrix split hi + lo).
 size_t mfma_f16_proj_bytes(uint32_t d, uint32_t L);
@@ -69,8 +75,10 @@ hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
 // Workgroups that take the same run of positions of different lists then read neighbouring parts of the code array
 // at about the same time.  Worth it from score_order_min() candidates per list on.
 uint64_t score_order_min();
-hipError_t launch_cand_order(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
-                             uint64_t max_scored, uint64_t n_docs, uint32_t* order, hipStream_t stream);
+// Fills *out for lists of at most max_scored ids (ranges a power of two <= max_ranges); false: not applicable.
+bool cand_order_plan(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
+                     uint64_t max_scored, uint64_t n_docs, uint32_t max_ranges, uint32_t* order, CandOrderArgs* out);
+hipError_t launch_cand_order(const CandOrderArgs& a, hipStream_t stream);  // a.ranges <= 4096
 bool score_masklut_supported(uint32_t L, uint32_t C);
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
 

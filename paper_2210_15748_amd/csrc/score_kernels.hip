@@ -643,91 +643,31 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     }
 }
 
-// Counting sort of a candidate list's slots by range of document id: one workgroup per list, ranges = the leading
-// bits of the id (about 128 candidates per range when the ids are spread evenly), two passes over the ids.
+// Stand-alone form of the candidate grouping (cand_order.hpp): one workgroup per list.
 constexpr uint32_t ORDER_THREADS = 512, ORDER_MAX_RANGES = 4096;
-__global__ __launch_bounds__(ORDER_THREADS) void cand_order_kernel(const uint32_t* __restrict__ cand_ids,
-                                                                   const uint64_t* __restrict__ cand_off, uint64_t cand_uniform,
-                                                                   uint32_t shift, uint32_t ranges,
-                                                                   uint32_t* __restrict__ order) {
+__global__ __launch_bounds__(ORDER_THREADS) void cand_order_kernel(CandOrderArgs a) {
     __shared__ uint32_t bin[ORDER_MAX_RANGES];
     __shared__ uint32_t wave_sum[ORDER_THREADS / 64];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint64_t base = cand_uniform ? (uint64_t)b * cand_uniform : cand_off[b];
-    const uint64_t n = cand_uniform ? cand_uniform : cand_off[b + 1] - base;
-    const uint32_t* ids = cand_ids + base;
-    uint32_t* out = order + base;
-    auto range_of = [&](uint32_t id) {  // empty slots (id 0xFFFFFFFF) and anything past the end go to the last range
-        const uint32_t r = shift < 32 ? id >> shift : 0;
-        return r < ranges ? r : ranges - 1;
-    };
-    for (uint32_t i = tid; i < ranges; i += ORDER_THREADS) bin[i] = 0;
-    __syncthreads();
-    // eight loads in flight per thread; a list of up to 4096 ids stays in registers for the second pass
-    constexpr int U = 8;
-    const bool cached = n <= (uint64_t)U * ORDER_THREADS;
-    uint32_t held[U];
-    for (uint64_t i0 = 0; i0 < n; i0 += (uint64_t)U * ORDER_THREADS) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
-            held[u] = i < n ? ids[i] : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (i0 + tid + (uint64_t)u * ORDER_THREADS < n) atomicAdd(&bin[range_of(held[u])], 1u);
-    }
-    __syncthreads();
-    // exclusive prefix sum of the bins: thread t owns bins [t*per, (t+1)*per)
-    const uint32_t per = (ranges + ORDER_THREADS - 1) / ORDER_THREADS;
-    uint32_t mine = 0;
-    for (uint32_t j = 0; j < per; ++j)
-        if (tid * per + j < ranges) mine += bin[tid * per + j];
-    uint32_t incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off, 64);
-        if ((int)lane >= off) incl += o;
-    }
-    if (lane == 63) wave_sum[wave] = incl;
-    __syncthreads();
-    uint32_t run = incl - mine;
-    for (uint32_t w2 = 0; w2 < wave; ++w2) run += wave_sum[w2];
-    for (uint32_t j = 0; j < per; ++j)
-        if (tid * per + j < ranges) {
-            const uint32_t c = bin[tid * per + j];
-            bin[tid * per + j] = run;
-            run += c;
-        }
-    __syncthreads();
-    for (uint64_t i0 = 0; i0 < n; i0 += (uint64_t)U * ORDER_THREADS) {
-        if (!cached) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
-                held[u] = i < n ? ids[i] : 0;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t i = i0 + tid + (uint64_t)u * ORDER_THREADS;
-            if (i < n) out[atomicAdd(&bin[range_of(held[u])], 1u)] = (uint32_t)i;
-        }
-    }
+    cand_order_body<ORDER_THREADS>(a, blockIdx.x, bin, wave_sum);
 }
 
 uint64_t score_order_min() { return 1024; }
 
-hipError_t launch_cand_order(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
-                             uint64_t max_scored, uint64_t n_docs, uint32_t* order, hipStream_t stream) {
-    if (n_queries == 0 || max_scored == 0) return hipSuccess;
-    if (max_scored > 0xFFFFFFFFull) return hipErrorInvalidValue;  // slots are 32-bit
+bool cand_order_plan(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
+                     uint64_t max_scored, uint64_t n_docs, uint32_t max_ranges, uint32_t* order, CandOrderArgs* out) {
+    if (n_queries == 0 || max_scored == 0 || max_scored > 0xFFFFFFFFull || max_ranges == 0) return false;  // slots are 32-bit
     uint32_t id_bits = 1;
     while (id_bits < 32 && ((n_docs ? n_docs - 1 : 0) >> id_bits)) ++id_bits;
-    uint32_t log_ranges = 0;
-    while ((128ull << log_ranges) < max_scored && (1u << log_ranges) < ORDER_MAX_RANGES && log_ranges < id_bits) ++log_ranges;
-    hipLaunchKernelGGL(cand_order_kernel, dim3(n_queries), dim3(ORDER_THREADS), 0, stream, cand_ids, cand_off, cand_uniform,
-                       id_bits - log_ranges, 1u << log_ranges, order);
+    uint32_t log_ranges = 0;   // about 128 candidates per range when the ids are spread evenly
+    while ((128ull << log_ranges) < max_scored && (2u << log_ranges) <= max_ranges && log_ranges < id_bits) ++log_ranges;
+    *out = CandOrderArgs{cand_ids, cand_off, cand_uniform, n_queries, id_bits - log_ranges, 1u << log_ranges, order};
+    return true;
+}
+
+hipError_t launch_cand_order(const CandOrderArgs& a, hipStream_t stream) {
+    if (a.n_lists == 0) return hipSuccess;
+    if (a.ranges > ORDER_MAX_RANGES) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(cand_order_kernel, dim3(a.n_lists), dim3(ORDER_THREADS), 0, stream, a);
     return hipGetLastError();
 }
 
