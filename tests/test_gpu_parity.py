@@ -189,12 +189,15 @@ def test_scores_edge_lengths_and_ragged_queries(algo):
         assert np.array_equal(got[co[b]:co[b + 1]], orc.scores(dc, off, qc[qo[b]:qo[b + 1]], c)), b
 
 
-@pytest.mark.parametrize("L,Cb,eq1", [(32, 7, False), (64, 8, True), (8, 11, False)])
-def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1):
+@pytest.mark.parametrize("L,Cb,eq1,hash_algo", [(32, 7, False, dz.HASH_AUTO), (64, 8, True, dz.HASH_AUTO),
+                                                 (8, 11, False, dz.HASH_AUTO),
+                                                 (32, 7, False, dz.HASH_SCALAR),   # the grouping as a launch of its own
+                                                 (16, 9, True, dz.HASH_SCALAR)])
+def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1, hash_algo):
     """Lists long enough for the mask-table kernel to take them grouped by document id range: uniform ids, ids all
     from one narrow range (one range gets nearly everything), descending ids, empty slots and repeats, lists of unequal
     length, one too short for the grouping.  Every score must land in its own slot."""
-    say(f"long candidate lists L={L} C={Cb} eq1={eq1}")
+    say(f"long candidate lists L={L} C={Cb} eq1={eq1} hash_algo={hash_algo}")
     rng = np.random.default_rng(L + Cb)
     d, N = 64, 50_000
     lens = rng.integers(0, 6, N)
@@ -206,6 +209,7 @@ def test_scores_long_candidate_lists_in_any_id_order(L, Cb, eq1):
     Q = np.clip(pool[rng.integers(0, 30, nq)] + rng.integers(-40, 41, (nq, d)), -127, 127).astype(np.int8)
     R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
     ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, hash_algo, dz.SCORE_AUTO)
     if eq1:
         dz.set_score_transform(ix, dz.SCORE_EQ1_Q16)
     dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
