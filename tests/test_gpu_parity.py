@@ -588,3 +588,35 @@ def test_random_configuration_end_to_end(seed):
         want_ids, want_sc = orc.topk(s, k, cands[b])
         assert np.array_equal(sc[b], want_sc), b
         assert np.array_equal(ids[b], want_ids), b
+
+
+def test_timing_of_every_call_and_of_every_third():
+    """dessert_enable_timing: 1 = every call is timed, n = every n-th; dessert_get_timing reaches the timed calls only."""
+    say("timing: every call, every third call, off")
+    w = gen.make(1)
+    p = w.preset
+    ix = dz.create(p.d, p.L, p.C, proj=w.proj.to(DEV))
+    dz.build_index(ix, w.docs.to(DEV), w.lengths)
+    q, ql = w.queries.to(DEV), w.q_lengths
+    want = dz.search(ix, q, ql, p.k)
+    dz.enable_timing(ix, True)
+    for _ in range(4):
+        got = dz.search(ix, q, ql, p.k)
+    for back in range(4):
+        t = dz.get_timing(ix, back)
+        assert t["total_ms"] > 0 and t["score_ms"] > 0 and t["hash_ms"] > 0 and t["topk_ms"] > 0
+        assert t["total_ms"] >= t["score_ms"]
+    with pytest.raises(dz.DessertError):
+        dz.get_timing(ix, 4)
+    dz.enable_timing(ix, 3)                      # calls 0, 3 and 6 of the next seven
+    for _ in range(7):
+        got = dz.search(ix, q, ql, p.k)
+    for back in range(3):
+        assert dz.get_timing(ix, back)["total_ms"] > 0
+    with pytest.raises(dz.DessertError):
+        dz.get_timing(ix, 3)
+    dz.enable_timing(ix, False)
+    dz.search(ix, q, ql, p.k)
+    with pytest.raises(dz.DessertError):
+        dz.get_timing(ix, 0)
+    assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
