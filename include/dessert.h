@@ -26,7 +26,15 @@
  *     and unchanged while the index is searched.
  *   - Asynchrony: all device work is enqueued on config.stream; calls return
  *     without synchronising.  Host arrays are read before the call returns.
- *     Outputs are valid once the caller has synchronised the stream.  (One
+ *     Outputs are valid once the caller has synchronised the stream.  Calls
+ *     on a stream that is being captured into a HIP graph: dessert_search,
+ *     dessert_scores and dessert_filter_query record
+ *     a fixed sequence of kernel launches when all query sets of the batch
+ *     have the same length and all candidate lists have the same length; with
+ *     unequal lengths (their offset arrays would be uploaded from a staging
+ *     buffer that later calls reuse), in debug mode, and for
+ *     dessert_build_index, a capturing stream gives DESSERT_ESTATE.  Timing
+ *     events are not recorded while capturing.  (One
  *     copy runs on a stream the handle owns: the offsets upload of
  *     dessert_build_index, beside the hash kernel; it starts after the work
  *     config.stream held at entry and config.stream waits for it before the
@@ -66,7 +74,8 @@ typedef enum {
     DESSERT_EINVAL = 1,   /* bad argument, nothing launched */
     DESSERT_ENOMEM = 2,   /* host or device allocation inside the library failed */
     DESSERT_EHIP = 3,     /* a HIP call failed; see dessert_last_error() */
-    DESSERT_ESTATE = 4    /* call order: search before build_index */
+    DESSERT_ESTATE = 4    /* call order (search before build_index, filter query before filter build, a filter
+                             left over from an earlier build_index), or a call that cannot be captured into a graph */
 } dessert_status_t;
 
 enum { DESSERT_I8 = 0, DESSERT_F16 = 1 };                       /* vector element type */
@@ -161,7 +170,9 @@ dessert_status_t dessert_hash(const dessert_index_t *index, const void *vectors_
  *   lengths_host  host, [n_docs] u32: m_i = |S_i| (0 allowed); sum must equal n_vectors
  *   codes_dev     dev, out, dessert_code_bytes(n_vectors): code (offsets[i]+j)*L + t of the array = f_t(x_j of S_i)
  *   offsets_dev   dev, out, [n_docs+1] u64: exclusive scan of lengths (in vectors)
- * The handle remembers codes_dev / offsets_dev for later searches. */
+ * The handle remembers codes_dev / offsets_dev for later searches.  A candidate filter built over an earlier
+ * collection on this handle is dropped: dessert_filter_query gives DESSERT_ESTATE until dessert_filter_build
+ * has run again. */
 dessert_status_t dessert_build_index(dessert_index_t *index, const void *vectors_dev, uint64_t n_vectors,
                                      const uint32_t *lengths_host, uint64_t n_docs,
                                      uint8_t *codes_dev, uint64_t *offsets_dev);
@@ -199,6 +210,14 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
                                 const uint32_t *q_lengths_host, uint32_t n_queries,
                                 const uint32_t *cand_ids_dev, const uint64_t *cand_offsets_host,
                                 void *workspace_dev, size_t workspace_bytes, int32_t *out_scores_dev);
+
+/* Debug mode (Sec. 1.1: the candidates are ids of the N sets of the collection): with enable != 0, every later
+ * dessert_search / dessert_scores call that gets candidate ids first range-checks them on
+ * the device and returns DESSERT_EINVAL, naming the first offending slot, if an id is neither below n_docs nor the
+ * empty-slot value 0xFFFFFFFF; nothing else is launched then.  The check waits for the stream (it reads one word
+ * back), so calls in debug mode are synchronous and cannot be captured into a graph.  Off by default: candidate ids
+ * are then used as given. */
+dessert_status_t dessert_set_debug(dessert_index_t *index, int enable);
 
 /* Candidate filter (Sec. 5 "Filtering"): an inverted index from centroid ids to document ids and the
  * query-side selection of the documents to score.  The centroids are an input (any centroid set works;
@@ -269,6 +288,13 @@ dessert_status_t dessert_get_timing(dessert_index_t *index, uint32_t calls_back,
  * buf_dev: dev, 16-byte aligned, bytes >= 16; ms_per_pass: host, out. */
 dessert_status_t dessert_probe_read_bandwidth(const void *buf_dev, size_t bytes, int device, void *stream, int reps,
                                               float *ms_per_pass);
+
+/* Measurement and test aid: the scoring kernel instantiation that the handle's most recent dessert_search /
+ * dessert_scores call launched, spelled as a profiler's kernel trace prints it (e.g.
+ * "score_masklut_kernel<32, 7, 1, 0, 1, false>": tables, index bits, bytes per code, score transform form, query sets
+ * per workgroup, chunks split over workgroups); "" if nothing was launched.  Lets a caller pair a run with the
+ * profiler summary of the same kernel.  The string lives in the handle. */
+const char *dessert_last_score_kernel(const dessert_index_t *index);
 
 const char *dessert_last_error(void);
 const char *dessert_version(void);

@@ -37,6 +37,7 @@ EXPORTS = [
     "dessert_set_query_weights",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
+    "dessert_set_debug", "dessert_last_score_kernel",
     "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
     "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
@@ -84,6 +85,9 @@ def lib() -> C.CDLL:
     l.dessert_search_workspace_bytes.restype = sz
     l.dessert_search.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, sz, vp, vp]
     l.dessert_scores.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
+    l.dessert_set_debug.argtypes = [vp, C.c_int]
+    l.dessert_last_score_kernel.argtypes = [vp]
+    l.dessert_last_score_kernel.restype = C.c_char_p
     l.dessert_filter_kmeans_workspace_bytes.argtypes = [vp, u64, u32]
     l.dessert_filter_kmeans_workspace_bytes.restype = sz
     l.dessert_filter_kmeans.argtypes = [vp, vp, u64, vp, u32, u32, vp, sz]
@@ -279,6 +283,14 @@ def search(ix: Index, q_vectors: torch.Tensor, q_lengths, k: int, cand_ids: Opti
                                 None if co is None else co.ctypes.data, k, workspace.data_ptr(), workspace.numel(),
                                 out_ids.data_ptr(), out_scores.data_ptr()))
     return out_ids, out_scores
+
+
+def last_score_kernel(ix: Index) -> str:
+    return lib().dessert_last_score_kernel(ix.handle).decode()
+
+
+def set_debug(ix: Index, enable: bool = True) -> None:
+    _check(lib().dessert_set_debug(ix.handle, int(bool(enable))))
 
 
 def scores(ix: Index, q_vectors: torch.Tensor, q_lengths, cand_ids: Optional[torch.Tensor] = None,

@@ -1,6 +1,8 @@
 // C ABI of the library (declared in include/dessert.h): argument validation,
-// workspace carving and kernel sequencing.  No compute happens on the host
-// beyond the exclusive scan of the document lengths in dessert_build_index.
+// workspace carving and kernel sequencing.  Host-side arithmetic is limited to
+// the exclusive scan of the document lengths in dessert_build_index, the L+1
+// fixed-point table entries of a score transform (phi or Eq. 1 of the count / L
+// values, host libm, in dessert_set_score_transform) and launch-shape planning.
 #include "../../include/dessert.h"
 
 #include <hip/hip_runtime.h>
@@ -71,6 +73,9 @@ struct dessert_index {
     uint32_t f_max_bucket = 0;                // most documents in one bucket
     bool f_built = false;
     int transform = DESSERT_SCORE_RAW_COUNTS;
+    char last_score_kernel[128] = "";  // instantiation launched by the last scoring step (dessert_last_score_kernel)
+    bool debug = false;            // dessert_set_debug: candidate ids are range-checked before they are used
+    unsigned long long* dbg_flag = nullptr;  // device, the first offending slot found by the checking kernel (library-owned)
     int hash_algo = DESSERT_HASH_AUTO;
     int score_algo = DESSERT_SCORE_AUTO;
     // index state
@@ -262,13 +267,22 @@ dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, con
     return DESSERT_OK;
 }
 
-// Shared body of dessert_search (k > 0) and dessert_scores (k == 0).
-dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uint32_t* q_lengths, uint32_t B,
+// Is the handle's stream being captured into a HIP graph?  (A failed query counts as "no".)
+bool stream_capturing(const dessert_index* ix) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ix->stream, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs != hipStreamCaptureStatusNone;
+}
+
+// Shared body of dessert_search (k > 0), dessert_scores (k == 0), after the batch has
+// been checked.  cand_off: host offsets, read only when the candidate lists have unequal lengths.
+dessert_status_t search_impl(dessert_index* ix, const Batch& bt, const void* q_vectors, uint32_t B,
                              const uint32_t* cand_ids, const uint64_t* cand_off, uint32_t k, void* workspace,
                              size_t workspace_bytes, int32_t* scores_out, uint32_t* out_ids, int32_t* out_scores) {
-    Batch bt;
-    dessert_status_t st = check_batch(ix, q_vectors, q_lengths, B, cand_ids, cand_off, &bt);
-    if (st != DESSERT_OK) return st;
+    dessert_status_t st = DESSERT_OK;
     if (B == 0) return DESSERT_OK;
     if (ix->transform != DESSERT_SCORE_RAW_COUNTS && bt.max_q_len > 16383)
         return fail(DESSERT_EINVAL, "the fixed-point score transforms need query sets of at most 16383 vectors");
@@ -292,12 +306,28 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     uint64_t* d_cand_off = (uint64_t*)(ws + w.cand_off);
     int32_t* scores = own_scores ? (int32_t*)(ws + w.scores) : scores_out;
 
-    const bool timed = ix->timed_now();
-    dessert_index::TimingSlot& ts = ix->begin_timed();
-    if (timed) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
     // Offset arrays are uploaded only when the lengths differ (equal lengths travel as kernel
     // arguments); they go through a pinned slot so that the uploads never block the host.
     const bool need_q = bt.q_uniform == 0, need_c = cand_ids && bt.cand_uniform == 0;
+    // Under graph capture only a fixed sequence of kernel launches can be recorded: an offsets upload would replay
+    // whatever a later call left in the pinned slot, and event records or a read-back cannot be captured at all.
+    const bool capturing = stream_capturing(ix);
+    if (capturing && (need_q || need_c))
+        return fail(DESSERT_ESTATE, "graph capture needs query sets of equal length and candidate lists of equal length");
+    if (capturing && ix->debug && cand_ids)
+        return fail(DESSERT_ESTATE, "graph capture is not possible in debug mode (the id check reads a flag back)");
+    if (ix->debug && cand_ids) {  // range-check the ids before any kernel uses them as indices
+        unsigned long long bad_slot = 0;
+        HIP_TRY(launch_check_cand_ids(cand_ids, bt.total_scored, ix->n_docs, ix->dbg_flag, ix->stream));
+        HIP_TRY(hipMemcpyAsync(&bad_slot, ix->dbg_flag, sizeof(bad_slot), hipMemcpyDeviceToHost, ix->stream));
+        HIP_TRY(hipStreamSynchronize(ix->stream));
+        if (bad_slot != ~0ull)
+            return fail(DESSERT_EINVAL, "cand_ids_dev[%llu] is neither below n_docs = %llu nor the empty-slot value 0xFFFFFFFF",
+                        bad_slot, (unsigned long long)ix->n_docs);
+    }
+    const bool timed = !capturing && ix->timed_now();
+    dessert_index::TimingSlot* tsp = timed ? &ix->begin_timed() : nullptr;
+    if (timed) HIP_TRY(hipEventRecord(tsp->ev[0], ix->stream));
     if (need_q || need_c) {
         dessert_index::MetaSlot& ms = ix->meta[ix->meta_next++ % dessert_index::kMetaSlots];
         if (ms.pending) {
@@ -357,19 +387,19 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
     if (st != DESSERT_OK) return st;
     if (grouping && !grouped) HIP_TRY(launch_cand_order(oa, ix->stream));
     if (grouping) sa.order = oa.order;
-    if (timed) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
+    if (timed) { HIP_TRY(hipEventRecord(tsp->ev[1], ix->stream)); tsp->hash = true; }
     if (algo == DESSERT_SCORE_MASKLUT) {
         if (sa.sigma_mean) return fail(DESSERT_EINVAL, "the MEAN score transforms run on the code-compare kernel only");
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
             return fail(DESSERT_EINVAL, "mask-table scoring needs L in {8,16,32,64,128} (C <= 8), or L = 8 with C <= 11, "
                                         "L = 16 with C <= 10, L = 32 with C = 9");
-        HIP_TRY(launch_score_masklut(sa, ix->stream));
+        HIP_TRY(launch_score_masklut(sa, ix->stream, ix->last_score_kernel, sizeof(ix->last_score_kernel)));
     } else if (algo == DESSERT_SCORE_BYTECMP) {
-        HIP_TRY(launch_score_bytecmp(sa, ix->stream));
+        HIP_TRY(launch_score_bytecmp(sa, ix->stream, ix->last_score_kernel, sizeof(ix->last_score_kernel)));
     } else {
         return fail(DESSERT_EINVAL, "unknown scoring algorithm %d", algo);
     }
-    if (timed) { HIP_TRY(hipEventRecord(ts.ev[2], ix->stream)); ts.score = true; }
+    if (timed) { HIP_TRY(hipEventRecord(tsp->ev[2], ix->stream)); tsp->score = true; }
 
     if (k) {
         TopkArgs ta{};
@@ -377,9 +407,9 @@ dessert_status_t search_impl(dessert_index* ix, const void* q_vectors, const uin
         ta.n_queries = B; ta.max_scored = bt.max_scored; ta.k = k; ta.max_score = sa.remap ? bt.max_q_len * ix->remap_max : bt.max_q_len * ix->cfg.L;
         ta.partial = (uint64_t*)(ws + w.partial); ta.out_ids = out_ids; ta.out_scores = out_scores;
         HIP_TRY(launch_topk(ta, ix->stream));
-        if (timed) { HIP_TRY(hipEventRecord(ts.ev[3], ix->stream)); ts.topk = true; }
+        if (timed) { HIP_TRY(hipEventRecord(tsp->ev[3], ix->stream)); tsp->topk = true; }
     }
-    if (timed) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    if (timed) { HIP_TRY(hipEventRecord(tsp->ev[4], ix->stream)); tsp->any = true; ++ix->timed_calls; }
     return DESSERT_OK;
 }
 
@@ -483,6 +513,7 @@ void dessert_destroy(dessert_index_t* ix) {
     if (ix->proj) (void)hipFree(ix->proj);
     if (ix->proj_mfma) (void)hipFree(ix->proj_mfma);
     if (ix->remap) (void)hipFree(ix->remap);
+    if (ix->dbg_flag) (void)hipFree(ix->dbg_flag);
     if (ix->f_cent) (void)hipFree(ix->f_cent);
     if (ix->f_table) (void)hipFree(ix->f_table);
     if (ix->f_cursor) (void)hipFree(ix->f_cursor);
@@ -586,10 +617,16 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
                     (unsigned long long)n_vectors);
     DeviceGuard guard(ix->cfg.device);
     if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+    if (stream_capturing(ix))
+        return fail(DESSERT_ESTATE, "dessert_build_index cannot be captured into a graph (it uploads the offsets from a "
+                                    "staging buffer that later calls reuse)");
+    // a new collection: the old index and any candidate filter built over it are gone
     ix->built = false;
+    ix->f_built = false;
+    ix->f_K = 0;
     const bool timed = ix->timed_now();
-    dessert_index::TimingSlot& ts = ix->begin_timed();
-    if (timed) HIP_TRY(hipEventRecord(ts.ev[0], ix->stream));
+    dessert_index::TimingSlot* tsp = timed ? &ix->begin_timed() : nullptr;
+    if (timed) HIP_TRY(hipEventRecord(tsp->ev[0], ix->stream));
     // The code layout does not depend on document boundaries, so hashing starts first, the host
     // scans the lengths while the GPU works, and the offsets go up on the library's own stream
     // beside the hash kernel: after whatever the caller's stream held at entry (it may still read
@@ -597,7 +634,7 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     HIP_TRY(hipEventRecord(ix->build_entry, ix->stream));
     dessert_status_t st = run_hash(ix, vectors_dev, n_vectors, codes_dev);
     if (st != DESSERT_OK) return st;
-    if (timed) { HIP_TRY(hipEventRecord(ts.ev[1], ix->stream)); ts.hash = true; }
+    if (timed) { HIP_TRY(hipEventRecord(tsp->ev[1], ix->stream)); tsp->hash = true; }
     // the staging buffer may still feed the previous build's upload (enqueued before this hash launch)
     if (ix->upload_pending) {
         HIP_TRY(hipEventSynchronize(ix->upload_done));
@@ -622,7 +659,7 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     HIP_TRY(hipEventRecord(ix->upload_done, ix->copy_stream));
     HIP_TRY(hipStreamWaitEvent(ix->stream, ix->upload_done, 0));
     ix->upload_pending = true;
-    if (timed) { HIP_TRY(hipEventRecord(ts.ev[4], ix->stream)); ts.any = true; ++ix->timed_calls; }
+    if (timed) { HIP_TRY(hipEventRecord(tsp->ev[4], ix->stream)); tsp->any = true; ++ix->timed_calls; }
     ix->codes = codes_dev;
     ix->offsets = offsets_dev;
     ix->n_docs = n_docs;
@@ -645,16 +682,36 @@ dessert_status_t dessert_search(const dessert_index_t* ix, const void* q_vectors
                                 int32_t* out_scores_dev) {
     if (k == 0 || k > 16384) return fail(DESSERT_EINVAL, "k must be in 1..16384, got %u", k);
     if (n_queries && (!out_ids_dev || !out_scores_dev)) return fail(DESSERT_EINVAL, "output pointer is NULL");
-    return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
-                       cand_offsets_host, k, workspace_dev, workspace_bytes, nullptr, out_ids_dev, out_scores_dev);
+    Batch bt;
+    dessert_status_t st = check_batch(ix, q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev, cand_offsets_host, &bt);
+    if (st != DESSERT_OK) return st;
+    return search_impl(const_cast<dessert_index*>(ix), bt, q_vectors_dev, n_queries, cand_ids_dev, cand_offsets_host, k,
+                       workspace_dev, workspace_bytes, nullptr, out_ids_dev, out_scores_dev);
 }
 
 dessert_status_t dessert_scores(const dessert_index_t* ix, const void* q_vectors_dev, const uint32_t* q_lengths_host,
                                 uint32_t n_queries, const uint32_t* cand_ids_dev, const uint64_t* cand_offsets_host,
                                 void* workspace_dev, size_t workspace_bytes, int32_t* out_scores_dev) {
     if (n_queries && !out_scores_dev) return fail(DESSERT_EINVAL, "out_scores_dev is NULL");
-    return search_impl(const_cast<dessert_index*>(ix), q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev,
-                       cand_offsets_host, 0, workspace_dev, workspace_bytes, out_scores_dev, nullptr, nullptr);
+    Batch bt;
+    dessert_status_t st = check_batch(ix, q_vectors_dev, q_lengths_host, n_queries, cand_ids_dev, cand_offsets_host, &bt);
+    if (st != DESSERT_OK) return st;
+    return search_impl(const_cast<dessert_index*>(ix), bt, q_vectors_dev, n_queries, cand_ids_dev, cand_offsets_host, 0,
+                       workspace_dev, workspace_bytes, out_scores_dev, nullptr, nullptr);
+}
+
+const char* dessert_last_score_kernel(const dessert_index_t* ix) { return ix ? ix->last_score_kernel : ""; }
+
+dessert_status_t dessert_set_debug(dessert_index_t* ix, int enable) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (enable && !ix->dbg_flag) {
+        DeviceGuard guard(ix->cfg.device);
+        if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
+        hipError_t e = hipMalloc((void**)&ix->dbg_flag, sizeof(unsigned long long));
+        if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipMalloc(debug flag): %s", hipGetErrorString(e));
+    }
+    ix->debug = enable != 0;
+    return DESSERT_OK;
 }
 
 dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroids_dev, uint32_t n_centroids,
@@ -826,6 +883,8 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     uint32_t* cursor = (uint32_t*)(ws + w.cursor);
     uint64_t* lists = (uint64_t*)(ws + w.lists);
     if (!q_uniform) {
+        if (stream_capturing(ix))
+            return fail(DESSERT_ESTATE, "graph capture needs query sets of equal length");
         dessert_status_t st = upload_small(ix, q_off.data(), ((size_t)n_queries + 1) * 4, d_q_off);
         if (st != DESSERT_OK) return st;
     }

@@ -69,7 +69,9 @@ __device__ inline uint32_t q_begin(const ScoreArgs& a, uint32_t b) { return a.q_
 __device__ inline uint64_t cand_begin(const ScoreArgs& a, uint32_t b) {
     return a.cand_uniform ? (uint64_t)b * a.cand_uniform : a.cand_off[b];
 }
-hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream);
+// desc (optional, desc_len bytes): receives the name of the kernel instantiation that was launched, spelled as a
+// profiler prints it ("" when nothing was launched).
+hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream, char* desc = nullptr, size_t desc_len = 0);
 // Candidate lists gathered from all over the code array: order[list start + p] = the slots of a list grouped by
 // range of document id (a counting sort over the leading id bits; the order inside a range is unspecified).
 // Workgroups that take the same run of positions of different lists then read neighbouring parts of the code array
@@ -79,8 +81,12 @@ uint64_t score_order_min();
 bool cand_order_plan(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
                      uint64_t max_scored, uint64_t n_docs, uint32_t max_ranges, uint32_t* order, CandOrderArgs* out);
 hipError_t launch_cand_order(const CandOrderArgs& a, hipStream_t stream);  // a.ranges <= 4096
+// Debug aid: *first_bad = the lowest slot whose id is neither below n_docs nor the empty-slot value 0xFFFFFFFF,
+// all ones if every id is fine (two launches: reset, then a scan of the n ids).
+hipError_t launch_check_cand_ids(const uint32_t* cand_ids, uint64_t n, uint64_t n_docs, unsigned long long* first_bad,
+                                 hipStream_t stream);
 bool score_masklut_supported(uint32_t L, uint32_t C);
-hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream);
+hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream, char* desc = nullptr, size_t desc_len = 0);
 
 // ---- candidate filter (Sec. 5 "Filtering") ---------------------------------------------
 bool filter_supported(uint32_t d);

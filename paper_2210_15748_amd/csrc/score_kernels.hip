@@ -4,6 +4,8 @@
 // Scores are raw integer counts (no division by L, no remap of Eq. 1).
 #include "kernels.hpp"
 
+#include <cstdio>
+
 namespace dessert {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -95,7 +97,8 @@ __global__ __launch_bounds__(256) void score_bytecmp_kernel(ScoreArgs a) {
     }
 }
 
-hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
+hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream, char* desc, size_t desc_len) {
+    if (desc && desc_len) desc[0] = 0;
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
     if ((a.code_bytes != 1 && a.code_bytes != 2) || (a.L * a.code_bytes) % 4) return hipErrorInvalidValue;
     if (a.sigma_mean && !a.remap) return hipErrorInvalidValue;
@@ -111,6 +114,7 @@ hipError_t launch_score_bytecmp(const ScoreArgs& a, hipStream_t stream) {
     }
     uint64_t bx = (a.max_scored + 3) / 4;
     if (bx > 4096) bx = 4096;
+    if (desc) snprintf(desc, desc_len, "score_bytecmp_kernel<%u>", a.code_bytes);
     if (a.code_bytes == 1)
         hipLaunchKernelGGL(score_bytecmp_kernel<1>, dim3((unsigned)bx, a.n_queries), dim3(256), lds, stream, a);
     else
@@ -684,6 +688,30 @@ static hipError_t launch_fill_zero(int32_t* p, uint64_t n, hipStream_t stream) {
     return hipGetLastError();
 }
 
+__global__ void reset_first_bad_kernel(unsigned long long* first_bad) { *first_bad = ~0ull; }
+
+__global__ __launch_bounds__(256) void check_cand_ids_kernel(const uint32_t* __restrict__ ids, uint64_t n, uint64_t n_docs,
+                                                             unsigned long long* first_bad) {
+    unsigned long long worst = ~0ull;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t id = ids[i];
+        if (id != 0xFFFFFFFFu && id >= n_docs && i < worst) worst = i;
+    }
+    if (worst != ~0ull) atomicMin(first_bad, worst);
+}
+
+hipError_t launch_check_cand_ids(const uint32_t* cand_ids, uint64_t n, uint64_t n_docs, unsigned long long* first_bad,
+                                 hipStream_t stream) {
+    if (!first_bad) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reset_first_bad_kernel, dim3(1), dim3(1), 0, stream, first_bad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n == 0) return e;
+    uint64_t blocks = (n + 2047) / 2048;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(check_cand_ids_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, cand_ids, n, n_docs, first_bad);
+    return hipGetLastError();
+}
+
 // One-byte codes: L in {8, 16, 32, 64, 128}.  16-bit codes: the L * 2^C * 4-byte table has to fit 64 KB of LDS.
 bool score_masklut_supported(uint32_t L, uint32_t C) {
     if (C >= 1 && C <= 8) return L == 8 || L == 16 || L == 32 || L == 64 || L == 128;
@@ -691,7 +719,7 @@ bool score_masklut_supported(uint32_t L, uint32_t C) {
 }
 
 template <int L, int CB, int CW>
-static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
+static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char* desc, size_t desc_len) {
     // two query sets per workgroup when every document is scored for every set and the paired
     // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
     constexpr bool PAIR_OK = (size_t)L * (1u << CB) * 8 <= 32 * 1024;
@@ -738,6 +766,10 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
             gy_linear = (uint32_t)gyz;
         }
     }
+    // the instantiation as a profiler prints it
+    if (desc)
+        snprintf(desc, desc_len, "score_masklut_kernel<%d, %d, %d, %d, %d, %s>", L, CB, CW, a.q_weights ? 2 : a.remap ? 1 : 0,
+                 pair ? 2 : 1, gz > 1 ? "true" : "false");
     if constexpr (PAIR_OK) {
         if (pair) {
             auto kern2 = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 2, false>
@@ -761,13 +793,14 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream) {
+hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream, char* desc, size_t desc_len) {
+    if (desc && desc_len) desc[0] = 0;
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
     if (!score_masklut_supported(a.L, a.C) || a.code_bytes != (a.C > 8 ? 2u : 1u)) return hipErrorInvalidValue;
     if (a.sigma_mean || (a.q_weights && !a.remap)) return hipErrorInvalidValue;  // max of a tabulated phi only
     const uint32_t cb = a.C <= 6 ? 6 : a.C;
 #define DESSERT_LUT_CASE(L_, CB_, CW_) \
-    if (a.L == L_ && cb == CB_) return launch_masklut_t<L_, CB_, CW_>(a, stream);
+    if (a.L == L_ && cb == CB_) return launch_masklut_t<L_, CB_, CW_>(a, stream, desc, desc_len);
     DESSERT_LUT_CASE(8, 6, 1) DESSERT_LUT_CASE(8, 7, 1) DESSERT_LUT_CASE(8, 8, 1)
     DESSERT_LUT_CASE(16, 6, 1) DESSERT_LUT_CASE(16, 7, 1) DESSERT_LUT_CASE(16, 8, 1)
     DESSERT_LUT_CASE(32, 6, 1) DESSERT_LUT_CASE(32, 7, 1) DESSERT_LUT_CASE(32, 8, 1)
