@@ -28,7 +28,7 @@
  *     without synchronising.  Host arrays are read before the call returns.
  *     Outputs are valid once the caller has synchronised the stream.  Calls
  *     on a stream that is being captured into a HIP graph: dessert_search,
- *     dessert_scores and dessert_filter_query record
+ *     dessert_scores, dessert_search_noalloc and dessert_filter_query record
  *     a fixed sequence of kernel launches when all query sets of the batch
  *     have the same length and all candidate lists have the same length; with
  *     unequal lengths (their offset arrays would be uploaded from a staging
@@ -211,8 +211,24 @@ dessert_status_t dessert_scores(const dessert_index_t *index, const void *q_vect
                                 const uint32_t *cand_ids_dev, const uint64_t *cand_offsets_host,
                                 void *workspace_dev, size_t workspace_bytes, int32_t *out_scores_dev);
 
+/* Allocation-free form of dessert_search, for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same results as
+ * dessert_search for a batch in which every query set has q_length vectors and every candidate list has
+ * cand_length ids (cand_ids_dev NULL: every document is scored and cand_length is ignored); such a batch needs no
+ * offset arrays, so nothing is read from host arrays either.  The workspace is a device array built into the
+ * library, DESSERT_NOALLOC_SCRATCH_BYTES per GPU (each GPU the library is used on holds it until the process
+ * ends); a batch whose dessert_search_workspace_bytes(...) exceeds it gives DESSERT_EINVAL with the two sizes in
+ * the message.  The call allocates nothing and calls no allocating HIP routine.  All calls on one GPU share that
+ * GPU's array: two calls may not overlap on one GPU (different streams or threads), whichever handles they use;
+ * calls in stream order on one stream are fine.  Inputs and outputs are the caller's, as in dessert_search. */
+#define DESSERT_NOALLOC_SCRATCH_BYTES (16u << 20)
+size_t dessert_noalloc_scratch_bytes(void);
+dessert_status_t dessert_search_noalloc(const dessert_index_t *index, const void *q_vectors_dev, uint32_t q_length,
+                                        uint32_t n_queries, const uint32_t *cand_ids_dev, uint64_t cand_length,
+                                        uint32_t k, uint32_t *out_ids_dev, int32_t *out_scores_dev);
+
 /* Debug mode (Sec. 1.1: the candidates are ids of the N sets of the collection): with enable != 0, every later
- * dessert_search / dessert_scores call that gets candidate ids first range-checks them on
+ * dessert_search / dessert_scores / dessert_search_noalloc call that gets candidate ids first range-checks them on
  * the device and returns DESSERT_EINVAL, naming the first offending slot, if an id is neither below n_docs nor the
  * empty-slot value 0xFFFFFFFF; nothing else is launched then.  The check waits for the stream (it reads one word
  * back), so calls in debug mode are synchronous and cannot be captured into a graph.  Off by default: candidate ids
@@ -290,7 +306,7 @@ dessert_status_t dessert_probe_read_bandwidth(const void *buf_dev, size_t bytes,
                                               float *ms_per_pass);
 
 /* Measurement and test aid: the scoring kernel instantiation that the handle's most recent dessert_search /
- * dessert_scores call launched, spelled as a profiler's kernel trace prints it (e.g.
+ * dessert_scores / dessert_search_noalloc call launched, spelled as a profiler's kernel trace prints it (e.g.
  * "score_masklut_kernel<32, 7, 1, 0, 1, false>": tables, index bits, bytes per code, score transform form, query sets
  * per workgroup, chunks split over workgroups); "" if nothing was launched.  Lets a caller pair a run with the
  * profiler summary of the same kernel.  The string lives in the handle. */

@@ -37,7 +37,7 @@ EXPORTS = [
     "dessert_set_query_weights",
     "dessert_code_bytes",
     "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
-    "dessert_set_debug", "dessert_last_score_kernel",
+    "dessert_noalloc_scratch_bytes", "dessert_search_noalloc", "dessert_set_debug", "dessert_last_score_kernel",
     "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
     "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
@@ -85,6 +85,9 @@ def lib() -> C.CDLL:
     l.dessert_search_workspace_bytes.restype = sz
     l.dessert_search.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, sz, vp, vp]
     l.dessert_scores.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
+    l.dessert_noalloc_scratch_bytes.argtypes = []
+    l.dessert_noalloc_scratch_bytes.restype = sz
+    l.dessert_search_noalloc.argtypes = [vp, vp, u32, u32, vp, u64, u32, vp, vp]
     l.dessert_set_debug.argtypes = [vp, C.c_int]
     l.dessert_last_score_kernel.argtypes = [vp]
     l.dessert_last_score_kernel.restype = C.c_char_p
@@ -283,6 +286,33 @@ def search(ix: Index, q_vectors: torch.Tensor, q_lengths, k: int, cand_ids: Opti
                                 None if co is None else co.ctypes.data, k, workspace.data_ptr(), workspace.numel(),
                                 out_ids.data_ptr(), out_scores.data_ptr()))
     return out_ids, out_scores
+
+
+def search_noalloc(ix: Index, q_vectors: torch.Tensor, q_length: int, k: int, cand_ids: Optional[torch.Tensor] = None,
+                   out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None):
+    """dessert_search_noalloc: query sets of q_length vectors each, candidate lists [B, cand_length] (or None: every
+    document); the library's built-in scratch array is the workspace.  Outputs are allocated here only if not given."""
+    q_vectors = _check_vectors(ix, q_vectors)
+    if q_length <= 0 or q_vectors.shape[0] % q_length:
+        raise ValueError("the number of query vectors must be a multiple of q_length")
+    B = q_vectors.shape[0] // q_length
+    cand_len = 0
+    if cand_ids is not None:
+        if cand_ids.dim() != 2 or cand_ids.shape[0] != B or cand_ids.dtype not in (torch.int32, torch.uint32):
+            raise ValueError("cand_ids must be a device tensor [B, cand_length] of int32 / uint32")
+        cand_ids = cand_ids.contiguous()
+        cand_len = cand_ids.shape[1]
+    if out_ids is None:
+        out_ids = torch.empty(B, k, dtype=torch.uint32, device=ix.device)
+    if out_scores is None:
+        out_scores = torch.empty(B, k, dtype=torch.int32, device=ix.device)
+    _check(lib().dessert_search_noalloc(ix.handle, q_vectors.data_ptr(), q_length, B, _ptr(cand_ids), cand_len, k,
+                                        out_ids.data_ptr(), out_scores.data_ptr()))
+    return out_ids, out_scores
+
+
+def noalloc_scratch_bytes() -> int:
+    return int(lib().dessert_noalloc_scratch_bytes())
 
 
 def last_score_kernel(ix: Index) -> str:

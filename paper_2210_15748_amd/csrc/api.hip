@@ -11,6 +11,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -50,6 +51,33 @@ struct DeviceGuard {
     }
 };
 
+// Workspace of dessert_search_noalloc: one array per GPU, held until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress; the device address it yields (one per device) is what kernels
+// and copies get.
+constexpr size_t kScratchBytes = DESSERT_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+// Device address of this device's copy of `scratch`; looked up once per device, with that device current.
+dessert_status_t scratch_address(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return fail(DESSERT_EINVAL, "device %d out of range", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(DESSERT_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return DESSERT_OK;
+}
 }  // namespace
 
 struct dessert_index {
@@ -267,6 +295,34 @@ dessert_status_t check_batch(const dessert_index* ix, const void* q_vectors, con
     return DESSERT_OK;
 }
 
+// The same checks for a batch whose query sets all have q_len vectors and whose candidate lists all have cand_len
+// ids: nothing is read from host arrays and nothing is allocated.
+dessert_status_t check_uniform_batch(const dessert_index* ix, const void* q_vectors, uint32_t q_len, uint32_t B,
+                                     const uint32_t* cand_ids, uint64_t cand_len, Batch* out) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!ix->built) return fail(DESSERT_ESTATE, "dessert_build_index has not been called");
+    if (B == 0) return DESSERT_OK;
+    if (B > 65535) return fail(DESSERT_EINVAL, "n_queries > 65535");
+    if (!q_vectors) return fail(DESSERT_EINVAL, "q_vectors_dev is NULL");
+    if (q_len == 0) return fail(DESSERT_EINVAL, "q_length = 0");
+    if ((uint64_t)q_len * ix->cfg.L * code_width(ix->cfg) > 65535)
+        return fail(DESSERT_EINVAL, "q_length: the query set's codes (%llu bytes) exceed 65535 bytes",
+                    (unsigned long long)q_len * ix->cfg.L * code_width(ix->cfg));
+    if ((uint64_t)q_len * B > 0xFFFFFFFFull) return fail(DESSERT_EINVAL, "more than 2^32-1 query vectors");
+    out->total_q = (uint64_t)q_len * B;
+    out->max_q_len = out->q_uniform = q_len;
+    if (cand_ids) {
+        if (cand_len == 0) return fail(DESSERT_EINVAL, "cand_length = 0 with candidate ids given");
+        out->max_scored = out->cand_uniform = cand_len;
+        out->total_scored = cand_len * B;
+    } else {
+        out->max_scored = ix->n_docs;
+        out->total_scored = (uint64_t)B * ix->n_docs;
+    }
+    if (out->max_scored > 0x7FFFFFFFull * 64) return fail(DESSERT_EINVAL, "too many documents per query set");
+    return DESSERT_OK;
+}
+
 // Is the handle's stream being captured into a HIP graph?  (A failed query counts as "no".)
 bool stream_capturing(const dessert_index* ix) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
@@ -277,7 +333,7 @@ bool stream_capturing(const dessert_index* ix) {
     return cs != hipStreamCaptureStatusNone;
 }
 
-// Shared body of dessert_search (k > 0), dessert_scores (k == 0), after the batch has
+// Shared body of dessert_search (k > 0), dessert_scores (k == 0) and dessert_search_noalloc, after the batch has
 // been checked.  cand_off: host offsets, read only when the candidate lists have unequal lengths.
 dessert_status_t search_impl(dessert_index* ix, const Batch& bt, const void* q_vectors, uint32_t B,
                              const uint32_t* cand_ids, const uint64_t* cand_off, uint32_t k, void* workspace,
@@ -466,6 +522,11 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
 
     DeviceGuard guard(c->device);
     if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", c->device);
+    {   // the allocation-free entry point works in this device's copy of the scratch array
+        void* sp = nullptr;
+        dessert_status_t st = scratch_address(c->device, &sp);
+        if (st != DESSERT_OK) return st;
+    }
     dessert_index* ix = new (std::nothrow) dessert_index();
     if (!ix) return fail(DESSERT_ENOMEM, "out of host memory");
     ix->cfg = *c;
@@ -698,6 +759,27 @@ dessert_status_t dessert_scores(const dessert_index_t* ix, const void* q_vectors
     if (st != DESSERT_OK) return st;
     return search_impl(const_cast<dessert_index*>(ix), bt, q_vectors_dev, n_queries, cand_ids_dev, cand_offsets_host, 0,
                        workspace_dev, workspace_bytes, out_scores_dev, nullptr, nullptr);
+}
+
+size_t dessert_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+dessert_status_t dessert_search_noalloc(const dessert_index_t* ix, const void* q_vectors_dev, uint32_t q_length,
+                                        uint32_t n_queries, const uint32_t* cand_ids_dev, uint64_t cand_length,
+                                        uint32_t k, uint32_t* out_ids_dev, int32_t* out_scores_dev) {
+    if (k == 0 || k > 16384) return fail(DESSERT_EINVAL, "k must be in 1..16384, got %u", k);
+    if (n_queries && (!out_ids_dev || !out_scores_dev)) return fail(DESSERT_EINVAL, "output pointer is NULL");
+    Batch bt;
+    dessert_status_t st = check_uniform_batch(ix, q_vectors_dev, q_length, n_queries, cand_ids_dev, cand_length, &bt);
+    if (st != DESSERT_OK) return st;
+    if (n_queries == 0) return DESSERT_OK;
+    const size_t need = carve(ix, n_queries, bt.total_q, bt.total_scored, bt.max_scored, k, true).total;
+    if (need > kScratchBytes)
+        return fail(DESSERT_EINVAL, "this batch needs %zu bytes of workspace, the built-in scratch array holds %zu: "
+                                    "use dessert_search with a workspace of the caller's", need, kScratchBytes);
+    void* ws = g_scratch_ptr[(ix->cfg.device >= 0 && ix->cfg.device < kMaxDevices) ? ix->cfg.device : 0];
+    if (!ws) return fail(DESSERT_ESTATE, "no scratch address recorded for device %d", ix->cfg.device);
+    return search_impl(const_cast<dessert_index*>(ix), bt, q_vectors_dev, n_queries, cand_ids_dev, nullptr, k, ws,
+                       kScratchBytes, nullptr, out_ids_dev, out_scores_dev);
 }
 
 const char* dessert_last_score_kernel(const dessert_index_t* ix) { return ix ? ix->last_score_kernel : ""; }

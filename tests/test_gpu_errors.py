@@ -164,6 +164,7 @@ def test_debug_mode_catches_a_candidate_id_out_of_range():
     dz.set_debug(ix, True)
     expect(dz.EINVAL, r"cand_ids_dev\[17\]", lambda: dz.search(ix, Qd, [32], 5, cand_ids=as_dev(bad), cand_offsets=[0, 64]))
     expect(dz.EINVAL, r"cand_ids_dev\[17\]", lambda: dz.scores(ix, Qd, [32], cand_ids=as_dev(bad), cand_offsets=[0, 64]))
+    expect(dz.EINVAL, r"cand_ids_dev\[17\]", lambda: dz.search_noalloc(ix, Qd, 32, 5, cand_ids=as_dev(bad).view(1, 64)))
     got = dz.scores(ix, Qd, [32], cand_ids=as_dev(good), cand_offsets=[0, 64]).cpu().numpy()
     dz.set_debug(ix, False)
     again = dz.scores(ix, Qd, [32], cand_ids=as_dev(good), cand_offsets=[0, 64]).cpu().numpy()
