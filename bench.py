@@ -60,29 +60,44 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_roofline(p, n_vectors: int, hash_kernel_ms):
-    """int8 vectors: the hash kernel is bound by HBM (d bytes read + L code bytes written per vector).  fp16 vectors
-    with a Gaussian matrix: bound by the fp16 matrix cores (the matrix is split into two fp16 parts, so
-    2 * 2 * d * 8L flops per vector with the 8 bit rows per table the tiles hold)."""
+def build_roofline(p, n_vectors: int, hash_kernel_ms, mix_gbs=None):
+    """int8 vectors: the hash kernel is bound by HBM (d bytes read + L code bytes written per vector); `mix_gbs` is what
+    a kernel with the same 4 : 1 read : write traffic and no arithmetic gets on this GPU in this run.  fp16 vectors with
+    a Gaussian matrix: bound by the fp16 matrix cores.  The method's work is 2 * d * L * C flops per vector (Sec. 3
+    SRP, the m L d hashing term of Thm 2): that is `achieved`.  The kernel issues 2 * 2 * d * 8L (the fp32 matrix is
+    split into two fp16 parts and a table's C bit rows are padded to 8 per tile): reported as `kernel_issued`."""
     if not hash_kernel_ms:
         return None
     if p.dtype == "i8":
         a = n_vectors * (p.d + p.L) / (hash_kernel_ms * 1e-3) / 1e9
-        return {"bound": "hbm", "kernel": "hash_mfma_i8_kernel", "achieved": round(a, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4)}
-    a = n_vectors * 2 * 2 * p.d * 8 * p.L / (hash_kernel_ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": "hash_mfma_f16_kernel", "achieved": round(a, 2), "peak": MFMA_F16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(a / MFMA_F16_PEAK_TFLOPS, 4)}
+        r = {"bound": "hbm", "kernel": "hash_mfma_i8_kernel", "achieved": round(a, 2), "peak": HBM_PEAK_GBS,
+             "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None,
+             "algorithmic_bytes_per_launch": n_vectors * (p.d + p.L), "kernel_ms": round(hash_kernel_ms, 5)}
+        if mix_gbs:
+            r["measured_read_write_mix_GBs"] = round(mix_gbs, 1)
+            r["frac_of_measured_mix"] = round(a / mix_gbs, 4)
+        return r
+    method = n_vectors * 2 * p.d * p.L * p.C / (hash_kernel_ms * 1e-3) / 1e12
+    issued = n_vectors * 2 * 2 * p.d * 8 * p.L / (hash_kernel_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": "hash_mfma_f16_kernel", "achieved": round(method, 2), "peak": MFMA_F16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(method / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+            "flops": "the method's 2*d*L*C per vector", "kernel_ms": round(hash_kernel_ms, 5),
+            "kernel_issued": {"achieved": round(issued, 2), "frac": round(issued / MFMA_F16_PEAK_TFLOPS, 4),
+                              "flops": "2*2*d*8L per vector: hi + lo fp16 parts of the fp32 matrix, 8 bit rows per table"}}
 
 
 def traffic_from_profile(kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (FETCH_SIZE and
+    """HBM bytes per launch of the scoring kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
     WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel calibration factors 2.0 and 1.0 stated there).
-    Valid for the full candidate-rerank preset only; None if the summary is missing."""
+    `kernel` is the instantiation this run launched, spelled as the profiler prints it: the summary's lines must be
+    about exactly that instantiation, else None (a summary made for an older kernel says nothing about this one).
+    Valid for the full candidate-rerank preset only."""
     path = os.path.join(ROOT, "profiles", "cfg3_search_and_build_kernels.txt")
     try:
         text = open(path).read()
     except OSError:
+        return None
+    if not kernel:
         return None
     vals = {}
     section = None
@@ -91,8 +106,13 @@ def traffic_from_profile(kernel: str):
             section = "fetch"
         elif line.startswith("## --pmc WRITE_SIZE"):
             section = "write"
-        elif section and kernel in line and "mean=" in line:
-            vals.setdefault(section, float(line.split("mean=")[1]))
+        elif line.startswith("## "):
+            section = None
+        elif section and "mean=" in line:
+            name = line.split("grid=")[0].strip()
+            # the summary keeps the tail of long names: the launched name must end with what the line shows
+            if name and kernel.endswith(name.lstrip(":").lstrip()) and "score_" in kernel and name.endswith(">"):
+                vals.setdefault(section, float(line.split("mean=")[1]))
     if "fetch" not in vals or "write" not in vals:
         return None
     return int((vals["fetch"] * 2.0 + vals["write"] * 1.0) * 1024)
@@ -103,13 +123,19 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="untimed search steps run for about this long BEFORE the warm-up steps (reported as settle_steps): "
+                         "after a change of load this GPU runs 10-30 %% slower for some 25 ms while its power "
+                         "management settles (DESIGN.md, measurement), which at 0.4 ms per step is longer than any "
+                         "reasonable count of warm-up steps; 0 = none")
     ap.add_argument("--config", type=int, default=3, help="preset number (3 = candidate rerank, the metric's workload)")
     ap.add_argument("--sweep-m", type=int, default=None,
                     help="run the synthetic-experiment shape instead of a preset: 1000 documents of m vectors, L = 8, "
                          "C = log2(m) + 1, queries = noisy documents (not the metric's workload)")
     ap.add_argument("--n-docs", type=int, default=None, help="shrink the preset (for quick trials; not the metric)")
     ap.add_argument("--n-queries", type=int, default=None)
-    ap.add_argument("--build-reps", type=int, default=5)
+    ap.add_argument("--build-reps", type=int, default=20)
+    ap.add_argument("--build-warmup", type=int, default=10)
     ap.add_argument("--score-algo", type=int, default=0)
     ap.add_argument("--hash-algo", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -168,7 +194,8 @@ def main() -> int:
     codes = torch.empty(w.n_vectors, p.L, dtype=dz.code_dtype(ix), device=dev)
     offsets = torch.empty(w.n_docs + 1, dtype=torch.int64, device=dev)
     lengths = w.lengths.numpy().astype(np.uint32)
-    dz.build_index(ix, w.docs, lengths, codes, offsets)          # warm-up + the index used below
+    for _ in range(max(1, args.build_warmup)):                   # warm-up + the index used below
+        dz.build_index(ix, w.docs, lengths, codes, offsets)
     torch.cuda.synchronize()
     tb = time.perf_counter()
     for _ in range(args.build_reps):
@@ -177,7 +204,8 @@ def main() -> int:
     build_ms = (time.perf_counter() - tb) * 1e3 / max(1, args.build_reps)
     hash_kernel_ms = float(np.mean([dz.get_timing(ix, i)["hash_ms"] for i in range(min(args.build_reps, 64))])) \
         if args.build_reps else 0.0
-    log(f"[bench] build_index: {build_ms:.3f} ms/call, hash kernel {hash_kernel_ms:.3f} ms")
+    log(f"[bench] build_index: {build_ms:.3f} ms/call, hash kernel {hash_kernel_ms:.3f} ms  per call: "
+        + " ".join(f"{dz.get_timing(ix, i)['hash_ms']:.3f}" for i in reversed(range(min(args.build_reps, 64)))))
 
     # ---- search (S1-S5)
     B, k = p.n_queries, p.k
@@ -192,6 +220,15 @@ def main() -> int:
     def step():
         dz.search(ix, w.queries, ql, k, cand_ids=cand, cand_offsets=co, workspace=ws, out_ids=out_ids, out_scores=out_sc)
 
+    # settle phase (see --settle-ms): the same step, untimed, until the clocks have settled; then the W warm-up steps
+    settle_steps = 0
+    if args.settle_ms > 0:
+        t_s = time.perf_counter()
+        while (time.perf_counter() - t_s) * 1e3 < args.settle_ms:
+            for _ in range(8):
+                step()
+            torch.cuda.synchronize()
+            settle_steps += 8
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -222,6 +259,7 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     if not args.graph:
         tim = [dz.get_timing(ix, i) for i in range(n_t)]
+    score_kernel = dz.last_score_kernel(ix)
     score_ms = float(np.mean([t["score_ms"] for t in tim]))
     qhash_ms = float(np.mean([t["hash_ms"] for t in tim]))
     topk_ms = float(np.mean([t["topk_ms"] for t in tim]))
@@ -303,6 +341,14 @@ def main() -> int:
     read_gbs = dz.probe_read_bandwidth(probe, reps=10)
     del probe
     log(f"[bench] plain streaming read: {read_gbs:.0f} GB/s")
+    # ---- and a kernel with the index build's traffic (128 bytes read, 32 written per vector) and no arithmetic
+    mix_gbs = None
+    if p.dtype == "i8":
+        mix_src = torch.empty(1 << 30, dtype=torch.int32, device=dev).zero_()   # 4 GiB read
+        mix_dst = torch.empty(1 << 28, dtype=torch.int32, device=dev)           # 1 GiB written
+        mix_gbs = dz.probe_mix_bandwidth(mix_src, mix_dst, reps=10)
+        del mix_src, mix_dst
+        log(f"[bench] read-write mix 4:1 without arithmetic: {mix_gbs:.0f} GB/s")
 
     # ---- roofline of the dominant kernel (scoring): algorithmic bytes = code bytes of every scored document
     if cand is not None:
@@ -314,7 +360,8 @@ def main() -> int:
         achieved = code_bytes / (score_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "score_masklut_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": traffic_from_profile("score_masklut_kernel")
+                    "kernel_launched": score_kernel,
+                    "traffic": traffic_from_profile(score_kernel)
                     if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None) else None,
                     "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5),
                     "measured_stream_read_GBs": round(read_gbs, 1), "frac_of_measured_stream": round(achieved / read_gbs, 4)}
@@ -329,6 +376,7 @@ def main() -> int:
         achieved = lane_ops / (score_ms * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "score_masklut_kernel", "achieved": round(achieved, 3), "peak": VALU_PEAK_TLOPS,
                     "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_TLOPS, 4), "traffic": None,
+                    "kernel_launched": score_kernel,
                     "lane_ops_per_vector_and_32_queries": ops_unit, "algorithmic_lane_ops_per_launch": lane_ops,
                     "kernel_ms": round(score_ms, 5), "code_bytes_streamed_once": w.n_vectors * p.L * codes.element_size(),
                     # the same work in the method's own unit: table-code comparisons (document vector x query vector x table)
@@ -395,6 +443,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_steps": settle_steps,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
@@ -409,30 +458,40 @@ def main() -> int:
         "kernel_ms": {"query_hash": round(qhash_ms, 5), "score": round(score_ms, 5), "topk": round(topk_ms, 5)},
         "index_build": {"metric": "index-build vectors/sec", "value": round(w.n_vectors / (build_ms * 1e-3), 1),
                         "unit": "vectors/s", "ms_per_call": round(build_ms, 4), "hash_kernel_ms": round(hash_kernel_ms, 4),
-                        "reps": args.build_reps,
-                        "roofline": build_roofline(p, w.n_vectors, hash_kernel_ms)},
+                        "reps": args.build_reps, "warmup": max(1, args.build_warmup),
+                        "roofline": build_roofline(p, w.n_vectors, hash_kernel_ms, mix_gbs)},
         "candidate_filter": filt,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
-    # The default run also measures the exhaustive mid-scale preset (every document scored for every query set): a
-    # second view of the same metric, ALU-bound instead of HBM-bound.  It runs as a child process after this one's
-    # timed regions; not part of "value".
+    # The default run also measures the other presets that score every document for every query set, each in a child
+    # process after this one's timed regions (not part of "value"): the exhaustive mid-scale preset (the same metric,
+    # ALU-bound instead of HBM-bound), the large preset (8M documents: the index build over 563M vectors and a batch of
+    # 32 query sets) and the fp16 / Gaussian stress preset (tolerance path, checked against the oracle on a sample).
     if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None and not args.graph
             and not args.transform and not args.no_cpu_baseline and not args.no_secondary):
         import subprocess
         torch.cuda.synchronize()
-        try:
-            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--config", "2", "--no-cpu-baseline",
-                                    "--steps", "20", "--warmup", "3", "--build-reps", "3"],
-                                   capture_output=True, text=True, timeout=240)
-            sub = json.loads(child.stdout.strip().splitlines()[-1])
-            line["exhaustive_mid_scale"] = {
-                "workload": sub["config"]["workload"], "value": sub["value"], "unit": sub["unit"],
-                "ms_per_step": sub["ms_per_step"], "kernel_ms": sub["kernel_ms"], "config": sub["config"],
-                "roofline": sub["roofline"], "index_build": sub["index_build"]}
-        except Exception as e:  # the metric line must come out whatever happens to the extra measurement
-            line["exhaustive_mid_scale"] = {"error": repr(e)}
+        torch.cuda.empty_cache()
+
+        def child(name, argv, timeout):
+            try:
+                r = subprocess.run([sys.executable, os.path.abspath(__file__)] + argv, capture_output=True, text=True,
+                                   timeout=timeout)
+                sub = json.loads(r.stdout.strip().splitlines()[-1])
+                out = {"workload": sub["config"]["workload"], "value": sub["value"], "unit": sub["unit"],
+                       "ms_per_step": sub["ms_per_step"], "kernel_ms": sub["kernel_ms"], "config": sub["config"],
+                       "roofline": sub["roofline"], "index_build": sub["index_build"]}
+                if sub.get("cpu_baseline"):
+                    out["cpu_baseline"] = sub["cpu_baseline"]
+                line[name] = out
+            except Exception as e:  # the metric line must come out whatever happens to an extra measurement
+                line[name] = {"error": repr(e)}
+            log(f"[bench] {name}: {json.dumps(line[name])[:400]}")
+
+        child("exhaustive_mid_scale", ["--config", "2", "--no-cpu-baseline", "--steps", "20", "--warmup", "3", "--build-reps", "20"], 240)
+        child("large_exhaustive_index_build", ["--config", "4", "--no-cpu-baseline", "--steps", "10", "--warmup", "2", "--build-reps", "5"], 300)
+        child("fp16_stress", ["--config", "5", "--steps", "5", "--warmup", "2", "--build-reps", "3", "--cpu-sample-queries", "8"], 300)
     print(json.dumps(line), flush=True)
     return 0
 

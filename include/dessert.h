@@ -312,6 +312,13 @@ dessert_status_t dessert_probe_read_bandwidth(const void *buf_dev, size_t bytes,
  * profiler summary of the same kernel.  The string lives in the handle. */
 const char *dessert_last_score_kernel(const dessert_index_t *index);
 
+/* Measurement aid, not part of the method: the traffic of index building without its arithmetic.  Times `reps` passes
+ * of a kernel that reads 4 * out_bytes from in_dev and writes out_bytes to out_dev in whole lines (the 4 : 1 read : write
+ * mix of 128-byte vectors in, 32 code bytes out), HIP events on `stream`; synchronises.  What it achieves is the ceiling
+ * for dessert_build_index on this GPU, to set beside the nameplate 8 TB/s.  Both buffers dev, 16-byte aligned. */
+dessert_status_t dessert_probe_mix_bandwidth(const void *in_dev, void *out_dev, size_t out_bytes, int device, void *stream,
+                                             int reps, float *ms_per_pass);
+
 const char *dessert_last_error(void);
 const char *dessert_version(void);
 

@@ -40,7 +40,7 @@ EXPORTS = [
     "dessert_noalloc_scratch_bytes", "dessert_search_noalloc", "dessert_set_debug", "dessert_last_score_kernel",
     "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
-    "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_last_error",
+    "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_probe_mix_bandwidth", "dessert_last_error",
     "dessert_version",
 ]
 
@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
     l.dessert_enable_timing.argtypes = [vp, C.c_int]
     l.dessert_get_timing.argtypes = [vp, u32, C.POINTER(C.c_float)]
     l.dessert_probe_read_bandwidth.argtypes = [vp, sz, C.c_int, vp, C.c_int, C.POINTER(C.c_float)]
+    l.dessert_probe_mix_bandwidth.argtypes = [vp, vp, sz, C.c_int, vp, C.c_int, C.POINTER(C.c_float)]
     l.dessert_last_error.restype = C.c_char_p
     l.dessert_version.restype = C.c_char_p
     _lib = l
@@ -406,3 +407,16 @@ def probe_read_bandwidth(buf: torch.Tensor, reps: int = 10) -> float:
     stream = torch.cuda.current_stream(buf.device).cuda_stream
     _check(lib().dessert_probe_read_bandwidth(buf.data_ptr(), nbytes, buf.device.index or 0, stream, reps, C.byref(ms)))
     return nbytes / (ms.value * 1e-3) / 1e9
+
+
+def probe_mix_bandwidth(src: torch.Tensor, dst: torch.Tensor, reps: int = 10) -> float:
+    """dessert_probe_mix_bandwidth: GB/s (read + written) of a kernel that reads 4 bytes of `src` for every byte it
+    writes to `dst` and computes nothing (measurement aid: the ceiling for the index build's traffic)."""
+    out_bytes = dst.numel() * dst.element_size()
+    if src.numel() * src.element_size() < 4 * out_bytes:
+        raise ValueError("src must hold four times the bytes of dst")
+    ms = C.c_float()
+    stream = torch.cuda.current_stream(dst.device).cuda_stream
+    _check(lib().dessert_probe_mix_bandwidth(src.data_ptr(), dst.data_ptr(), out_bytes, dst.device.index or 0, stream, reps,
+                                             C.byref(ms)))
+    return 5 * out_bytes / (ms.value * 1e-3) / 1e9

@@ -501,7 +501,33 @@ dessert_status_t dessert_probe_read_bandwidth(const void* buf_dev, size_t bytes,
     *ms_per_pass = ms / (float)reps;
     return DESSERT_OK;
 }
-const char* dessert_version(void) { return "dessert-gfx950 0.1"; }
+dessert_status_t dessert_probe_mix_bandwidth(const void* in_dev, void* out_dev, size_t out_bytes, int device, void* stream,
+                                            int reps, float* ms_per_pass) {
+    if (!in_dev || !out_dev || !ms_per_pass || out_bytes < 16 || reps < 1) return fail(DESSERT_EINVAL, "bad probe arguments");
+    if ((uintptr_t)in_dev % 16 || (uintptr_t)out_dev % 16) return fail(DESSERT_EINVAL, "probe buffers must be 16-byte aligned");
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", device);
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipError_t ec = hipEventCreate(&e1); ec != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(DESSERT_EHIP, "hipEventCreate: %s", hipGetErrorString(ec));
+    }
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_mix_probe(in_dev, out_dev, out_bytes, st);  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, st);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_mix_probe(in_dev, out_dev, out_bytes, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(DESSERT_EHIP, "mix probe: %s", hipGetErrorString(e));
+    *ms_per_pass = ms / (float)reps;
+    return DESSERT_OK;
+}
+const char* dessert_version(void) { return "dessert-gfx950 0.2"; }
 
 dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out) {
     if (!c || !out) return fail(DESSERT_EINVAL, "config or out is NULL");

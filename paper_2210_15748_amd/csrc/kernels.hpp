@@ -38,6 +38,8 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
 
 // ---- measurement aid: one pass of a plain streaming read over [buf, buf+bytes) ------------
 hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t stream);
+// one pass that reads 4 * out_bytes from `in` and writes out_bytes to `out` (index building's traffic without its arithmetic)
+hipError_t launch_mix_probe(const void* in, void* out, size_t out_bytes, hipStream_t stream);
 
 // ---- scoring (Alg. 2: collision counts, sigma = max, A = sum) ---------------
 struct ScoreArgs {

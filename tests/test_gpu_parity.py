@@ -69,6 +69,23 @@ def test_hash_mfma_shapes(d, L, Cb):
     assert np.array_equal(got, codes)
 
 
+@pytest.mark.parametrize("L,Cb,n", [(32, 7, 1_200_001), (32, 3, 70_000), (64, 8, 140_003), (16, 12, 150_000), (32, 9, 140_003)])
+def test_hash_long_runs_several_tiles_per_wave(L, Cb, n):
+    """Runs long enough that a wave of the MFMA kernel loops over several tiles (more than 4096 workgroups x 4 waves x
+    64 vectors in the first case), ragged tail, both code widths."""
+    say(f"hash long run L={L} C={Cb} n={n}")
+    rng = np.random.default_rng(L * 31 + Cb)
+    d = 128
+    X = rng.integers(-127, 128, (n, d)).astype(np.int8)
+    X[::1001] = 0
+    X[n - 1] = -X[0]
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.set_algo(ix, dz.HASH_MFMA, dz.SCORE_AUTO)
+    got = dz.hash(ix, torch.from_numpy(X).to(DEV)).cpu().numpy()
+    assert np.array_equal(got, orc.hash_i8(X, R, L, Cb))
+
+
 def test_hash_scalar_odd_shapes_and_seed_rule():
     say("hash scalar d=50 L=12 C=3 seed-derived projection")
     rng = np.random.default_rng(1)
