@@ -130,8 +130,9 @@ dessert_status_t dessert_set_algo(dessert_index_t *index, int hash_algo, int sco
  *     vectors is the maximum (MAX) or the mean (MEAN) of phi(count / L), with phi(x) = x (IDENTITY),
  *     e^x - 1 (EXPM1) or 1/(1+e^-x) - 1/2 (SIGMOID).  phi is tabulated for the L+1 counts as
  *     round(65536 * phi); the mean of a document of m vectors is the integer (sum + floor(m/2)) / m, 0 for an
- *     empty document; the score is the sum over the query vectors.  Needs |Q| <= 16383.  The MEAN
- *     transforms run on the code-compare kernel only.
+ *     empty document; the score is the sum over the query vectors.  Needs |Q| <= 16383.  MEAN_IDENTITY has a
+ *     mask-table form (L a power of two, documents of at most 65535 vectors: with phi the identity the mean comes
+ *     from sums of collision counts); the other MEAN transforms run on the code-compare kernel only.
  * Applies to later dessert_search / dessert_scores calls. */
 enum {
     DESSERT_SCORE_RAW_COUNTS = 0,

@@ -110,6 +110,7 @@ struct dessert_index {
     const uint8_t* codes = nullptr;
     const uint64_t* offsets = nullptr;
     uint64_t n_docs = 0, n_vectors = 0;
+    uint64_t max_len = 0;   // longest document of the index, in vectors
     bool built = false;
     // pinned staging for the offsets upload
     uint64_t* h_offsets = nullptr;
@@ -420,9 +421,14 @@ dessert_status_t search_impl(dessert_index* ix, const Batch& bt, const void* q_v
     sa.max_scored = bt.max_scored; sa.total_scored = bt.total_scored; sa.n_vectors = ix->n_vectors; sa.scores = scores;
     sa.remap = ix->transform != DESSERT_SCORE_RAW_COUNTS ? ix->remap : nullptr;
     sa.sigma_mean = ix->transform >= DESSERT_SCORE_MEAN_IDENTITY_Q16 ? 1u : 0u;
+    // phi = identity with L a power of two: the table is 65536 / L * count exactly
+    sa.phi_identity = ((ix->transform == DESSERT_SCORE_MEAN_IDENTITY_Q16 || ix->transform == DESSERT_SCORE_MAX_IDENTITY_Q16) &&
+                       (ix->cfg.L & (ix->cfg.L - 1)) == 0) ? 1u : 0u;
     sa.q_weights = ix->q_weights;
     int algo = ix->score_algo;
-    if (algo == DESSERT_SCORE_AUTO && sa.sigma_mean) algo = DESSERT_SCORE_BYTECMP;  // the mean has no mask-table form
+    // sigma = mean has a mask-table form for phi = identity only (sums of counts), and for documents short enough
+    const bool mean_on_masklut = sa.sigma_mean && sa.phi_identity && ix->max_len <= MASKLUT_MEAN_MAX_LEN;
+    if (algo == DESSERT_SCORE_AUTO && sa.sigma_mean && !mean_on_masklut) algo = DESSERT_SCORE_BYTECMP;
     // the mask-table kernel lets idle lanes read code row 0, so it needs a non-empty code array
     if (algo == DESSERT_SCORE_AUTO || ix->n_vectors == 0)
         algo = (score_masklut_supported(ix->cfg.L, ix->cfg.C) && ix->n_vectors) ? DESSERT_SCORE_MASKLUT
@@ -431,7 +437,7 @@ dessert_status_t search_impl(dessert_index* ix, const Batch& bt, const void* q_v
     // grouped by document id range (with fewer than 8 lists the one workgroup per list of the grouping costs more
     // than the scoring gains).  The grouping rides in the hashing launch when that is the int8 MFMA kernel.
     CandOrderArgs oa{};
-    bool grouping = algo == DESSERT_SCORE_MASKLUT && !sa.sigma_mean && score_masklut_supported(ix->cfg.L, ix->cfg.C) &&
+    bool grouping = algo == DESSERT_SCORE_MASKLUT && score_masklut_supported(ix->cfg.L, ix->cfg.C) &&
                     cand_ids && B >= 8 && bt.max_scored >= score_order_min() && order_space(ix, B, bt.total_scored);
     if (grouping) {
         const uint32_t fused_ranges = hash_mfma_fused_ranges(ix->cfg.d, ix->cfg.L, ix->cfg.C);
@@ -445,7 +451,9 @@ dessert_status_t search_impl(dessert_index* ix, const Batch& bt, const void* q_v
     if (grouping) sa.order = oa.order;
     if (timed) { HIP_TRY(hipEventRecord(tsp->ev[1], ix->stream)); tsp->hash = true; }
     if (algo == DESSERT_SCORE_MASKLUT) {
-        if (sa.sigma_mean) return fail(DESSERT_EINVAL, "the MEAN score transforms run on the code-compare kernel only");
+        if (sa.sigma_mean && !mean_on_masklut)
+            return fail(DESSERT_EINVAL, "of the MEAN score transforms only MEAN_IDENTITY has a mask-table form (documents of at "
+                                        "most 65535 vectors); the others run on the code-compare kernel only");
         if (!score_masklut_supported(ix->cfg.L, ix->cfg.C))
             return fail(DESSERT_EINVAL, "mask-table scoring needs L in {8,16,32,64,128} (C <= 8), or L = 8 with C <= 11, "
                                         "L = 16 with C <= 10, L = 32 with C = 9");
@@ -697,8 +705,11 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     if (n_docs && !lengths_host) return fail(DESSERT_EINVAL, "lengths_host is NULL");
     if (n_vectors && (!vectors_dev || !codes_dev)) return fail(DESSERT_EINVAL, "vectors_dev / codes_dev is NULL");
     if (n_docs > 0xFFFFFFFEull) return fail(DESSERT_EINVAL, "document ids are 32-bit: n_docs too large");
-    uint64_t sum = 0;
-    for (uint64_t i = 0; i < n_docs; ++i) sum += lengths_host[i];
+    uint64_t sum = 0, longest = 0;
+    for (uint64_t i = 0; i < n_docs; ++i) {
+        sum += lengths_host[i];
+        if (lengths_host[i] > longest) longest = lengths_host[i];
+    }
     if (sum != n_vectors)
         return fail(DESSERT_EINVAL, "sum of lengths_host (%llu) != n_vectors (%llu)", (unsigned long long)sum,
                     (unsigned long long)n_vectors);
@@ -751,6 +762,7 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     ix->offsets = offsets_dev;
     ix->n_docs = n_docs;
     ix->n_vectors = n_vectors;
+    ix->max_len = longest;
     ix->built = true;
     return DESSERT_OK;
 }

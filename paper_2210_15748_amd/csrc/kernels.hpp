@@ -64,6 +64,8 @@ struct ScoreArgs {
     int32_t* scores;            // out: candidate mode [total_cand], else [B][n_docs]
     const uint32_t* remap;      // dev [L+1] fixed-point phi per collision count (Eq. 1, Sec. 4.1 examples), or nullptr: raw counts
     uint32_t sigma_mean;        // != 0: sigma = rounded mean of remap[count] over the document's vectors (else the max)
+    uint32_t phi_identity;      // != 0: remap[count] = 65536 / L * count exactly (phi = identity and L a power of two); the
+                                // mask-table kernel then forms the mean from sums of counts
     const uint32_t* q_weights;  // dev [total_q] Q16 weights of the outer sum (Sec. 4.2), or nullptr
 };
 // first query vector / first candidate slot of query set b (b may be n_queries: one past the end)
@@ -88,6 +90,8 @@ hipError_t launch_cand_order(const CandOrderArgs& a, hipStream_t stream);  // a.
 hipError_t launch_check_cand_ids(const uint32_t* cand_ids, uint64_t n, uint64_t n_docs, unsigned long long* first_bad,
                                  hipStream_t stream);
 bool score_masklut_supported(uint32_t L, uint32_t C);
+// longest document (in vectors) for which the mask-table kernel can form sigma = mean (32-bit numerators)
+constexpr uint64_t MASKLUT_MEAN_MAX_LEN = 65535;
 hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream, char* desc = nullptr, size_t desc_len = 0);
 
 // ---- candidate filter (Sec. 5 "Filtering") ---------------------------------------------

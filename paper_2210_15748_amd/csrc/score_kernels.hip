@@ -188,6 +188,25 @@ __device__ inline void planes_max(uint32_t* mx, const uint32_t* c) {
     for (int p = 0; p < P; ++p) mx[p] = select3(lt, c[p], mx[p]);
 }
 
+// acc (WA planes) += b (WB planes) per bit position: a ripple of full adders over b's planes, then of half adders
+template <int WA, int WB>
+__device__ inline void planes_add(uint32_t* acc, const uint32_t* b) {
+    static_assert(WB <= WA, "the addend is not wider than the accumulator");
+    uint32_t carry = 0;
+#pragma unroll
+    for (int p = 0; p < WB; ++p) {
+        const uint32_t x = acc[p];
+        acc[p] = xor3(x, b[p], carry);
+        carry = maj3(x, b[p], carry);
+    }
+#pragma unroll
+    for (int p = WB; p < WA; ++p) {
+        const uint32_t x = acc[p];
+        acc[p] = x ^ carry;
+        carry = x & carry;
+    }
+}
+
 template <int CTRL>
 __device__ inline uint32_t dpp_mov(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
@@ -234,7 +253,7 @@ constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
 constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && (L <= 16 || (L << CB) * 4 * W >= 64 * 1024)) ? 512 : 256; }
 // Waves per SIMD the register allocation must allow: the rotated form (L = 64) keeps 24 more per-lane
 // constants and would otherwise drop from 4 to 3.
-constexpr int masklut_min_waves(int L, int CW, int W) { return (L == 64 && CW == 1 && W == 1) ? 4 : 1; }
+constexpr int masklut_min_waves(int L, int CW, int W, int REMAP) { return (L == 64 && CW == 1 && W == 1 && REMAP < 3) ? 4 : 1; }
 constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
 
 // Per-workgroup bookkeeping, in static LDS beside the mask table.
@@ -261,6 +280,12 @@ struct LutBlockMeta {
 // per wave against 5.9 for a 4-byte one, and the code loads and address shifts are shared.
 // REMAP: 1 = apply the fixed-point table a.remap (Eq. 1, or another phi) to each per-query-vector maximum;
 // 2 = and weight the query vectors by a.q_weights (Sec. 4.2); 0 = raw counts.
+// 3 / 4 = sigma is the MEAN over the document's vectors of phi(count / L) with phi the identity (Sec. 4.1, the lemma
+// on sigma = (1/m) sum phi(x_i)), without / with weights: with L a power of two the Q16 table is 65536/L * count exactly,
+// so what is needed per query vector is S = sum_x cnt(q,x).  The count planes of a round (zeroed in lanes that hold no
+// row of the document) are added into a bit-sliced accumulator of P+4 planes, which every 16 rounds is added into one
+// of P+15 planes; the lanes of a document add theirs over DPP, each lane un-slices its share of the query vectors and
+// forms (65536/L * S + floor(m/2)) / m.  Needs documents shorter than 65536 vectors (32-bit numerators).
 // CW = bytes per table code (1: C <= 8, 2: wider codes); CB = bits of a table index (2^CB entries per table).
 // gz = chunk groups: with gz > 1 the 32-vector chunks of a query set are dealt round-robin to gz
 // workgroups, which add their partial sums into the (pre-zeroed) scores with integer atomics.
@@ -288,7 +313,7 @@ __device__ inline uint32_t rot_slot(uint32_t k, uint32_t b) {  // k = (k3 k2 k1 
 }
 
 template <int L, int CB, int CW, int REMAP, int W, bool SPLIT>
-__global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW, W)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
+__global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW, W, REMAP)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
                                                             uint32_t gz_arg) {
     constexpr bool ROT = (L == 64 && CW == 1 && W == 1);
     const uint32_t gz = SPLIT ? gz_arg : 1u;
@@ -298,6 +323,10 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
     constexpr int G = (W == 2 && L <= 32) ? 4 : 8;
     constexpr int DOCS_PER_WAVE = 64 / G;
+    constexpr bool MEAN = REMAP >= 3;
+    constexpr bool WEIGHTED = REMAP == 2 || REMAP == 4;
+    constexpr int P1 = P + 4;    // planes of the 16-round accumulator: 16 * L < 2^(P+4)
+    constexpr int P2 = P + 15;   // planes of the document's accumulator: S <= L * m < 2^(P-1) * 2^16
     // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
     constexpr int LUT_WORDS = L * STRIDE * W;
@@ -469,11 +498,19 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
             const uint64_t lo = m ? meta.lo[doc] : 0;
             const uint32_t last_j = m ? m - 1 : 0;
 
-            uint32_t mx[W][P];
+            uint32_t mx[W][MEAN ? 1 : P];          // running maximum (sigma = max)
+            uint32_t sum1[W][MEAN ? P1 : 1];       // sums of the last few rounds, and of the document (sigma = mean)
+            uint32_t sum2[W][MEAN ? P2 : 1];
+            uint32_t rounds_in_sum1 = 0;
 #pragma unroll
-            for (int w = 0; w < W; ++w)
+            for (int w = 0; w < W; ++w) {
 #pragma unroll
-                for (int p = 0; p < P; ++p) mx[w][p] = 0;
+                for (int p = 0; p < (MEAN ? 1 : P); ++p) mx[w][p] = 0;
+#pragma unroll
+                for (int p = 0; p < (MEAN ? P1 : 1); ++p) sum1[w][p] = 0;
+#pragma unroll
+                for (int p = 0; p < (MEAN ? P2 : 1); ++p) sum2[w][p] = 0;
+            }
 
             // lanes past the end re-read the document's last vector (a repeated vector cannot
             // change the maximum); the next round's codes are requested before this round's
@@ -500,8 +537,9 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
                     dst[0] = v.x; dst[1] = v.y;
                 }
             };
-            // one round: the table reads of this lane's vector, the carry-save count and the running maximum
-            auto process = [&](const uint32_t (&dw)[LW]) {
+            // one round: the table reads of this lane's vector, the carry-save count and the running maximum (or sum).
+            // row = the lane's row of the document in this round before clamping: only rows 0 .. m-1 count towards a sum
+            auto process = [&](const uint32_t (&dw)[LW], int32_t row) {
                 const char* lut_bytes = reinterpret_cast<const char*>(lut);
                 uint32_t off[L];  // byte offset of x's entry within each table
 #pragma unroll
@@ -537,7 +575,25 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
                 for (int w = 0; w < W; ++w) {
                     uint32_t cnt[P];
                     csa_planes<L>(msk[w], cnt);
-                    planes_max<P>(mx[w], cnt);
+                    if constexpr (!MEAN) {
+                        planes_max<P>(mx[w], cnt);
+                    } else {
+                        const uint32_t keep = (row >= 0 && row < (int32_t)m) ? ~0u : 0u;
+#pragma unroll
+                        for (int p = 0; p < P; ++p) cnt[p] &= keep;
+                        planes_add<P1, P>(sum1[w], cnt);
+                    }
+                }
+                if constexpr (MEAN) {
+                    if (++rounds_in_sum1 == 16) {   // the same for every lane of the wave
+                        rounds_in_sum1 = 0;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) {
+                            planes_add<P2, P1>(sum2[w], sum1[w]);
+#pragma unroll
+                            for (int p = 0; p < P1; ++p) sum1[w][p] = 0;
+                        }
+                    }
                 }
             };
             // a round's G rows start on a 128-byte line of the code array (rows before the document's
@@ -556,11 +612,11 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
                 load_codes(clamped(j < 0 ? 0 : j), buf_a);
                 for (;;) {
                     load_codes(clamped(j + G), buf_b);
-                    process(buf_a);
+                    process(buf_a, j);
                     j += G;
                     if (!__any(j < j_end)) break;
                     load_codes(clamped(j + G), buf_a);
-                    process(buf_b);
+                    process(buf_b, j);
                     j += G;
                     if (!__any(j < j_end)) break;
                 }
@@ -570,44 +626,46 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
                 load_codes(clamped(j + G), buf_b);
                 for (;;) {
                     load_codes(clamped(j + 2 * G), buf_c);
-                    process(buf_a);
+                    process(buf_a, j);
                     j += G;
                     if (!__any(j < j_end)) break;
                     load_codes(clamped(j + 2 * G), buf_a);
-                    process(buf_b);
+                    process(buf_b, j);
                     j += G;
                     if (!__any(j < j_end)) break;
                     load_codes(clamped(j + 2 * G), buf_b);
-                    process(buf_c);
+                    process(buf_c, j);
                     j += G;
                     if (!__any(j < j_end)) break;
                 }
             }
 #pragma unroll
             for (int w = 0; w < W; ++w) {
-                if (m == 0) {  // empty document: the maximum over nothing is 0
+                int32_t score = 0;
+                if constexpr (!MEAN) {
+                    if (m == 0) {  // empty document: the maximum over nothing is 0
 #pragma unroll
-                    for (int p = 0; p < P; ++p) mx[w][p] = 0;
-                }
-                // merge the G lanes of a document: (G = 8) mirror within the half row, then the two
-                // quad exchanges
-                uint32_t o[P];
-                if constexpr (G == 8) {
+                        for (int p = 0; p < P; ++p) mx[w][p] = 0;
+                    }
+                    // merge the G lanes of a document: (G = 8) mirror within the half row, then the two
+                    // quad exchanges
+                    uint32_t o[P];
+                    if constexpr (G == 8) {
 #pragma unroll
-                    for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[w][p]);  // row_half_mirror
+                        for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x141>(mx[w][p]);  // row_half_mirror
+                        planes_max<P>(mx[w], o);
+                    }
+#pragma unroll
+                    for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[w][p]);   // quad_perm [1,0,3,2]
+                    planes_max<P>(mx[w], o);
+#pragma unroll
+                    for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[w][p]);   // quad_perm [2,3,0,1]
                     planes_max<P>(mx[w], o);
                 }
-#pragma unroll
-                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0xB1>(mx[w][p]);   // quad_perm [1,0,3,2]
-                planes_max<P>(mx[w], o);
-#pragma unroll
-                for (int p = 0; p < P; ++p) o[p] = dpp_mov<0x4E>(mx[w][p]);   // quad_perm [2,3,0,1]
-                planes_max<P>(mx[w], o);
-                int32_t score = 0;
-                if constexpr (!REMAP) {
+                if constexpr (REMAP == 0) {
 #pragma unroll
                     for (int p = P - 1; p >= 0; --p) score = 2 * score + __builtin_popcount(mx[w][p]);
-                } else {
+                } else if constexpr (!MEAN) {
                     // similarity remap (Eq. 1 as a table of L+1 fixed-point values): every lane of
                     // the group holds the merged maxima; lane `sub` un-slices query vectors sub,
                     // sub+8, sub+16, sub+24, looks their maxima up, and the eight partial sums are
@@ -620,13 +678,50 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
 #pragma unroll
                         for (int p = P - 1; p >= 0; --p) v = 2 * v + ((mx[w][p] >> q) & 1u);
                         uint32_t term = a.remap[v];  // remap[0] = 0, and absent query vectors have maximum 0
-                        if (REMAP == 2 && c0 + q < q_len[w])
+                        if (WEIGHTED && c0 + q < q_len[w])
                             term = (uint32_t)(((uint64_t)a.q_weights[q_lo[w] + c0 + q] * term + 32768) >> 16);
                         part += term;
                     }
                     if constexpr (G == 8) part += dpp_mov<0x141>(part);  // row_half_mirror
                     part += dpp_mov<0xB1>(part);   // quad_perm [1,0,3,2]
                     part += dpp_mov<0x4E>(part);   // quad_perm [2,3,0,1]
+                    score = (int32_t)part;
+                } else {
+                    // sigma = mean of count / L: the document's sums S(q) = sum_x cnt(q,x), first this lane's
+                    // (what is left in the 16-round accumulator joins the document's), then the G lanes' by
+                    // bit-sliced additions over the same lane exchanges as above
+                    planes_add<P2, P1>(sum2[w], sum1[w]);
+                    uint32_t o[P2];
+                    if constexpr (G == 8) {
+#pragma unroll
+                        for (int p = 0; p < P2; ++p) o[p] = dpp_mov<0x141>(sum2[w][p]);
+                        planes_add<P2, P2>(sum2[w], o);
+                    }
+#pragma unroll
+                    for (int p = 0; p < P2; ++p) o[p] = dpp_mov<0xB1>(sum2[w][p]);
+                    planes_add<P2, P2>(sum2[w], o);
+#pragma unroll
+                    for (int p = 0; p < P2; ++p) o[p] = dpp_mov<0x4E>(sum2[w][p]);
+                    planes_add<P2, P2>(sum2[w], o);
+                    // 65536 / L is a power of two: phi(S / (m L)) summed over the vectors = S << (16 - log2 L), below 2^32
+                    // for documents shorter than 65536 vectors; the mean is that over m, rounded half up, 0 if m = 0
+                    constexpr int SH = 16 - (P - 1);
+                    static_assert((1 << (P - 1)) == L, "L is a power of two");
+                    uint32_t part = 0;
+#pragma unroll
+                    for (int jq = 0; jq < 32 / G; ++jq) {
+                        const uint32_t q = sub + G * jq;
+                        uint32_t v = 0;
+#pragma unroll
+                        for (int p = P2 - 1; p >= 0; --p) v = 2 * v + ((sum2[w][p] >> q) & 1u);
+                        uint32_t term = m ? ((v << SH) + m / 2) / m : 0u;
+                        if (WEIGHTED && c0 + q < q_len[w])
+                            term = (uint32_t)(((uint64_t)a.q_weights[q_lo[w] + c0 + q] * term + 32768) >> 16);
+                        part += term;
+                    }
+                    if constexpr (G == 8) part += dpp_mov<0x141>(part);
+                    part += dpp_mov<0xB1>(part);
+                    part += dpp_mov<0x4E>(part);
                     score = (int32_t)part;
                 }
                 if (valid && sub == 0 && b0 + w < a.n_queries && c0 < q_len[w]) {
@@ -723,7 +818,7 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
     // two query sets per workgroup when every document is scored for every set and the paired
     // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
     constexpr bool PAIR_OK = (size_t)L * (1u << CB) * 8 <= 32 * 1024;
-    bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2;
+    bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2 && !a.sigma_mean;  // the mean form takes one set per workgroup
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
     // workgroups, but at least 64 (32 = one run of 8 documents for each of the four waves when the
     // documents are long: about 4096 vectors per workgroup keep the table build amortised)
@@ -766,30 +861,36 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
             gy_linear = (uint32_t)gyz;
         }
     }
+    // transform form of the kernel: raw counts, tabulated phi of the maximum (weighted or not), mean of the counts
+    const int remap = a.sigma_mean ? (a.q_weights ? 4 : 3) : a.q_weights ? 2 : a.remap ? 1 : 0;
     // the instantiation as a profiler prints it
     if (desc)
-        snprintf(desc, desc_len, "score_masklut_kernel<%d, %d, %d, %d, %d, %s>", L, CB, CW, a.q_weights ? 2 : a.remap ? 1 : 0,
-                 pair ? 2 : 1, gz > 1 ? "true" : "false");
+        snprintf(desc, desc_len, "score_masklut_kernel<%d, %d, %d, %d, %d, %s>", L, CB, CW, remap, pair ? 2 : 1,
+                 gz > 1 ? "true" : "false");
+    using Kernel = void (*)(ScoreArgs, uint32_t, uint32_t, uint32_t);
     if constexpr (PAIR_OK) {
         if (pair) {
-            auto kern2 = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 2, false>
-                         : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 2, false>
-                                     : score_masklut_kernel<L, CB, CW, 0, 2, false>;
+            const Kernel kern2 = remap == 2   ? score_masklut_kernel<L, CB, CW, 2, 2, false>
+                                 : remap == 1 ? score_masklut_kernel<L, CB, CW, 1, 2, false>
+                                              : score_masklut_kernel<L, CB, CW, 0, 2, false>;
             hipLaunchKernelGGL(kern2, grid, dim3(masklut_threads(L, CB, 2)), 0, stream, a, dpb, gy_linear, 1u);
             return hipGetLastError();
         }
     }
-    if (gz > 1) {
-        auto kern = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 1, true>
-                    : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 1, true>
-                                : score_masklut_kernel<L, CB, CW, 0, 1, true>;
-        hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, gz);
-        return hipGetLastError();
-    }
-    auto kern = a.q_weights ? score_masklut_kernel<L, CB, CW, 2, 1, false>
-                : a.remap   ? score_masklut_kernel<L, CB, CW, 1, 1, false>
+    Kernel kern;
+    if (gz > 1)
+        kern = remap == 4   ? score_masklut_kernel<L, CB, CW, 4, 1, true>
+               : remap == 3 ? score_masklut_kernel<L, CB, CW, 3, 1, true>
+               : remap == 2 ? score_masklut_kernel<L, CB, CW, 2, 1, true>
+               : remap == 1 ? score_masklut_kernel<L, CB, CW, 1, 1, true>
+                            : score_masklut_kernel<L, CB, CW, 0, 1, true>;
+    else
+        kern = remap == 4   ? score_masklut_kernel<L, CB, CW, 4, 1, false>
+               : remap == 3 ? score_masklut_kernel<L, CB, CW, 3, 1, false>
+               : remap == 2 ? score_masklut_kernel<L, CB, CW, 2, 1, false>
+               : remap == 1 ? score_masklut_kernel<L, CB, CW, 1, 1, false>
                             : score_masklut_kernel<L, CB, CW, 0, 1, false>;
-    hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, 1u);
+    hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, gz);
     return hipGetLastError();
 }
 
@@ -797,7 +898,8 @@ hipError_t launch_score_masklut(const ScoreArgs& a, hipStream_t stream, char* de
     if (desc && desc_len) desc[0] = 0;
     if (a.n_queries == 0 || a.max_scored == 0) return hipSuccess;
     if (!score_masklut_supported(a.L, a.C) || a.code_bytes != (a.C > 8 ? 2u : 1u)) return hipErrorInvalidValue;
-    if (a.sigma_mean || (a.q_weights && !a.remap)) return hipErrorInvalidValue;  // max of a tabulated phi only
+    // a tabulated phi of the maximum, or the mean of the counts themselves (phi = identity)
+    if ((a.sigma_mean && !a.phi_identity) || (a.q_weights && !a.remap)) return hipErrorInvalidValue;
     const uint32_t cb = a.C <= 6 ? 6 : a.C;
 #define DESSERT_LUT_CASE(L_, CB_, CW_) \
     if (a.L == L_ && cb == CB_) return launch_masklut_t<L_, CB_, CW_>(a, stream, desc, desc_len);

@@ -46,8 +46,8 @@ def build_case(seed, d, L, Cb):
                                        (12, 5, dz.SCORE_AUTO), (64, 8, dz.SCORE_AUTO), (16, 3, dz.SCORE_MASKLUT)])
 def test_aggregations_match_oracle(transform, weighted, L, Cb, algo):
     phi, sigma = KINDS[transform]
-    if algo == dz.SCORE_MASKLUT and sigma == orc.SIGMA_MEAN:
-        pytest.skip("the mean runs on the code-compare kernel only (checked as an error below)")
+    if algo == dz.SCORE_MASKLUT and sigma == orc.SIGMA_MEAN and phi != orc.PHI_IDENTITY:
+        pytest.skip("of the means only phi = identity has a mask-table form (the others are checked as an error below)")
     say(f"aggregation transform={transform} weighted={weighted} L={L} C={Cb} algo={algo}")
     rng, lens, X, q_lens, Q, R = build_case(L * 100 + Cb + transform, 64, L, Cb)
     ix = dz.create(64, L, Cb, proj=torch.from_numpy(R).to(DEV))
@@ -62,10 +62,12 @@ def test_aggregations_match_oracle(transform, weighted, L, Cb, algo):
         w = rng.integers(0, 65537, Q.shape[0]).astype(np.uint32)
         w[:3] = [65536, 0, 1]
         dz.set_query_weights(ix, torch.from_numpy(w.view(np.int32)).to(DEV))
+    want_masklut = algo != dz.SCORE_BYTECMP and (L, Cb) != (12, 5) and (sigma == orc.SIGMA_MAX or phi == orc.PHI_IDENTITY)
     ref = lambda b, sel=None: orc.scores_general(dc, off, qc[qo[b]:qo[b + 1]], phi, sigma, weights=None if w is None else w[qo[b]:qo[b + 1]],
                                                  doc_ids=sel, eq1_C=Cb)
     Qd = torch.from_numpy(Q).to(DEV)
     got = dz.scores(ix, Qd, q_lens).cpu().numpy()
+    assert dz.last_score_kernel(ix).startswith("score_masklut_kernel" if want_masklut else "score_bytecmp_kernel"), dz.last_score_kernel(ix)
     for b in range(len(q_lens)):
         assert np.array_equal(got[b], ref(b)), b
     # candidate lists with an empty slot, then top-k

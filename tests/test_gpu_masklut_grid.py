@@ -5,7 +5,7 @@ loops) plus L = 8 and the 16-bit code shapes, each as
   pair    every document for a batch of three query sets (two sets per workgroup where the paired table fits);
   split   query sets longer than 32 vectors on a small grid (their 32-vector chunks dealt to several workgroups);
   chunks  query sets longer than 32 vectors on a grid large enough that one workgroup takes all chunks;
-with raw counts, the Eq. 1 remap and a weighted sum of a tabulated phi.  Every test also asserts which
+with raw counts, the Eq. 1 remap, a weighted sum of a tabulated phi, and the mean of count / L plain and weighted.  Every test also asserts which
 instantiation the launch picked."""
 import re
 import sys
@@ -45,8 +45,12 @@ def make_reference(form, dc, off, Cb):
         return dz.SCORE_RAW_COUNTS, False, lambda q, w, sel: orc.scores(dc, off, q, sel)
     if form == "eq1":
         return dz.SCORE_EQ1_Q16, False, lambda q, w, sel: orc.scores_eq1(dc, off, q, Cb, sel)
-    return dz.SCORE_MAX_SIGMOID_Q16, True, lambda q, w, sel: orc.scores_general(dc, off, q, orc.PHI_SIGMOID, orc.SIGMA_MAX,
-                                                                                  weights=w, doc_ids=sel)
+    if form == "weighted":
+        return dz.SCORE_MAX_SIGMOID_Q16, True, lambda q, w, sel: orc.scores_general(dc, off, q, orc.PHI_SIGMOID, orc.SIGMA_MAX,
+                                                                                      weights=w, doc_ids=sel)
+    # sigma = mean of count / L (Sec. 4.1), plain and weighted
+    return dz.SCORE_MEAN_IDENTITY_Q16, form == "mean_weighted", lambda q, w, sel: orc.scores_general(
+        dc, off, q, orc.PHI_IDENTITY, orc.SIGMA_MEAN, weights=w, doc_ids=sel)
 
 
 def launched(ix):
@@ -55,7 +59,7 @@ def launched(ix):
     return tuple(int(x) for x in m.groups()[:5]) + (m.group(6) == "true",)
 
 
-@pytest.mark.parametrize("form", ["raw", "eq1", "weighted"])
+@pytest.mark.parametrize("form", ["raw", "eq1", "weighted", "mean", "mean_weighted"])
 @pytest.mark.parametrize("mode", ["cand", "pair", "split"])
 @pytest.mark.parametrize("L,Cb", NARROW + WIDE)
 def test_masklut_instantiation_matches_oracle(L, Cb, mode, form):
@@ -87,7 +91,7 @@ def test_masklut_instantiation_matches_oracle(L, Cb, mode, form):
         dz.set_query_weights(ix, torch.from_numpy(w.view(np.int32)).to(DEV))
     wq = lambda b: None if w is None else w[qo[b]:qo[b + 1]]
     Qd = torch.from_numpy(Q).to(DEV)
-    want_remap = {"raw": 0, "eq1": 1, "weighted": 2}[form]
+    want_remap = {"raw": 0, "eq1": 1, "weighted": 2, "mean": 3, "mean_weighted": 4}[form]
     cb = max(Cb, 6)
     some = False
     if mode in ("pair", "split"):                    # every document for every query set
@@ -95,7 +99,7 @@ def test_masklut_instantiation_matches_oracle(L, Cb, mode, form):
         kl = launched(ix)
         assert kl[:4] == (L, cb, 2 if Cb > 8 else 1, want_remap), kl
         if mode == "pair":
-            assert kl[4:] == (2 if pair_ok(L, Cb) else 1, False), kl
+            assert kl[4:] == (2 if pair_ok(L, Cb) and want_remap < 3 else 1, False), kl
         else:
             assert kl[4:] == (1, True), kl
         for b in range(len(q_lens)):
