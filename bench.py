@@ -294,20 +294,17 @@ def main() -> int:
         f_query_ms, (f_ids, f_cnt) = ev_ms(lambda: dz.filter_query(ix, w.queries, ql, f_probe, f_k), 10)
         f_cand = f_ids.view(torch.int32)
 
-        def chain(qv, qlen):   # filter, then search on the filter's ids; workspaces and outputs allocated once, as a serving loop would
+        def chain(qv, qlen):   # filter, then search among the filter's ids, in one call; workspace and outputs allocated once, as a serving loop would
             nb = len(qlen)
-            f_ws = torch.empty(int(dz.lib().dessert_filter_workspace_bytes(ix.handle, nb, qv.shape[0], int(max(qlen)), f_probe)),
+            c_ws = torch.empty(int(dz.lib().dessert_filter_search_workspace_bytes(ix.handle, nb, qv.shape[0], int(max(qlen)), f_probe, f_k, k)),
                                dtype=torch.uint8, device=dev)
-            s_ws = torch.empty(dz.workspace_bytes(ix, nb, qv.shape[0], nb * f_k, k), dtype=torch.uint8, device=dev)
             o_ids = torch.empty(nb, k, dtype=torch.uint32, device=dev)
             o_sc = torch.empty(nb, k, dtype=torch.int32, device=dev)
-            c_off = np.arange(nb + 1, dtype=np.uint64) * f_k
-            return lambda: dz.search(ix, qv, qlen, k, cand_ids=dz.filter_query(ix, qv, qlen, f_probe, f_k, workspace=f_ws)[0].view(torch.int32),
-                                     cand_offsets=c_off, workspace=s_ws, out_ids=o_ids, out_scores=o_sc)
+            return lambda: dz.filter_search(ix, qv, qlen, f_probe, f_k, k, workspace=c_ws, out_ids=o_ids, out_scores=o_sc)
         chain_ms, _ = ev_ms(chain(w.queries, ql), 10)
         # one query set at a time (the paper's tables quote latency per query): same chain, batch of 1
         q1, ql1 = w.queries[: p.q_len].contiguous(), ql[:1]
-        one_ms, _ = ev_ms(chain(q1, ql1), 50)
+        one_ms, _ = ev_ms(chain(q1, ql1), 200)
         kept = float(np.mean([len(set(w.planted[b].tolist()) & set(f_ids[b].cpu().tolist())) for b in range(0, B, 8)]))
         gemm_ops = 2.0 * w.n_vectors * Kc * p.d
         filt = {"n_centroids": Kc,

@@ -28,7 +28,7 @@
  *     without synchronising.  Host arrays are read before the call returns.
  *     Outputs are valid once the caller has synchronised the stream.  Calls
  *     on a stream that is being captured into a HIP graph: dessert_search,
- *     dessert_scores, dessert_search_noalloc and dessert_filter_query record
+ *     dessert_scores, dessert_search_noalloc, dessert_filter_query and dessert_filter_search record
  *     a fixed sequence of kernel launches when all query sets of the batch
  *     have the same length and all candidate lists have the same length; with
  *     unequal lengths (their offset arrays would be uploaded from a staging
@@ -285,6 +285,19 @@ dessert_status_t dessert_filter_query(const dessert_index_t *index, const void *
                                       const uint32_t *q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
                                       uint32_t filter_k, void *workspace_dev, size_t workspace_bytes,
                                       uint32_t *out_ids_dev, int32_t *out_counts_dev);
+
+/* The paper's whole query (Sec. 5: filter the collection down to filter_k candidate documents per query set, score
+ * those with Alg. 2, return the k best) in one call: dessert_filter_query followed by dessert_search on its ids, with the
+ * same results as the two calls.  Between the two steps only the SET of candidates matters, so the filter leaves out the
+ * ordering of its filter_k documents (a fifth of its time for one query set).  workspace_dev: dev, 256-byte aligned,
+ * dessert_filter_search_workspace_bytes(...) bytes (0 before dessert_filter_build); it also holds the candidate lists.
+ * out_ids_dev / out_scores_dev: dev, out, [n_queries][k], as dessert_search. */
+size_t dessert_filter_search_workspace_bytes(const dessert_index_t *index, uint32_t n_queries, uint64_t total_q_vectors,
+                                             uint32_t max_q_len, uint32_t filter_probe, uint32_t filter_k, uint32_t k);
+dessert_status_t dessert_filter_search(const dessert_index_t *index, const void *q_vectors_dev,
+                                       const uint32_t *q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
+                                       uint32_t filter_k, uint32_t k, void *workspace_dev, size_t workspace_bytes,
+                                       uint32_t *out_ids_dev, int32_t *out_scores_dev);
 
 /* Per-kernel timing of dessert_search / dessert_scores / dessert_build_index
  * calls on this handle, measured with HIP events recorded on config.stream

@@ -40,6 +40,7 @@ EXPORTS = [
     "dessert_noalloc_scratch_bytes", "dessert_search_noalloc", "dessert_set_debug", "dessert_last_score_kernel",
     "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
+    "dessert_filter_search_workspace_bytes", "dessert_filter_search",
     "dessert_enable_timing", "dessert_get_timing", "dessert_probe_read_bandwidth", "dessert_probe_mix_bandwidth", "dessert_last_error",
     "dessert_version",
 ]
@@ -98,6 +99,9 @@ def lib() -> C.CDLL:
     l.dessert_filter_workspace_bytes.argtypes = [vp, u32, u64, u32, u32]
     l.dessert_filter_workspace_bytes.restype = sz
     l.dessert_filter_query.argtypes = [vp, vp, vp, u32, u32, u32, vp, sz, vp, vp]
+    l.dessert_filter_search_workspace_bytes.argtypes = [vp, u32, u64, u32, u32, u32, u32]
+    l.dessert_filter_search_workspace_bytes.restype = sz
+    l.dessert_filter_search.argtypes = [vp, vp, vp, u32, u32, u32, u32, vp, sz, vp, vp]
     l.dessert_enable_timing.argtypes = [vp, C.c_int]
     l.dessert_get_timing.argtypes = [vp, u32, C.POINTER(C.c_float)]
     l.dessert_probe_read_bandwidth.argtypes = [vp, sz, C.c_int, vp, C.c_int, C.POINTER(C.c_float)]
@@ -387,6 +391,28 @@ def filter_query(ix: Index, q_vectors: torch.Tensor, q_lengths, filter_probe: in
     _check(lib().dessert_filter_query(ix.handle, q_vectors.data_ptr(), ql.ctypes.data, B, filter_probe, filter_k,
                                       workspace.data_ptr(), workspace.numel(), ids.data_ptr(), counts.data_ptr()))
     return ids, counts
+
+
+def filter_search(ix: Index, q_vectors: torch.Tensor, q_lengths, filter_probe: int, filter_k: int, k: int,
+                  workspace: Optional[torch.Tensor] = None, out_ids: Optional[torch.Tensor] = None,
+                  out_scores: Optional[torch.Tensor] = None):
+    """dessert_filter_search: filter, then search among the filter's candidates.  Returns (ids [B, k] uint32, scores [B, k] int32)."""
+    q_vectors = _check_vectors(ix, q_vectors)
+    ql = _host_u32(q_lengths)
+    B = ql.shape[0]
+    if int(ql.sum()) != q_vectors.shape[0]:
+        raise ValueError("sum(q_lengths) != number of query vectors")
+    if workspace is None:
+        nbytes = int(lib().dessert_filter_search_workspace_bytes(ix.handle, B, q_vectors.shape[0], int(ql.max()) if B else 0,
+                                                                 filter_probe, filter_k, k))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=ix.device)
+    if out_ids is None:
+        out_ids = torch.empty(B, k, dtype=torch.uint32, device=ix.device)
+    if out_scores is None:
+        out_scores = torch.empty(B, k, dtype=torch.int32, device=ix.device)
+    _check(lib().dessert_filter_search(ix.handle, q_vectors.data_ptr(), ql.ctypes.data, B, filter_probe, filter_k, k,
+                                       workspace.data_ptr(), workspace.numel(), out_ids.data_ptr(), out_scores.data_ptr()))
+    return out_ids, out_scores
 
 
 def enable_timing(ix: Index, enable=True) -> None:

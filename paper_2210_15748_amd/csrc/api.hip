@@ -963,10 +963,13 @@ size_t dessert_filter_workspace_bytes(const dessert_index_t* ix, uint32_t n_quer
     return carve_filter(ix, n_queries, total_q_vectors, max_q_len, filter_probe).total;
 }
 
-dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_vectors_dev,
-                                      const uint32_t* q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
-                                      uint32_t filter_k, void* workspace_dev, size_t workspace_bytes,
-                                      uint32_t* out_ids_dev, int32_t* out_counts_dev) {
+namespace {
+// Body of dessert_filter_query.  ordered = false: the filter_k documents of a query set are written in no particular
+// order (dessert_filter_search only needs the set).
+dessert_status_t filter_query_impl(const dessert_index_t* cix, const void* q_vectors_dev,
+                                   const uint32_t* q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
+                                   uint32_t filter_k, void* workspace_dev, size_t workspace_bytes,
+                                   uint32_t* out_ids_dev, int32_t* out_counts_dev, bool ordered) {
     dessert_index* ix = const_cast<dessert_index*>(cix);
     if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
     if (!ix->f_built) return fail(DESSERT_ESTATE, "dessert_filter_build has not been called");
@@ -1023,8 +1026,80 @@ dessert_status_t dessert_filter_query(const dessert_index_t* cix, const void* q_
     const FilterHistPlan hp = filter_hist_plan(n_queries, max_q * filter_probe, ix->n_docs, ix->f_sub);
     HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
                               ix->n_docs ? ix->n_docs - 1 : 0, (ix->n_docs && total_q) ? &hp : nullptr, out_ids_dev,
-                              out_counts_dev, ix->stream));
+                              out_counts_dev, ordered, ix->stream));
     return DESSERT_OK;
+}
+
+// Workspace of dessert_filter_search: the filter's, the search's, and the candidate lists between them.
+struct ChainWorkspace {
+    size_t filter, filter_bytes, ids, counts, search, search_bytes, total;
+};
+ChainWorkspace carve_chain(const dessert_index* ix, uint32_t B, uint64_t total_q, uint32_t max_q, uint32_t probe,
+                           uint32_t filter_k, uint32_t k) {
+    ChainWorkspace w{};
+    size_t p = 0;
+    w.filter_bytes = carve_filter(ix, B, total_q, max_q, probe).total;
+    w.filter = p;  p += align_up(w.filter_bytes, 256);
+    w.ids = p;     p += align_up((size_t)B * filter_k * 4, 256);
+    w.counts = p;  p += align_up((size_t)B * filter_k * 4, 256);
+    const uint64_t scored = (uint64_t)B * filter_k;
+    w.search_bytes = carve(ix, B, total_q, scored, filter_k, k, true).total;
+    w.search = p;  p += align_up(w.search_bytes, 256);
+    w.total = p;
+    return w;
+}
+}  // namespace
+
+dessert_status_t dessert_filter_query(const dessert_index_t* ix, const void* q_vectors_dev,
+                                      const uint32_t* q_lengths_host, uint32_t n_queries, uint32_t filter_probe,
+                                      uint32_t filter_k, void* workspace_dev, size_t workspace_bytes,
+                                      uint32_t* out_ids_dev, int32_t* out_counts_dev) {
+    return filter_query_impl(ix, q_vectors_dev, q_lengths_host, n_queries, filter_probe, filter_k, workspace_dev,
+                             workspace_bytes, out_ids_dev, out_counts_dev, true);
+}
+
+size_t dessert_filter_search_workspace_bytes(const dessert_index_t* ix, uint32_t n_queries, uint64_t total_q_vectors,
+                                             uint32_t max_q_len, uint32_t filter_probe, uint32_t filter_k, uint32_t k) {
+    if (!ix || !ix->f_built || !ix->built) return 0;
+    return carve_chain(ix, n_queries, total_q_vectors, max_q_len, filter_probe, filter_k, k).total;
+}
+
+dessert_status_t dessert_filter_search(const dessert_index_t* ix, const void* q_vectors_dev, const uint32_t* q_lengths_host,
+                                       uint32_t n_queries, uint32_t filter_probe, uint32_t filter_k, uint32_t k,
+                                       void* workspace_dev, size_t workspace_bytes, uint32_t* out_ids_dev,
+                                       int32_t* out_scores_dev) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!ix->f_built) return fail(DESSERT_ESTATE, "dessert_filter_build has not been called");
+    if (k == 0 || k > 16384) return fail(DESSERT_EINVAL, "k must be in 1..16384, got %u", k);
+    if (filter_k == 0 || filter_k > 16384) return fail(DESSERT_EINVAL, "filter_k must be in 1..16384, got %u", filter_k);
+    if (filter_probe == 0 || filter_probe > ix->f_K || filter_probe > 1024)
+        return fail(DESSERT_EINVAL, "filter_probe must be in 1..min(n_centroids, 1024), got %u", filter_probe);
+    if (n_queries == 0) return DESSERT_OK;
+    if (!q_lengths_host || !workspace_dev || !out_ids_dev || !out_scores_dev) return fail(DESSERT_EINVAL, "NULL argument");
+    if ((uintptr_t)workspace_dev % 256) return fail(DESSERT_EINVAL, "workspace_dev must be 256-byte aligned");
+    uint64_t total_q = 0;
+    uint32_t max_q = 0;
+    for (uint32_t b = 0; b < n_queries && b < 65536; ++b) {
+        total_q += q_lengths_host[b];
+        if (q_lengths_host[b] > max_q) max_q = q_lengths_host[b];
+    }
+    const ChainWorkspace w = carve_chain(ix, n_queries, total_q, max_q, filter_probe, filter_k, k);
+    if (workspace_bytes < w.total)
+        return fail(DESSERT_EINVAL, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, w.total);
+    char* ws = (char*)workspace_dev;
+    uint32_t* cand = (uint32_t*)(ws + w.ids);
+    // the candidates go straight into the scoring, which does not care about their order: the filter skips its sort
+    dessert_status_t st = filter_query_impl(ix, q_vectors_dev, q_lengths_host, n_queries, filter_probe, filter_k, ws + w.filter,
+                                            w.filter_bytes, cand, (int32_t*)(ws + w.counts), false);
+    if (st != DESSERT_OK) return st;
+    // lists of equal length filter_k (unused slots hold 0xFFFFFFFF, which the scoring marks -1 and the top-k skips)
+    Batch bt;
+    st = check_batch(ix, q_vectors_dev, q_lengths_host, n_queries, nullptr, nullptr, &bt);
+    if (st != DESSERT_OK) return st;
+    bt.max_scored = bt.cand_uniform = filter_k;
+    bt.total_scored = (uint64_t)n_queries * filter_k;
+    return search_impl(const_cast<dessert_index*>(ix), bt, q_vectors_dev, n_queries, cand, nullptr, k, ws + w.search,
+                       w.search_bytes, nullptr, out_ids_dev, out_scores_dev);
 }
 
 dessert_status_t dessert_enable_timing(dessert_index_t* ix, int enable) {

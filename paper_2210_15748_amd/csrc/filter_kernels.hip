@@ -723,7 +723,10 @@ FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe) {
     const uint64_t blocks = (n + 128 * pl.nt - 1) / (128 * pl.nt);
     uint64_t want = (2048 + blocks - 1) / blocks;  // aim at ~2048 workgroups
     if (want > groups) want = groups;
-    if (want > 64) want = 64;
+    // a few query vectors alone (one query set): the launch is a chain of global -> LDS stages per workgroup, so more,
+    // shorter ranges cut its latency; the merge of a vector's lists is wave-wide for one probe, a thread's loop otherwise
+    const uint64_t cap = blocks <= 4 ? (probe == 1 ? 512 : 128) : 64;
+    if (want > cap) want = cap;
     if (want < 1) want = 1;
     const uint32_t per = (groups + (uint32_t)want - 1) / (uint32_t)want;
     pl.tiles_per_range = per * FILTER_TG;

@@ -178,9 +178,10 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 // lists must be 16-byte aligned and list_stride a multiple of 4 (the lists are read 16 bytes at a time).
 // hp: nullptr, or the plan by which launch_filter_count laid out its histograms behind the counts (counts = the
 // start of that array): the selection then skips its first pass over a list and, with rows, decides the id digits
-// inside one slab's run.
+// inside one slab's run.  ordered = false: the k best of a list are written in no particular order (their set is
+// the same; saves the sort when only the set matters).
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
                              uint32_t k, uint32_t max_score, uint64_t max_id, const FilterHistPlan* hp, uint32_t* out_ids,
-                             int32_t* out_scores, hipStream_t stream);
+                             int32_t* out_scores, bool ordered, hipStream_t stream);
 
 }  // namespace dessert

@@ -827,6 +827,9 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
     const uint32_t wave_docs = masklut_threads(L, CB, pair ? 2 : 1) / 64 * 8;  // one run of 8 documents per wave
     uint32_t dpb_min = wave_docs > 64 ? wave_docs : 64;
     while (dpb_min > wave_docs && (uint64_t)(dpb_min / 2) * mean_len >= 4096) dpb_min /= 2;
+    // a single short list (one query set's candidates): even 64 documents per workgroup leave most CUs idle and the launch
+    // is a chain of memory round trips per workgroup, so one run of documents per wave
+    if (((a.max_scored + 63) / 64) * gy < 256) dpb_min = wave_docs;
     // candidate lists are gathered from all over the code array and the kernel is bound by those reads:
     // smaller workgroups (their start-up phases overlap better) measure faster as long as the table is small
     uint32_t dpb = (a.cand_ids && (size_t)L * (1u << CB) * 4 <= 16 * 1024) ? LUT_DOCS / 2 : LUT_DOCS;

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_merge_kernel(TopkArgs a, Ke
 // one workgroup per stored list whose length is read from device memory.  There are only as many workgroups
 // as lists, so each is wide and keeps many loads in flight: a pass over a list is a few round trips.
 constexpr uint32_t TOPK_LIST_THREADS = 1024;
-template <typename KT>  // stored key type: uint64_t, or uint32_t when keys_fit_32
+template <typename KT, bool ORDERED>  // stored key type: uint64_t, or uint32_t when keys_fit_32; ORDERED: best first, else any order
 __global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT* __restrict__ lists, uint64_t list_stride,
                                                                        const uint32_t* __restrict__ counts, uint32_t k,
                                                                        KeyPlan plan, uint32_t kpad, uint32_t* __restrict__ out_ids,
@@ -82,10 +82,10 @@ __global__ __launch_bounds__(TOPK_LIST_THREADS) void topk_lists_kernel(const KT*
     const SlabDirectory* dir = segs ? &directory : nullptr;
     if constexpr (sizeof(KT) == 8) {
         StoredKeysPairs keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeysPairs, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
+        block_select<TOPK_LIST_THREADS, StoredKeysPairs, 8, false, ORDERED>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
     } else {
         StoredKeys32 keys{lists + (size_t)b * list_stride};
-        block_select<TOPK_LIST_THREADS, StoredKeys32, 8>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
+        block_select<TOPK_LIST_THREADS, StoredKeys32, 8, false, ORDERED>(keys, counts[b], k, kpad, sorted, sh, plan, first_hist, dir);
     }
     for (uint32_t i = threadIdx.x; i < k; i += TOPK_LIST_THREADS)
         write_result(sorted[i], plan.id_bits, out_ids + (size_t)b * k + i, out_scores + (size_t)b * k + i);
@@ -98,16 +98,21 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint64_t>,
+    static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint64_t, true>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    static hipError_t a4 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint32_t>,
+    static hipError_t a4 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint32_t, true>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    return a0 != hipSuccess ? a0 : a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4;
+    static hipError_t a5 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint64_t, false>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a6 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint32_t, false>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    return a0 != hipSuccess ? a0 : a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4 != hipSuccess ? a4
+           : a5 != hipSuccess ? a5 : a6;
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
                              uint32_t k, uint32_t max_score, uint64_t max_id, const FilterHistPlan* hp, uint32_t* out_ids,
-                             int32_t* out_scores, hipStream_t stream) {
+                             int32_t* out_scores, bool ordered, hipStream_t stream) {
     if (n_queries == 0 || k == 0) return hipSuccess;
     if (k > TOPK_KMAX) return hipErrorInvalidValue;
     // the lists are read 16 bytes at a time
@@ -126,12 +131,16 @@ hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const 
     const uint32_t* hist0 = hist_bins ? counts + hp->hist_off : nullptr;
     const uint32_t* segs = (hist_bins && hp->rows) ? counts + hp->seg_off : nullptr;
     const uint32_t slabs = hist_bins ? hp->slabs : 0;
-    if (keys_fit_32(max_score, max_id))
-        hipLaunchKernelGGL(topk_lists_kernel<uint32_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream,
-                           (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins, segs, slabs);
-    else
-        hipLaunchKernelGGL(topk_lists_kernel<uint64_t>, dim3(n_queries), dim3(TOPK_LIST_THREADS), lds, stream, lists,
-                           list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0, hist_bins, segs, slabs);
+    const dim3 grid(n_queries), block(TOPK_LIST_THREADS);
+    if (keys_fit_32(max_score, max_id)) {
+        auto kern = ordered ? topk_lists_kernel<uint32_t, true> : topk_lists_kernel<uint32_t, false>;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint32_t*)lists, list_stride, counts, k, plan, kpad, out_ids,
+                           out_scores, hist0, hist_bins, segs, slabs);
+    } else {
+        auto kern = ordered ? topk_lists_kernel<uint64_t, true> : topk_lists_kernel<uint64_t, false>;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, lists, list_stride, counts, k, plan, kpad, out_ids, out_scores, hist0,
+                           hist_bins, segs, slabs);
+    }
     return hipGetLastError();
 }
 

@@ -276,7 +276,8 @@ __device__ void bitonic_sort_lds(uint64_t* a, uint32_t npad) {
 // sorted: kpad = next power of two >= max(k, 2) entries of LDS.
 // first_hist: optional, leading_score_bins() counters (see there).  dir: optional, see SlabDirectory (key sources
 // with SEGMENTS only); it replaces first_hist.
-template <int T, typename Keys, int U = 4, bool CACHE = false>
+// ORDERED = false: the k best keys are left in `sorted` in no particular order (callers that only need the set).
+template <int T, typename Keys, int U = 4, bool CACHE = false, bool ORDERED = true>
 __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
                              SelectShared& sh, const KeyPlan& plan, const uint32_t* first_hist = nullptr,
                              const SlabDirectory* dir = nullptr) {
@@ -494,6 +495,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     while (gpad < at_or_above) gpad <<= 1;
                     for (uint32_t i = at_or_above + tid; i < gpad; i += T) gathered[i] = 0;
                     __syncthreads();
+                    // (sorted even when the order is not asked for: more keys than k were gathered)
                     bitonic_sort_lds<T>(gathered, gpad);
                     for (uint32_t i = tid; i < k; i += T) sorted[i] = gathered[i];
                     __syncthreads();
@@ -537,6 +539,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         });
     }
     __syncthreads();
+    if constexpr (!ORDERED) return;
     // 1 to 16 keys per thread: sort in registers
     if (kpad >= (uint32_t)T && kpad <= 16u * T) {
         switch (kpad / T) {

@@ -150,6 +150,67 @@ def test_filter_then_search_chain_with_empty_slots():
     assert hits >= 12, hits
 
 
+@pytest.mark.parametrize("probe,filter_k,k,q_lens,n_docs,max_len", [
+    (1, 512, 10, [32] * 6, 20_000, 40),        # equal lengths, lists filled
+    (1, 4096, 10, [32], 200_000, 3),           # one query set: the single-query form of the chain
+    (2, 300, 50, [5, 40, 1, 33], 1500, 12),    # unequal query sets
+    (4, 16, 16, [32, 7], 1500, 12),            # k = filter_k
+    (8, 4096, 100, [12, 7], 1500, 12),         # fewer hit documents than filter_k: empty slots reach the scoring
+    (37, 2000, 20, [1800, 5], 150_000, 3),     # 64-bit list keys
+    (3, 5000, 5000, [20, 32, 7], 100_000, 3)])
+def test_filter_search_equals_filter_then_search_and_the_oracle(probe, filter_k, k, q_lens, n_docs, max_len):
+    """dessert_filter_search (one call, candidates unordered in between) against dessert_filter_query + dessert_search
+    and against the oracle's pipeline: the filter's set of documents, their scores, the k best."""
+    say(f"filter_search probe={probe} filter_k={filter_k} k={k} q_lens={q_lens[:4]} N={n_docs}")
+    rng = np.random.default_rng(500 + probe)
+    d, K = 128, 37
+    ix, X, Cn, R, off, lens = setup(rng, d, K, n_docs, max_len, dup_centroids=True)
+    dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
+    nq = int(sum(q_lens))
+    Q = np.clip(Cn[rng.integers(0, K, nq)].astype(np.int64) + rng.integers(-60, 61, (nq, d)), -127, 127).astype(np.int8)
+    Qd = torch.from_numpy(Q).to(DEV)
+    ids, sc = dz.filter_search(ix, Qd, q_lens, probe, filter_k, k)
+    cand, _ = dz.filter_query(ix, Qd, q_lens, probe, filter_k)
+    ids2, sc2 = dz.search(ix, Qd, q_lens, k, cand_ids=cand)
+    assert torch.equal(ids, ids2) and torch.equal(sc, sc2)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    obo, obd = orc.inverted_index(orc.assign_centroids(X, Cn), off, K)
+    dc, qc = orc.hash_i8(X, R, 32, 7), orc.hash_i8(Q, R, 32, 7)
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    for b in range(len(q_lens)):
+        want_cand, _ = orc.filter_query(Q[qo[b]:qo[b + 1]], Cn, obo, obd, n_docs, probe, filter_k)
+        real = want_cand[want_cand != 0xFFFFFFFF].astype(np.int64)
+        want_ids, want_sc = orc.topk(orc.scores(dc, off, qc[qo[b]:qo[b + 1]], real), k, real)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+    # twice more on the same workspace: same answer (the unordered candidate lists may differ from call to call)
+    ws = torch.empty(int(dz.lib().dessert_filter_search_workspace_bytes(ix.handle, len(q_lens), nq, max(q_lens), probe, filter_k, k)),
+                     dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        a, b_ = dz.filter_search(ix, Qd, q_lens, probe, filter_k, k, workspace=ws)
+        assert np.array_equal(a.cpu().numpy(), ids) and np.array_equal(b_.cpu().numpy(), sc)
+
+
+def test_filter_search_argument_errors():
+    rng = np.random.default_rng(77)
+    ix, X, Cn, R, off, lens = setup(rng, 128, 9, 300, 10)
+    Qd = torch.from_numpy(X[:40].copy()).to(DEV)
+    with pytest.raises(dz.DessertError, match="dessert_filter_build has not been called") as e:
+        dz.filter_search(ix, Qd, [8, 32], 1, 10, 5)
+    assert e.value.status == dz.ESTATE
+    dz.filter_build(ix, torch.from_numpy(Cn).to(DEV), torch.from_numpy(X).to(DEV))
+    for args, msg in [((0, 10, 5), "filter_probe must be"), ((10, 10, 5), "filter_probe must be"), ((1, 16385, 5), "filter_k must be"),
+                      ((1, 10, 0), "k must be")]:
+        with pytest.raises(dz.DessertError, match=msg) as e:
+            dz.filter_search(ix, Qd, [8, 32], *args)
+        assert e.value.status == dz.EINVAL
+    with pytest.raises(dz.DessertError, match="workspace too small"):
+        dz.filter_search(ix, Qd, [8, 32], 1, 10, 5, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    ids, sc = dz.filter_search(ix, Qd, [8, 32], 1, 10, 5)
+    cand, _ = dz.filter_query(ix, Qd, [8, 32], 1, 10)
+    ids2, sc2 = dz.search(ix, Qd, [8, 32], 5, cand_ids=cand)
+    assert torch.equal(ids, ids2) and torch.equal(sc, sc2)
+
+
 def test_search_all_slots_empty_and_k_larger_than_real_candidates():
     say("search with mostly empty candidate slots")
     rng = np.random.default_rng(9)
