@@ -110,8 +110,8 @@ def traffic_from_profile(kernel: str):
             section = None
         elif section and "mean=" in line:
             name = line.split("grid=")[0].strip()
-            # the summary keeps the tail of long names: the launched name must end with what the line shows
-            if name and kernel.endswith(name.lstrip(":").lstrip()) and "score_" in kernel and name.endswith(">"):
+            # the summary keeps the tail of long names: from "score_" on it must be exactly the launched instantiation
+            if "score_" in name and name[name.index("score_"):] == kernel:
                 vals.setdefault(section, float(line.split("mean=")[1]))
     if "fetch" not in vals or "write" not in vals:
         return None
