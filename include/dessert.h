@@ -26,7 +26,8 @@
  *     and unchanged while the index is searched.
  *   - Asynchrony: all device work is enqueued on config.stream; calls return
  *     without synchronising.  Host arrays are read before the call returns.
- *     Outputs are valid once the caller has synchronised the stream.  Calls
+ *     Outputs are valid once the caller has synchronised the stream.  (dessert_set_score_transform
+ *     is asynchronous too: the new table is written in stream order.)  Calls
  *     on a stream that is being captured into a HIP graph: dessert_search,
  *     dessert_scores, dessert_search_noalloc, dessert_filter_query and dessert_filter_search record
  *     a fixed sequence of kernel launches when all query sets of the batch
@@ -177,6 +178,17 @@ dessert_status_t dessert_hash(const dessert_index_t *index, const void *vectors_
 dessert_status_t dessert_build_index(dessert_index_t *index, const void *vectors_dev, uint64_t n_vectors,
                                      const uint32_t *lengths_host, uint64_t n_docs,
                                      uint8_t *codes_dev, uint64_t *offsets_dev);
+
+/* Attach an index built earlier (Alg. 1's sketch D is the code array plus the offsets; nothing else is kept): the arrays that
+ * a dessert_build_index call with the same configuration and the same projection matrix (dessert_get_projection; pass it as
+ * config.proj_dev) wrote, e.g. reloaded from disk, become this handle's index without hashing anything again.
+ *   codes_dev    dev, dessert_code_bytes(n_vectors) bytes, as written by dessert_build_index
+ *   offsets_dev  dev, [n_docs+1] u64, as written by dessert_build_index
+ *   max_length   vectors of the longest document (bounds checks and kernel choice; the largest offsets difference)
+ * Nothing is read on the device and nothing is checked against the arrays' contents.  Buffers must stay alive as for
+ * dessert_build_index; a candidate filter of the previous collection is dropped. */
+dessert_status_t dessert_attach_index(dessert_index_t *index, const uint8_t *codes_dev, const uint64_t *offsets_dev,
+                                      uint64_t n_docs, uint64_t n_vectors, uint64_t max_length);
 
 /* Workspace bytes needed by dessert_search / dessert_scores for a batch of
  * n_queries query sets with total_q_vectors vectors in all, total_scored

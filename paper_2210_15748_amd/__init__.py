@@ -36,7 +36,7 @@ EXPORTS = [
     "dessert_create", "dessert_destroy", "dessert_get_projection", "dessert_set_algo", "dessert_set_score_transform",
     "dessert_set_query_weights",
     "dessert_code_bytes",
-    "dessert_hash", "dessert_build_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
+    "dessert_hash", "dessert_build_index", "dessert_attach_index", "dessert_search_workspace_bytes", "dessert_search", "dessert_scores",
     "dessert_noalloc_scratch_bytes", "dessert_search_noalloc", "dessert_set_debug", "dessert_last_score_kernel",
     "dessert_filter_kmeans_workspace_bytes", "dessert_filter_kmeans",
     "dessert_filter_build", "dessert_filter_workspace_bytes", "dessert_filter_query",
@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
     l.dessert_code_bytes.restype = sz
     l.dessert_hash.argtypes = [vp, vp, u64, vp]
     l.dessert_build_index.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+    l.dessert_attach_index.argtypes = [vp, vp, vp, u64, u64, u64]
     l.dessert_search_workspace_bytes.argtypes = [vp, u32, u64, u64, u32]
     l.dessert_search_workspace_bytes.restype = sz
     l.dessert_search.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, sz, vp, vp]
@@ -247,6 +248,21 @@ def build_index(ix: Index, vectors: torch.Tensor, lengths, codes: Optional[torch
                                      codes.data_ptr(), offsets.data_ptr()))
     ix.codes, ix.offsets, ix.n_docs = codes, offsets, n_docs
     return codes, offsets
+
+
+def attach_index(ix: Index, codes: torch.Tensor, offsets: torch.Tensor, max_length: Optional[int] = None) -> None:
+    """dessert_attach_index: make arrays written by an earlier build_index (same configuration and projection matrix) this
+    handle's index.  max_length (longest document) is computed from the offsets if not given."""
+    if not codes.is_cuda or not offsets.is_cuda or offsets.dtype != torch.int64 or offsets.dim() != 1 or offsets.numel() < 1:
+        raise ValueError("codes and offsets must be device tensors, offsets int64 [n_docs + 1]")
+    if codes.dtype != code_dtype(ix) or codes.dim() != 2 or codes.shape[1] != ix.cfg.L:
+        raise ValueError(f"codes must be [n_vectors, {ix.cfg.L}] of {code_dtype(ix)}")
+    codes, offsets = codes.contiguous(), offsets.contiguous()
+    n_docs = offsets.numel() - 1
+    if max_length is None:
+        max_length = int((offsets[1:] - offsets[:-1]).max().item()) if n_docs else 0
+    _check(lib().dessert_attach_index(ix.handle, codes.data_ptr(), offsets.data_ptr(), n_docs, codes.shape[0], max_length))
+    ix.codes, ix.offsets, ix.n_docs = codes, offsets, n_docs
 
 
 def _batch(ix: Index, q_vectors, q_lengths, cand_ids, cand_offsets):

@@ -584,6 +584,7 @@ dessert_status_t dessert_create(const dessert_config_t* c, dessert_index_t** out
         e = hipMalloc(&ix->proj_mfma, mfma_f16_proj_bytes(c->d, c->L));
         if (e == hipSuccess) e = launch_repack_proj_f16((const float*)ix->proj, c->d, c->L, c->C, ix->proj_mfma, ix->stream);
     }
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->remap, SCORE_TABLE_MAX * sizeof(uint32_t));
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->upload_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->build_entry, hipEventDisableTiming);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ix->copy_stream, hipStreamNonBlocking);
@@ -666,9 +667,9 @@ dessert_status_t dessert_set_score_transform(dessert_index_t* ix, int transform)
             tab[c] = (uint32_t)std::llround(65536.0 * y);
             mx = std::max(mx, tab[c]);
         }
-        HIP_TRY(hipStreamSynchronize(ix->stream));  // searches in flight may still read the old table
-        if (!ix->remap) HIP_TRY(hipMalloc((void**)&ix->remap, (L + 1) * sizeof(uint32_t)));
-        HIP_TRY(hipMemcpy(ix->remap, tab.data(), (L + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+        // written by a launch that carries the values as its argument: behind the searches in flight that still read the
+        // old table, before those that follow; nothing to wait for
+        HIP_TRY(launch_write_table(tab.data(), L + 1, ix->remap, ix->stream));
         ix->remap_max = mx;
     }
     ix->transform = transform;
@@ -763,6 +764,27 @@ dessert_status_t dessert_build_index(dessert_index_t* ix, const void* vectors_de
     ix->n_docs = n_docs;
     ix->n_vectors = n_vectors;
     ix->max_len = longest;
+    ix->built = true;
+    return DESSERT_OK;
+}
+
+dessert_status_t dessert_attach_index(dessert_index_t* ix, const uint8_t* codes_dev, const uint64_t* offsets_dev, uint64_t n_docs,
+                                      uint64_t n_vectors, uint64_t max_length) {
+    if (!ix) return fail(DESSERT_EINVAL, "index is NULL");
+    if (!offsets_dev) return fail(DESSERT_EINVAL, "offsets_dev is NULL");
+    if (n_vectors && !codes_dev) return fail(DESSERT_EINVAL, "codes_dev is NULL");
+    if (n_docs > 0xFFFFFFFEull) return fail(DESSERT_EINVAL, "document ids are 32-bit: n_docs too large");
+    if (max_length > n_vectors) return fail(DESSERT_EINVAL, "max_length (%llu) exceeds n_vectors (%llu)",
+                                            (unsigned long long)max_length, (unsigned long long)n_vectors);
+    if (n_vectors && max_length == 0) return fail(DESSERT_EINVAL, "max_length is 0 with n_vectors > 0");
+    // a new collection: any candidate filter built over the previous one is gone
+    ix->f_built = false;
+    ix->f_K = 0;
+    ix->codes = codes_dev;
+    ix->offsets = offsets_dev;
+    ix->n_docs = n_docs;
+    ix->n_vectors = n_vectors;
+    ix->max_len = max_length;
     ix->built = true;
     return DESSERT_OK;
 }

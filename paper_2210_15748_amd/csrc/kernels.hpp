@@ -85,6 +85,9 @@ uint64_t score_order_min();
 bool cand_order_plan(const uint32_t* cand_ids, const uint64_t* cand_off, uint64_t cand_uniform, uint32_t n_queries,
                      uint64_t max_scored, uint64_t n_docs, uint32_t max_ranges, uint32_t* order, CandOrderArgs* out);
 hipError_t launch_cand_order(const CandOrderArgs& a, hipStream_t stream);  // a.ranges <= 4096
+// Write the n <= SCORE_TABLE_MAX words of a host table to dst (device) in stream order: the values travel as the launch's argument.
+constexpr uint32_t SCORE_TABLE_MAX = 192;   // L + 1 entries with L <= 128
+hipError_t launch_write_table(const uint32_t* table_host, uint32_t n, uint32_t* dst, hipStream_t stream);
 // Debug aid: *first_bad = the lowest slot whose id is neither below n_docs nor the empty-slot value 0xFFFFFFFF,
 // all ones if every id is fine (two launches: reset, then a scan of the n ids).
 hipError_t launch_check_cand_ids(const uint32_t* cand_ids, uint64_t n, uint64_t n_docs, unsigned long long* first_bad,

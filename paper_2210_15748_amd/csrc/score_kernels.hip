@@ -783,6 +783,23 @@ static hipError_t launch_fill_zero(int32_t* p, uint64_t n, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// A table of at most SCORE_TABLE_MAX words travels as a kernel argument and is written to device memory by the launch itself:
+// in stream order behind the searches that still read the old table, with no staging buffer and no synchronisation.
+struct ScoreTableArg {
+    uint32_t v[SCORE_TABLE_MAX];
+};
+__global__ void write_table_kernel(ScoreTableArg t, uint32_t n, uint32_t* __restrict__ dst) {
+    if (threadIdx.x < n) dst[threadIdx.x] = t.v[threadIdx.x];
+}
+
+hipError_t launch_write_table(const uint32_t* table_host, uint32_t n, uint32_t* dst, hipStream_t stream) {
+    if (n > SCORE_TABLE_MAX || !dst) return hipErrorInvalidValue;
+    ScoreTableArg arg{};
+    for (uint32_t i = 0; i < n; ++i) arg.v[i] = table_host[i];
+    hipLaunchKernelGGL(write_table_kernel, dim3(1), dim3(SCORE_TABLE_MAX), 0, stream, arg, n, dst);
+    return hipGetLastError();
+}
+
 __global__ void reset_first_bad_kernel(unsigned long long* first_bad) { *first_bad = ~0ull; }
 
 __global__ __launch_bounds__(256) void check_cand_ids_kernel(const uint32_t* __restrict__ ids, uint64_t n, uint64_t n_docs,

@@ -55,6 +55,7 @@ int main(void) {
     EXPECT(dessert_code_bytes(NULL, 10) == 0);
     EXPECT(dessert_hash(NULL, &c, 1, (uint8_t *)&c) == DESSERT_EINVAL);
     EXPECT(dessert_build_index(NULL, &c, 1, &len, 1, (uint8_t *)&c, off) == DESSERT_EINVAL);
+    EXPECT(dessert_attach_index(NULL, (const uint8_t *)&c, off, 1, 1, 1) == DESSERT_EINVAL);
     EXPECT(dessert_search_workspace_bytes(NULL, 1, 1, 1, 1) == 0);
     EXPECT(dessert_search(NULL, &c, &len, 1, NULL, NULL, 0, &c, 256, &len, (int32_t *)&len) == DESSERT_EINVAL);
     EXPECT(dessert_search(NULL, &c, &len, 1, NULL, NULL, 5, &c, 256, NULL, NULL) == DESSERT_EINVAL);

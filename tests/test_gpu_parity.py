@@ -343,6 +343,63 @@ def test_build_index_again_on_the_same_handle():
         assert np.array_equal(sc.cpu().numpy(), want_sc)
 
 
+def test_attach_index_resumes_without_rehashing(tmp_path):
+    """An index is its code array and offsets (Alg. 1's sketch): saved, reloaded and attached to a new handle made with the
+    same projection matrix it answers exactly as the handle that built it, filter included."""
+    say("attach_index: save codes / offsets / projection, attach to a fresh handle")
+    w = gen.make(3, n_docs=5000, n_queries=9, n_cand=300)
+    p = w.preset
+    ix, codes, offsets = make_index(w)
+    q, cand = w.queries.to(DEV), w.cand_ids.to(DEV)
+    want = dz.search(ix, q, w.q_lengths, p.k, cand_ids=cand)
+    want_all = dz.search(ix, q, w.q_lengths, 7)
+    torch.save({"codes": codes.cpu(), "offsets": offsets.cpu(), "proj": dz.get_projection(ix).cpu()}, tmp_path / "index.pt")
+    del ix
+    saved = torch.load(tmp_path / "index.pt", weights_only=True)
+    ix2 = dz.create(p.d, p.L, p.C, proj=saved["proj"].to(DEV))
+    with pytest.raises(dz.DessertError) as e:
+        dz.search(ix2, q, w.q_lengths, p.k, cand_ids=cand)
+    assert e.value.status == dz.ESTATE
+    dz.attach_index(ix2, saved["codes"].to(DEV), saved["offsets"].to(DEV))
+    got = dz.search(ix2, q, w.q_lengths, p.k, cand_ids=cand)
+    got_all = dz.search(ix2, q, w.q_lengths, 7)
+    assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+    assert torch.equal(got_all[0], want_all[0]) and torch.equal(got_all[1], want_all[1])
+    dc, qc = oracle_codes(w)
+    qs = [qc[b * p.q_len:(b + 1) * p.q_len] for b in range(p.n_queries)]
+    o_ids, o_sc, _ = orc.search(dc, w.offsets.numpy(), qs, 7)
+    assert np.array_equal(got_all[0].cpu().numpy(), o_ids) and np.array_equal(got_all[1].cpu().numpy(), o_sc)
+    l = dz.lib()
+    assert l.dessert_attach_index(ix2.handle, None, ix2.offsets.data_ptr(), 5, 10, 3) == dz.EINVAL
+    assert l.dessert_attach_index(ix2.handle, ix2.codes.data_ptr(), None, 5, 10, 3) == dz.EINVAL
+    assert l.dessert_attach_index(ix2.handle, ix2.codes.data_ptr(), ix2.offsets.data_ptr(), 5, 10, 11) == dz.EINVAL
+    assert l.dessert_attach_index(ix2.handle, ix2.codes.data_ptr(), ix2.offsets.data_ptr(), 5, 10, 0) == dz.EINVAL
+
+
+def test_score_transform_switches_in_stream_order_without_waiting():
+    """dessert_set_score_transform writes the new table in stream order: calls enqueued before the switch use the old
+    table, calls after it the new one, with no synchronisation in between."""
+    say("score transform switched between back-to-back calls")
+    w = gen.make(2, n_docs=4000, n_queries=6)
+    p = w.preset
+    ix, codes, _ = make_index(w)
+    q = w.queries.to(DEV)
+    outs = []
+    for t in (dz.SCORE_EQ1_Q16, dz.SCORE_MAX_EXPM1_Q16, dz.SCORE_RAW_COUNTS, dz.SCORE_MAX_SIGMOID_Q16, dz.SCORE_EQ1_Q16):
+        dz.set_score_transform(ix, t)
+        outs.append((t, dz.scores(ix, q, w.q_lengths)))          # no synchronisation between the calls
+    torch.cuda.synchronize()
+    dc, qc = oracle_codes(w)
+    off = w.offsets.numpy()
+    kinds = {dz.SCORE_EQ1_Q16: orc.PHI_EQ1, dz.SCORE_MAX_EXPM1_Q16: orc.PHI_EXPM1, dz.SCORE_MAX_SIGMOID_Q16: orc.PHI_SIGMOID}
+    for t, got in outs:
+        g = got.cpu().numpy()
+        for b in (0, 5):
+            qb = qc[b * p.q_len:(b + 1) * p.q_len]
+            want = orc.scores(dc, off, qb) if t == dz.SCORE_RAW_COUNTS else orc.scores_general(dc, off, qb, kinds[t], orc.SIGMA_MAX, eq1_C=p.C)
+            assert np.array_equal(g[b], want), (t, b)
+
+
 # ------------------------------------------------------------------ top-k and whole search
 def check_search(w, tag, score_algo=dz.SCORE_AUTO):
     p = w.preset
