@@ -132,6 +132,9 @@ def main() -> int:
     ap.add_argument("--sweep-m", type=int, default=None,
                     help="run the synthetic-experiment shape instead of a preset: 1000 documents of m vectors, L = 8, "
                          "C = log2(m) + 1, queries = noisy documents (not the metric's workload)")
+    ap.add_argument("--L", type=int, default=None, help="override the preset's number of tables (the paper's App. B grid: 16..128; not the metric)")
+    ap.add_argument("--C", type=int, default=None, help="override the preset's hashes per table (App. B grid: 4..8; not the metric)")
+    ap.add_argument("--n-cand", type=int, default=None, help="override the candidates per query set (App. B: filter_k 4096..16384; not the metric)")
     ap.add_argument("--n-docs", type=int, default=None, help="shrink the preset (for quick trials; not the metric)")
     ap.add_argument("--n-queries", type=int, default=None)
     ap.add_argument("--build-reps", type=int, default=20)
@@ -175,6 +178,13 @@ def main() -> int:
 
     t0 = time.time()
     which = gen.sweep_preset(args.sweep_m) if args.sweep_m else args.config
+    overridden = args.L is not None or args.C is not None or args.n_cand is not None
+    if overridden and not args.sweep_m:
+        import dataclasses
+        base = gen.PRESETS[args.config]
+        which = dataclasses.replace(base, L=args.L or base.L, C=args.C or base.C, n_cand=base.n_cand if args.n_cand is None else args.n_cand)
+        which.name = f"{base.name}_L{which.L}_C{which.C}_cand{which.n_cand}"
+        args.no_secondary = True
     w = gen.make(which, device=dev, n_docs=args.n_docs, n_queries=args.n_queries)
     p = w.preset
     torch.cuda.synchronize()
@@ -268,7 +278,7 @@ def main() -> int:
 
     # ---- candidate filter (Sec. 5 "Filtering") in front of the same search: reported beside the metric, not part of it
     filt = None
-    if args.config == 3 and not args.sweep_m and p.dtype == "i8" and not args.no_filter:
+    if args.config == 3 and not args.sweep_m and p.dtype == "i8" and not args.no_filter and not overridden:
         def ev_ms(fn, reps):
             fn()
             torch.cuda.synchronize()
@@ -359,7 +369,7 @@ def main() -> int:
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "kernel_launched": score_kernel,
                     "traffic": traffic_from_profile(score_kernel)
-                    if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None) else None,
+                    if (args.config == 3 and not args.sweep_m and args.n_docs is None and args.n_queries is None and not overridden) else None,
                     "algorithmic_bytes_per_launch": code_bytes, "kernel_ms": round(score_ms, 5),
                     "measured_stream_read_GBs": round(read_gbs, 1), "frac_of_measured_stream": round(achieved / read_gbs, 4)}
     else:

@@ -119,25 +119,35 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
 // 8; register r of lane-half g is bit r of table g*(L/2) + mt, so a lane's 16 accumulators of one
 // M-tile make one code.  A code row is LT*4 bytes either way (LT = L/4 M-tiles, or L/2 when WIDE)
 // and lane-half g owns the g-th half of it.
+// Table groups: with more tables than one launch takes (a code row of more than 64 bytes: L = 128 one-byte codes, L = 64
+// 16-bit codes) the tables are hashed in groups of 64 bytes of code row, one launch per group: `codes` then points at the
+// group's first byte of row 0, Rp at the group's matrix, and row_bytes (bytes from one vector's codes to the next) is the
+// full row.  The vectors are read once per group.
 // FUSED: the workgroups from hash_blocks on do not hash; workgroup hash_blocks + b groups candidate list b by
 // document id range (cand_order.hpp), with the LDS that holds R otherwise as its bins.
+// Threads per workgroup: a 64 KB matrix lets a CU hold two workgroups, and with four waves each the MFMA, the sign packing
+// and the loads of only two waves per SIMD do not overlap enough; eight waves share such a matrix.
+constexpr int mfma_threads(int KS, int LT) { return LT * KS * 1024 >= 64 * 1024 ? 512 : 256; }
+
 template <int KS, int LT, int NT, bool WIDE, bool FUSED>
-__global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restrict__ X, uint64_t n,
+__global__ __launch_bounds__(mfma_threads(KS, LT)) void hash_mfma_i8_kernel(const int8_t* __restrict__ X, uint64_t n,
                                                            const v4i* __restrict__ Rp, uint32_t cmask,
-                                                           uint8_t* __restrict__ codes, uint32_t hash_blocks,
-                                                           CandOrderArgs fused) {
+                                                           uint8_t* __restrict__ codes, uint32_t row_bytes,
+                                                           uint32_t hash_blocks, CandOrderArgs fused) {
     constexpr int D = KS * 32;
     constexpr int L = LT * 4;   // bytes per code row
     constexpr int OW = LT / 2;  // output dwords per lane (half a code row)
+    constexpr int T = mfma_threads(KS, LT);
+    constexpr int WAVES = T / 64;
     extern __shared__ v4i sR[];
     if constexpr (FUSED) {
         if (blockIdx.x >= hash_blocks) {
-            __shared__ uint32_t wave_sum[4];
-            cand_order_body<256>(fused, blockIdx.x - hash_blocks, reinterpret_cast<uint32_t*>(sR), wave_sum);
+            __shared__ uint32_t wave_sum[WAVES];
+            cand_order_body<T>(fused, blockIdx.x - hash_blocks, reinterpret_cast<uint32_t*>(sR), wave_sum);
             return;
         }
     }
-    for (int i = threadIdx.x; i < LT * KS * 64; i += 256) sR[i] = Rp[i];
+    for (int i = threadIdx.x; i < LT * KS * 64; i += T) sR[i] = Rp[i];
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restr
     const int g = lane >> 5;
     const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
 
-    for (uint64_t tile = (uint64_t)blockIdx.x * 4 + wave; tile < n_tiles; tile += (uint64_t)hash_blocks * 4) {
+    for (uint64_t tile = (uint64_t)blockIdx.x * WAVES + wave; tile < n_tiles; tile += (uint64_t)hash_blocks * WAVES) {
         const uint64_t v0 = tile * (32 * NT);
         v4i b[NT][KS];
 #pragma unroll
@@ -218,7 +228,7 @@ __global__ __launch_bounds__(256) void hash_mfma_i8_kernel(const int8_t* __restr
         for (int nt = 0; nt < NT; ++nt) {
             uint64_t v = v0 + nt * 32 + col;
             if (v < n) {
-                uint32_t* dst = (uint32_t*)(codes + v * L + g * (L / 2));
+                uint32_t* dst = (uint32_t*)(codes + v * row_bytes + g * (L / 2));
                 if constexpr (OW % 4 == 0) {
 #pragma unroll
                     for (int w = 0; w < OW; w += 4) {
@@ -266,61 +276,79 @@ static bool mfma_shape(uint32_t d, uint32_t L) {
     return (d == 64 || d == 128 || d == 256) && (L == 16 || L == 32 || L == 64);
 }
 
+// Tables per launch: at most 64 bytes of code row (the re-ordered matrix of a launch has to fit 64 KB of LDS)
+static uint32_t group_tables(uint32_t L, uint32_t C) {
+    const uint32_t cap = C <= 8 ? 64 : 32;
+    return L < cap ? L : cap;
+}
+static bool group_supported(uint32_t d, uint32_t Lg, uint32_t C) {
+    if (!(d == 64 || d == 128 || d == 256) || C < 1 || C > 16) return false;
+    if (!(Lg == 8 || Lg == 16 || Lg == 32 || (Lg == 64 && C <= 8))) return false;
+    const uint32_t lt = mfma_tiles(Lg, C);  // 2, 4, 8 or 16
+    return (size_t)lt * (d / 32) * 1024 <= 64 * 1024;
+}
+static size_t group_proj_bytes(uint32_t d, uint32_t Lg, uint32_t C) { return (size_t)mfma_tiles(Lg, C) * (d / 32) * 64 * 16; }
+
 size_t mfma_proj_bytes(uint32_t d, uint32_t L, uint32_t C) {
     if (!hash_mfma_supported(d, L, C)) return 0;
-    return (size_t)mfma_tiles(L, C) * (d / 32) * 64 * 16;
+    const uint32_t Lg = group_tables(L, C);
+    return (L / Lg) * group_proj_bytes(d, Lg, C);
 }
 
+// L in {8, 16, 32, 64}, and 128 with one-byte codes (two groups of 64 tables); the groups' matrices must fit LDS
 bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C) {
-    if (!(d == 64 || d == 128 || d == 256) || C < 1 || C > 16) return false;
-    if (!(L == 8 || L == 16 || L == 32 || (L == 64 && C <= 8))) return false;
-    const uint32_t lt = mfma_tiles(L, C);  // 2, 4, 8 or 16
-    return (size_t)lt * (d / 32) * 1024 <= 64 * 1024;
+    if (C < 1 || C > 16) return false;
+    if (!(L == 8 || L == 16 || L == 32 || L == 64 || (L == 128 && C <= 8))) return false;
+    return group_supported(d, group_tables(L, C), C);
 }
 
 hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
-    uint32_t total = (uint32_t)mfma_proj_bytes(d, L, C);
-    if (!total) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(repack_proj_i8_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, R, d, L, C, (int8_t*)Rp,
-                       total);
+    if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
+    const uint32_t Lg = group_tables(L, C);
+    const uint32_t total = (uint32_t)group_proj_bytes(d, Lg, C);
+    for (uint32_t grp = 0; grp < L / Lg; ++grp) {   // group grp = tables grp*Lg .. : rows grp*Lg*C .. of R
+        hipLaunchKernelGGL(repack_proj_i8_kernel, dim3((total + 255) / 256), dim3(256), 0, stream,
+                           R + (size_t)grp * Lg * C * d, d, Lg, C, (int8_t*)Rp + (size_t)grp * total, total);
+    }
     return hipGetLastError();
 }
 
 template <int KS, int LT>
-static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
+static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes, uint32_t row_bytes,
                                 const CandOrderArgs* fused, hipStream_t stream) {
     constexpr int NT = 2;
+    constexpr int T = mfma_threads(KS, LT), WAVES = T / 64;
     const uint64_t n_tiles = (n + 32 * NT - 1) / (32 * NT);
-    uint64_t blocks = (n_tiles + 3) / 4;
-    // waves loop over tiles; 4096 workgroups (sixteen per CU, four or five of them resident at a time) measured 3 %
-    // faster on 70M vectors than exactly one resident set of 1024: the tail of the launch is shorter
-    if (blocks > 4096) blocks = 4096;
+    uint64_t blocks = (n_tiles + WAVES - 1) / WAVES;
+    // waves loop over tiles; 16384 waves (sixteen workgroups of four per CU, four or five of them resident at a time)
+    // measured 3 % faster on 70M vectors than exactly one resident set: the tail of the launch is shorter
+    if (blocks > 16384 / WAVES) blocks = 16384 / WAVES;
     size_t lds = (size_t)LT * KS * 64 * 16;
     const uint32_t cmask = (1u << C) - 1u;
     if (fused) {
         if ((size_t)fused->ranges * 4 > lds || blocks + fused->n_lists > 0x7fffffffull) return hipErrorInvalidValue;
         const dim3 grid((unsigned)(blocks + fused->n_lists));
         if (C <= 8)
-            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, true>), grid, dim3(256), lds, stream, X, n,
-                               (const v4i*)Rp, cmask, codes, (uint32_t)blocks, *fused);
+            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, true>), grid, dim3(T), lds, stream, X, n,
+                               (const v4i*)Rp, cmask, codes, row_bytes, (uint32_t)blocks, *fused);
         else
-            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, true>), grid, dim3(256), lds, stream, X, n,
-                               (const v4i*)Rp, cmask, codes, (uint32_t)blocks, *fused);
+            hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, true>), grid, dim3(T), lds, stream, X, n,
+                               (const v4i*)Rp, cmask, codes, row_bytes, (uint32_t)blocks, *fused);
         return hipGetLastError();
     }
     if (C <= 8)
-        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, false>), dim3((unsigned)blocks), dim3(256), lds, stream, X,
-                           n, (const v4i*)Rp, cmask, codes, (uint32_t)blocks, CandOrderArgs{});
+        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, false, false>), dim3((unsigned)blocks), dim3(T), lds, stream, X,
+                           n, (const v4i*)Rp, cmask, codes, row_bytes, (uint32_t)blocks, CandOrderArgs{});
     else
-        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, false>), dim3((unsigned)blocks), dim3(256), lds, stream, X,
-                           n, (const v4i*)Rp, cmask, codes, (uint32_t)blocks, CandOrderArgs{});
+        hipLaunchKernelGGL((hash_mfma_i8_kernel<KS, LT, NT, true, false>), dim3((unsigned)blocks), dim3(T), lds, stream, X,
+                           n, (const v4i*)Rp, cmask, codes, row_bytes, (uint32_t)blocks, CandOrderArgs{});
     return hipGetLastError();
 }
 
 // ranges the fused grouping may use: the bins live in the LDS that holds R in the hashing workgroups
 uint32_t hash_mfma_fused_ranges(uint32_t d, uint32_t L, uint32_t C) {
     if (!hash_mfma_supported(d, L, C)) return 0;
-    const size_t words = (size_t)mfma_tiles(L, C) * (d / 32) * 64 * 4;
+    const size_t words = group_proj_bytes(d, group_tables(L, C), C) / 4;
     uint32_t r = 1;
     while ((size_t)r * 2 <= words && r < 4096) r *= 2;
     return r;
@@ -330,22 +358,32 @@ hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t
                                uint8_t* codes, const CandOrderArgs* fused, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
-    const uint32_t lt = mfma_tiles(L, C);
+    const uint32_t Lg = group_tables(L, C), groups = L / Lg;
+    const uint32_t lt = mfma_tiles(Lg, C);
+    const uint32_t code_bytes = C <= 8 ? 1 : 2;
+    const uint32_t row_bytes = L * code_bytes;
+    for (uint32_t grp = 0; grp < groups; ++grp) {
+        const void* Rg = (const char*)Rp + (size_t)grp * group_proj_bytes(d, Lg, C);
+        uint8_t* cg = codes + (size_t)grp * Lg * code_bytes;
+        const CandOrderArgs* fg = grp == 0 ? fused : nullptr;   // the candidate grouping rides in the first launch
+        hipError_t e = hipErrorInvalidValue;
 #define DESSERT_MFMA_CASE(KS_, LT_) \
-    if (d == KS_ * 32 && lt == LT_) return launch_mfma_t<KS_, LT_>(X, n, C, Rp, codes, fused, stream);
-    DESSERT_MFMA_CASE(2, 2)
-    DESSERT_MFMA_CASE(2, 4)
-    DESSERT_MFMA_CASE(2, 8)
-    DESSERT_MFMA_CASE(2, 16)
-    DESSERT_MFMA_CASE(4, 2)
-    DESSERT_MFMA_CASE(4, 4)
-    DESSERT_MFMA_CASE(4, 8)
-    DESSERT_MFMA_CASE(4, 16)
-    DESSERT_MFMA_CASE(8, 2)
-    DESSERT_MFMA_CASE(8, 4)
-    DESSERT_MFMA_CASE(8, 8)
+    if (d == KS_ * 32 && lt == LT_) e = launch_mfma_t<KS_, LT_>(X, n, C, Rg, cg, row_bytes, fg, stream);
+        DESSERT_MFMA_CASE(2, 2)
+        DESSERT_MFMA_CASE(2, 4)
+        DESSERT_MFMA_CASE(2, 8)
+        DESSERT_MFMA_CASE(2, 16)
+        DESSERT_MFMA_CASE(4, 2)
+        DESSERT_MFMA_CASE(4, 4)
+        DESSERT_MFMA_CASE(4, 8)
+        DESSERT_MFMA_CASE(4, 16)
+        DESSERT_MFMA_CASE(8, 2)
+        DESSERT_MFMA_CASE(8, 4)
+        DESSERT_MFMA_CASE(8, 8)
 #undef DESSERT_MFMA_CASE
-    return hipErrorInvalidValue;
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------

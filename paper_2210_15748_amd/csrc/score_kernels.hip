@@ -250,7 +250,7 @@ constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2
 constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
 // Threads per workgroup: a mask table of 32 KB or more limits a CU to a few workgroups, so eight waves share
 // one table instead of four: from 32 KB where the register budget allows it (few tables), always from 64 KB.
-constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && (L <= 16 || (L << CB) * 4 * W >= 64 * 1024)) ? 512 : 256; }
+constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && (L <= 16 || L >= 128 || (L << CB) * 4 * W >= 64 * 1024)) ? 512 : 256; }
 // Waves per SIMD the register allocation must allow: the rotated form (L = 64) keeps 24 more per-lane
 // constants and would otherwise drop from 4 to 3.
 constexpr int masklut_min_waves(int L, int CW, int W, int REMAP) { return (L == 64 && CW == 1 && W == 1 && REMAP < 3) ? 4 : 1; }

@@ -53,7 +53,9 @@ def test_hash_i8_bit_exact_ragged_sizes(algo, n):
     assert np.all(got[0] == 127)
 
 
-@pytest.mark.parametrize("d,L,Cb", [(128, 16, 6), (64, 16, 1), (256, 32, 8), (128, 64, 5), (64, 64, 8), (256, 16, 4)])
+@pytest.mark.parametrize("d,L,Cb", [(128, 16, 6), (64, 16, 1), (256, 32, 8), (128, 64, 5), (64, 64, 8), (256, 16, 4),
+                                    # more than 64 bytes of code row: hashed in table groups, one launch per group
+                                    (128, 128, 5), (64, 128, 8), (128, 128, 1)])
 def test_hash_mfma_shapes(d, L, Cb):
     say(f"hash mfma d={d} L={L} C={Cb}")
     rng = np.random.default_rng(d + L + Cb)
@@ -69,7 +71,8 @@ def test_hash_mfma_shapes(d, L, Cb):
     assert np.array_equal(got, codes)
 
 
-@pytest.mark.parametrize("L,Cb,n", [(32, 7, 1_200_001), (32, 3, 70_000), (64, 8, 140_003), (16, 12, 150_000), (32, 9, 140_003)])
+@pytest.mark.parametrize("L,Cb,n", [(32, 7, 1_200_001), (32, 3, 70_000), (64, 8, 140_003), (16, 12, 150_000), (32, 9, 140_003),
+                                    (128, 7, 70_001), (64, 11, 70_001)])
 def test_hash_long_runs_several_tiles_per_wave(L, Cb, n):
     """Runs long enough that a wave of the MFMA kernel loops over several tiles (more than 4096 workgroups x 4 waves x
     64 vectors in the first case), ragged tail, both code widths."""
