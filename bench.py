@@ -463,6 +463,10 @@ def main() -> int:
                    "step": "dessert_search: query hashing + scoring + top-k (index built once, before the timed region)"
                            + (", replayed from a captured HIP graph" if args.graph else "")},
         "kernel_ms": {"query_hash": round(qhash_ms, 5), "score": round(score_ms, 5), "topk": round(topk_ms, 5)},
+        # the scoring launches the means above are taken over (HIP events on a sample of the timed steps)
+        "score_kernel_ms_samples": {"n": len(tim), "median": round(float(np.median([t["score_ms"] for t in tim])), 5),
+                                    "min": round(float(np.min([t["score_ms"] for t in tim])), 5),
+                                    "max": round(float(np.max([t["score_ms"] for t in tim])), 5)},
         "index_build": {"metric": "index-build vectors/sec", "value": round(w.n_vectors / (build_ms * 1e-3), 1),
                         "unit": "vectors/s", "ms_per_call": round(build_ms, 4), "hash_kernel_ms": round(hash_kernel_ms, 4),
                         "reps": args.build_reps, "warmup": max(1, args.build_warmup),

@@ -478,6 +478,88 @@ def test_search_two_level_topk_many_short_documents():
     assert np.array_equal(ids.cpu().numpy(), want_ids)
 
 
+def test_search_with_the_largest_number_of_query_sets():
+    """65 535 query sets in one call (the limit the header states), exhaustive and with candidate lists; scores of a
+    sample of the sets and every top-k against the oracle."""
+    say("search: 65535 query sets of 1-2 vectors")
+    rng = np.random.default_rng(77)
+    d, L, Cb, N, B = 64, 16, 5, 300, 65535
+    lens = rng.integers(0, 5, N)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (32, d))
+    X = np.clip(pool[rng.integers(0, 32, V)] + rng.integers(-40, 41, (V, d)), -127, 127).astype(np.int8)
+    q_lens = rng.integers(1, 3, B).astype(np.int64)
+    nq = int(q_lens.sum())
+    Q = np.clip(pool[rng.integers(0, 32, nq)] + rng.integers(-40, 41, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    Qd = torch.from_numpy(Q).to(DEV)
+    raw = dz.scores(ix, Qd, q_lens).cpu().numpy()
+    ids, sc = dz.search(ix, Qd, q_lens, 5)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    sample = np.unique(np.concatenate([[0, 1, B - 2, B - 1], rng.integers(0, B, 1500)]))
+    for b in sample:
+        assert np.array_equal(raw[b], orc.scores(dc, off, qc[qo[b]:qo[b + 1]])), b
+    for b in range(B):
+        want_ids, want_sc = orc.topk(raw[b], 5)
+        assert np.array_equal(ids[b], want_ids) and np.array_equal(sc[b], want_sc), b
+    cand = rng.integers(0, N, (B, 6)).astype(np.int64)
+    got = dz.scores(ix, Qd, q_lens, cand_ids=torch.from_numpy(cand.astype(np.int32)).to(DEV)).cpu().numpy().reshape(B, 6)
+    for b in sample:
+        assert np.array_equal(got[b], orc.scores(dc, off, qc[qo[b]:qo[b + 1]], cand[b])), b
+    with pytest.raises(dz.DessertError) as e:
+        dz.scores(ix, torch.cat([Qd, Qd[:1]]), np.concatenate([q_lens, [1]]))
+    assert e.value.status == dz.EINVAL
+
+
+@pytest.mark.parametrize("L,Cb", [(16, 6), (32, 7), (128, 8)])
+def test_scores_one_very_long_document_among_short_ones(L, Cb):
+    """A document of 200 000 vectors (longer than any 16-bit length field) between short and empty ones: every
+    scoring form, exhaustive and as a candidate."""
+    say(f"scores: a 200000-vector document, L={L} C={Cb}")
+    rng = np.random.default_rng(L + Cb)
+    d = 64
+    lens = np.array([3, 0, 200_000, 1, 70, 0, 65_535, 65_536, 2], dtype=np.int64)
+    V = int(lens.sum())
+    pool = rng.integers(-127, 128, (40, d))
+    X = np.clip(pool[rng.integers(0, 40, V)] + rng.integers(-50, 51, (V, d)), -127, 127).astype(np.int8)
+    q_lens = np.array([32, 7, 40], dtype=np.int64)
+    nq = int(q_lens.sum())
+    Q = np.clip(pool[rng.integers(0, 40, nq)] + rng.integers(-50, 51, (nq, d)), -127, 127).astype(np.int8)
+    R = (rng.integers(0, 2, (L * Cb, d)) * 2 - 1).astype(np.int8)
+    ix = dz.create(d, L, Cb, proj=torch.from_numpy(R).to(DEV))
+    dz.build_index(ix, torch.from_numpy(X).to(DEV), lens)
+    dc, qc = orc.hash_i8(X, R, L, Cb), orc.hash_i8(Q, R, L, Cb)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    qo = np.concatenate([[0], np.cumsum(q_lens)])
+    Qd = torch.from_numpy(Q).to(DEV)
+    cand = np.array([2, 7, 2, 0, 6, 1], dtype=np.int64)
+    cand_dev = torch.from_numpy(np.tile(cand, (3, 1)).astype(np.int32)).to(DEV)
+    forms = [(dz.SCORE_RAW_COUNTS, lambda q, sel: orc.scores(dc, off, q, sel)),
+             (dz.SCORE_EQ1_Q16, lambda q, sel: orc.scores_eq1(dc, off, q, Cb, sel)),
+             (dz.SCORE_MEAN_IDENTITY_Q16, lambda q, sel: orc.scores_general(dc, off, q, orc.PHI_IDENTITY, orc.SIGMA_MEAN, doc_ids=sel))]
+    want = {t: [(ref(qc[qo[b]:qo[b + 1]], None), ref(qc[qo[b]:qo[b + 1]], cand)) for b in range(3)] for t, ref in forms}
+    for algo in (dz.SCORE_MASKLUT, dz.SCORE_BYTECMP):
+        dz.set_algo(ix, dz.HASH_AUTO, algo)
+        for transform, _ in forms:
+            if transform == dz.SCORE_MEAN_IDENTITY_Q16 and algo == dz.SCORE_MASKLUT:
+                continue                        # documents over 65 535 vectors: the mean runs on the code-compare kernel
+            dz.set_score_transform(ix, transform)
+            got = dz.scores(ix, Qd, q_lens).cpu().numpy()
+            gotc = dz.scores(ix, Qd, q_lens, cand_ids=cand_dev).cpu().numpy().reshape(3, len(cand))
+            for b in range(3):
+                assert np.array_equal(got[b], want[transform][b][0]), (algo, transform, b)
+                assert np.array_equal(gotc[b], want[transform][b][1]), (algo, transform, b)
+    dz.set_algo(ix, dz.HASH_AUTO, dz.SCORE_AUTO)
+    dz.set_score_transform(ix, dz.SCORE_MEAN_IDENTITY_Q16)  # AUTO routes the mean to the kernel that takes such lengths
+    got = dz.scores(ix, Qd, q_lens).cpu().numpy()
+    assert np.array_equal(got[0], want[dz.SCORE_MEAN_IDENTITY_Q16][0][0])
+
+
 def test_determinism_same_inputs_twice():
     say("determinism cfg3-reduced")
     w = gen.make(3, n_docs=20000, n_queries=4, n_cand=512)
