@@ -93,9 +93,15 @@ __global__ __launch_bounds__(256) void filter_gemm_kernel(const int8_t* __restri
                                                           const v4i* __restrict__ Cp, const v4i* __restrict__ T2,
                                                           uint32_t tiles, uint32_t K, uint32_t tiles_per_range,
                                                           uint32_t* __restrict__ assign, int32_t* __restrict__ out,
-                                                          int64_t* __restrict__ lists) {
+                                                          int64_t* __restrict__ lists, uint32_t zero_words) {
     constexpr int D = KS * 32;
     constexpr int P = MODE > 0 ? MODE : 1;
+    // list modes do not write `assign`: there it names zero_words words that the first workgroup clears for the kernel
+    // that follows (the counting kernel's list lengths), which saves a launch on the single-query path
+    if constexpr (MODE > 0) {
+        if (zero_words && blockIdx.x == 0 && blockIdx.y == 0)
+            for (uint32_t i = threadIdx.x; i < zero_words; i += 256) assign[i] = 0;
+    }
     // a list of one entry is an argmax: MODE = 1 keeps the 32-bit running key of MODE = 0 (no 64-bit list
     // inserts in the loop) and forms its list entry at the end
     constexpr bool ARGMAX = MODE == 0 || MODE == 1;
@@ -680,7 +686,7 @@ hipError_t launch_filter_prep(const int8_t* Cn, uint32_t K, uint32_t d, void* Cp
 template <int NT, int MODE>
 static hipError_t launch_gemm(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                               uint32_t ranges, uint32_t tiles_per_range, uint32_t* assign, int32_t* out, int64_t* lists,
-                              hipStream_t stream) {
+                              hipStream_t stream, uint32_t zero_words = 0) {
     if (n == 0) return hipSuccess;
     uint64_t blocks = (n + 4 * 32 * NT - 1) / (4 * 32 * NT);
     if (blocks > 0x7fffffffull || ranges == 0 || ranges > 65535) return hipErrorInvalidValue;
@@ -689,11 +695,11 @@ static hipError_t launch_gemm(const int8_t* X, uint64_t n, uint32_t d, uint32_t 
         return hipErrorInvalidValue;  // every range must hold at least one tile and together they cover all
     dim3 grid((unsigned)blocks, ranges), block(256);
     if (d == 64)
-        hipLaunchKernelGGL((filter_gemm_kernel<2, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
+        hipLaunchKernelGGL((filter_gemm_kernel<2, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists, zero_words);
     else if (d == 128)
-        hipLaunchKernelGGL((filter_gemm_kernel<4, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
+        hipLaunchKernelGGL((filter_gemm_kernel<4, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists, zero_words);
     else if (d == 256)
-        hipLaunchKernelGGL((filter_gemm_kernel<8, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists);
+        hipLaunchKernelGGL((filter_gemm_kernel<8, NT, MODE>), grid, block, 0, stream, X, n, (const v4i*)Cp, (const v4i*)T2, tiles, K, tiles_per_range, assign, out, lists, zero_words);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -738,7 +744,7 @@ FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe) {
 
 hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                      uint32_t probe, const FilterProbePlan& pl, int64_t* lists, uint32_t* probe_ids,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, uint32_t* zero, uint32_t zero_words) {
     if (n == 0) return hipSuccess;
     if (pl.ranges == 0 || probe > K || pl.width != list_width(probe)) return hipErrorInvalidValue;
     hipError_t e;
@@ -746,26 +752,26 @@ hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, ui
     const dim3 mgrid((unsigned)((n + 255) / 256)), mblock(256);
     switch (pl.width) {
         case 1:
-            e = pl.nt == 2 ? launch_gemm<2, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
-                           : launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words)
+                           : launch_gemm<1, 1>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge1_kernel, dim3((unsigned)((n + 3) / 4)), mblock, 0, stream, lists, n, per_vec, probe_ids);
             break;
         case 2:
-            e = pl.nt == 2 ? launch_gemm<2, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
-                           : launch_gemm<1, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words)
+                           : launch_gemm<1, 2>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<2>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
         case 4:
-            e = pl.nt == 2 ? launch_gemm<2, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
-                           : launch_gemm<1, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words)
+                           : launch_gemm<1, 4>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<4>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
         default:
-            e = pl.nt == 2 ? launch_gemm<2, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream)
-                           : launch_gemm<1, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, nullptr, nullptr, lists, stream);
+            e = pl.nt == 2 ? launch_gemm<2, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words)
+                           : launch_gemm<1, 8>(X, n, d, K, Cp, T2, pl.ranges, pl.tiles_per_range, zero, nullptr, lists, stream, zero_words);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(filter_merge_kernel<8>, mgrid, mblock, 0, stream, lists, n, per_vec, probe, probe_ids);
             break;
@@ -854,10 +860,12 @@ FilterHistPlan filter_hist_plan(uint32_t n_queries, uint32_t max_pairs, uint64_t
     return hp;
 }
 
+uint64_t filter_count_zero_words(const FilterHistPlan& hp, uint32_t n_queries) { return hp.rows ? n_queries : hp.seg_off; }
+
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
                                FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
-                               uint64_t list_stride, uint32_t* cursor, hipStream_t stream) {
+                               uint64_t list_stride, uint32_t* cursor, hipStream_t stream, bool zeroed) {
     if (n_queries == 0) return hipSuccess;
     if (n_queries > 65535 || n_docs > 0xFFFFFFFEull) return hipErrorInvalidValue;
     const FilterHistPlan hp = filter_hist_plan(n_queries, max_pairs, n_docs, sp);
@@ -865,10 +873,11 @@ hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint
     uint32_t* hist = hist_bins ? cursor + hp.hist_off : nullptr;
     uint32_t* segs = hp.rows ? cursor + hp.seg_off : nullptr;
     // the list lengths start from zero, and so does a histogram that is added up with atomics (rows are stored)
-    const uint64_t zero_words = hp.rows ? n_queries : hp.seg_off;
+    const uint64_t zero_words = filter_count_zero_words(hp, n_queries);
     uint64_t zb = (zero_words + 1023) / 1024;
-    hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, (int32_t*)cursor,
-                       zero_words);
+    if (!zeroed)
+        hipLaunchKernelGGL(filter_zero_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, (int32_t*)cursor,
+                           zero_words);
     if (n_docs == 0 || total_q == 0) return hipGetLastError();
     const uint32_t W = hp.counter_bytes;
     const uint64_t slab_docs = hp.slab_docs;

@@ -120,9 +120,10 @@ struct FilterProbePlan {
     size_t list_bytes;  // int64 lists[n][ranges][2][width]
 };
 FilterProbePlan filter_probe_plan(uint64_t n, uint32_t K, uint32_t probe);
+// zero / zero_words: words the launch also clears (nullptr / 0: none), for the kernel that follows it.
 hipError_t launch_filter_probe_lists(const int8_t* X, uint64_t n, uint32_t d, uint32_t K, const void* Cp, const void* T2,
                                      uint32_t probe, const FilterProbePlan& plan, int64_t* lists, uint32_t* probe_ids,
-                                     hipStream_t stream);
+                                     hipStream_t stream, uint32_t* zero = nullptr, uint32_t zero_words = 0);
 // A bucket is stored as S sub-buckets by document range (sub-bucket s of centroid c holds the bucket's documents
 // with id >> sub_shift == s), so that a query-side workgroup that counts one range of documents reads only that
 // part of every bucket it probes.  sub_off [K*S+1] are the sub-bucket starts in bucket_docs; bucket_off[c] = sub_off[c*S].
@@ -153,10 +154,13 @@ FilterHistPlan filter_hist_plan(uint32_t n_queries, uint32_t max_pairs, uint64_t
 // Per query set: one key (count, id) per document that at least one probed bucket holds, lists[b][0..cursor[b]).
 // max_pairs bounds (vectors of a query set) * probe, i.e. the largest possible count.  cursor: filter_hist_plan().words
 // u32 words (see above).
+// The kernel needs the first filter_count_zero_words() words of cursor cleared: zeroed = true says an earlier launch
+// has done that.
+uint64_t filter_count_zero_words(const FilterHistPlan& hp, uint32_t n_queries);
 hipError_t launch_filter_count(const uint32_t* probe_ids, uint64_t total_q, uint32_t probe, uint32_t max_pairs,
                                const uint32_t* q_off, uint32_t q_uniform, uint32_t n_queries, const uint32_t* sub_off,
                                FilterSubPlan sp, const uint32_t* bucket_docs, uint64_t n_docs, uint64_t* lists,
-                               uint64_t list_stride, uint32_t* cursor /*out*/, hipStream_t stream);
+                               uint64_t list_stride, uint32_t* cursor /*out*/, hipStream_t stream, bool zeroed = false);
 
 // ---- top-k (Alg. 2 last line, k best instead of argmax) ---------------------
 struct TopkArgs {
