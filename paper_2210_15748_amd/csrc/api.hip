@@ -957,8 +957,10 @@ dessert_status_t dessert_filter_kmeans(const dessert_index_t* ix, const int8_t* 
 
 namespace {
 struct FilterWorkspace {
-    size_t dist, probe_ids, q_off, cursor, lists, list_stride, total;
+    size_t dist, probe_ids, q_off, cursor, emit_plan, lists, list_stride, total;
 };
+// At most this many query sets in a call: the list selection runs in its two-launch form (launch_topk_lists)
+constexpr uint32_t FILTER_FEW_LISTS = 64;
 // max_q: vectors of the longest query set
 FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total_q, uint32_t max_q, uint32_t probe) {
     FilterWorkspace w{};
@@ -969,6 +971,7 @@ FilterWorkspace carve_filter(const dessert_index* ix, uint32_t B, uint64_t total
     w.probe_ids = p; p += align_up((size_t)total_q * probe * 4, 256);
     w.q_off = p;     p += align_up(((size_t)B + 1) * 4, 256);
     w.cursor = p;    p += align_up(filter_hist_plan(B, max_q * probe, ix->n_docs, ix->f_sub).words * 4, 256);  // list lengths + count histograms
+    w.emit_plan = p; p += align_up((size_t)FILTER_FEW_LISTS * TOPK_LISTS_EMIT_WORDS * 4, 256);
     // a query set hits at most (its vectors * probe) buckets of at most f_max_bucket documents each
     uint64_t hit = (uint64_t)max_q * probe * ix->f_max_bucket;
     if (hit > ix->n_docs) hit = ix->n_docs;
@@ -1053,7 +1056,8 @@ dessert_status_t filter_query_impl(const dessert_index_t* cix, const void* q_vec
                                 ix->stream, gemm_clears));
     HIP_TRY(launch_topk_lists(lists, w.list_stride, cursor, n_queries, filter_k, max_q * filter_probe,
                               ix->n_docs ? ix->n_docs - 1 : 0, (ix->n_docs && total_q) ? &hp : nullptr, out_ids_dev,
-                              out_counts_dev, ordered, ix->stream));
+                              out_counts_dev, ordered, ix->stream,
+                              (!ordered && n_queries <= FILTER_FEW_LISTS) ? (uint32_t*)(ws + w.emit_plan) : nullptr));
     return DESSERT_OK;
 }
 

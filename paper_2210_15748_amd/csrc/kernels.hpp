@@ -187,8 +187,12 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream);
 // start of that array): the selection then skips its first pass over a list and, with rows, decides the id digits
 // inside one slab's run.  ordered = false: the k best of a list are written in no particular order (their set is
 // the same; saves the sort when only the set matters).
+// emit_plan (unordered results only): nullptr, or TOPK_LISTS_EMIT_WORDS u32 words of scratch per list; the selection
+// then runs as two launches, the second of which copies the selected keys with many workgroups per list (for a handful
+// of long lists, where one workgroup per list would leave the chip idle during that pass).
+constexpr uint32_t TOPK_LISTS_EMIT_WORDS = 8;
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
                              uint32_t k, uint32_t max_score, uint64_t max_id, const FilterHistPlan* hp, uint32_t* out_ids,
-                             int32_t* out_scores, bool ordered, hipStream_t stream);
+                             int32_t* out_scores, bool ordered, hipStream_t stream, uint32_t* emit_plan = nullptr);
 
 }  // namespace dessert

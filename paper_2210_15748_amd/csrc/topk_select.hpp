@@ -277,8 +277,12 @@ __device__ void bitonic_sort_lds(uint64_t* a, uint32_t npad) {
 // first_hist: optional, leading_score_bins() counters (see there).  dir: optional, see SlabDirectory (key sources
 // with SEGMENTS only); it replaces first_hist.
 // ORDERED = false: the k best keys are left in `sorted` in no particular order (callers that only need the set).
-template <int T, typename Keys, int U = 4, bool CACHE = false, bool ORDERED = true>
-__device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
+// EMIT = false: when the selection ends in a pass over the whole list that copies the keys at or above the k-th one,
+// that pass is left to the caller: the function returns false with the k-th key in sh.prefix and the number of its
+// copies that belong to the result in sh.need (`sorted` then holds nothing).  It returns true when `sorted` holds the
+// result (always with EMIT = true); the value is the same for every thread.
+template <int T, typename Keys, int U = 4, bool CACHE = false, bool ORDERED = true, bool EMIT = true>
+__device__ bool block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t kpad, uint64_t* sorted,
                              SelectShared& sh, const KeyPlan& plan, const uint32_t* first_hist = nullptr,
                              const SlabDirectory* dir = nullptr) {
     const uint32_t tid = threadIdx.x;
@@ -499,7 +503,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                     bitonic_sort_lds<T>(gathered, gpad);
                     for (uint32_t i = tid; i < k; i += T) sorted[i] = gathered[i];
                     __syncthreads();
-                    return;
+                    return true;
                 }
                 if (by_dir) {
                     // The keys of the threshold bin rank slab by slab: thread s takes slab s's count of them, an
@@ -530,6 +534,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
                 }
             }
         }
+        if constexpr (!EMIT) return false;
         const K kth = (K)sh.prefix;        // the k-th largest key
         const uint32_t need_eq = sh.need;  // copies of it that belong to the result
         append_pass(sorted, [&](K key) {
@@ -539,7 +544,7 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
         });
     }
     __syncthreads();
-    if constexpr (!ORDERED) return;
+    if constexpr (!ORDERED) return true;
     // 1 to 16 keys per thread: sort in registers
     if (kpad >= (uint32_t)T && kpad <= 16u * T) {
         switch (kpad / T) {
@@ -549,9 +554,10 @@ __device__ void block_select(const Keys& keys, uint64_t n, uint32_t k, uint32_t 
             case 8: bitonic_sort_regs<T, 8, K>(sorted); break;
             default: bitonic_sort_regs<T, 16, K>(sorted); break;
         }
-        return;
+        return true;
     }
     bitonic_sort_lds<T>(sorted, kpad);
+    return true;
 }
 
 // Key sources.  operator()(i) = key i; load(i, n, out) = the VEC keys i .. i+VEC-1 (i a multiple of VEC; entries at or

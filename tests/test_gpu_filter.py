@@ -153,6 +153,9 @@ def test_filter_then_search_chain_with_empty_slots():
 @pytest.mark.parametrize("probe,filter_k,k,q_lens,n_docs,max_len", [
     (1, 512, 10, [32] * 6, 20_000, 40),        # equal lengths, lists filled
     (1, 4096, 10, [32], 200_000, 3),           # one query set: the single-query form of the chain
+    (1, 4096, 4096, [32], 200_000, 3),         # the same with k = filter_k: every selected candidate is compared
+    (2, 1000, 1000, [9] * 40, 60_000, 3),      # 40 lists: still the two-launch selection; k = filter_k
+    (1, 700, 700, [16] * 70, 60_000, 3),       # 70 lists: one workgroup per list
     (2, 300, 50, [5, 40, 1, 33], 1500, 12),    # unequal query sets
     (4, 16, 16, [32, 7], 1500, 12),            # k = filter_k
     (8, 4096, 100, [12, 7], 1500, 12),         # fewer hit documents than filter_k: empty slots reach the scoring
