@@ -120,9 +120,9 @@ hipError_t launch_hash_scalar(const void* X, uint32_t dtype, uint64_t n, uint32_
 // M-tile make one code.  A code row is LT*4 bytes either way (LT = L/4 M-tiles, or L/2 when WIDE)
 // and lane-half g owns the g-th half of it.
 // Table groups: with more tables than one launch takes (a code row of more than 64 bytes: L = 128 one-byte codes, L = 64
-// 16-bit codes) the tables are hashed in groups of 64 bytes of code row, one launch per group: `codes` then points at the
-// group's first byte of row 0, Rp at the group's matrix, and row_bytes (bytes from one vector's codes to the next) is the
-// full row.  The vectors are read once per group.
+// 16-bit codes; or a matrix over 64 KB: d = 256 from 32 bytes of code row on) the tables are hashed in groups, one launch
+// per group: `codes` then points at the group's first byte of row 0, Rp at the group's matrix, and row_bytes (bytes from
+// one vector's codes to the next) is the full row.  The vectors are read once per group.
 // FUSED: the workgroups from hash_blocks on do not hash; workgroup hash_blocks + b groups candidate list b by
 // document id range (cand_order.hpp), with the LDS that holds R otherwise as its bins.
 // Threads per workgroup: a 64 KB matrix lets a CU hold two workgroups, and with four waves each the MFMA, the sign packing
@@ -276,35 +276,38 @@ static bool mfma_shape(uint32_t d, uint32_t L) {
     return (d == 64 || d == 128 || d == 256) && (L == 16 || L == 32 || L == 64);
 }
 
-// Tables per launch: at most 64 bytes of code row (the re-ordered matrix of a launch has to fit 64 KB of LDS)
-static uint32_t group_tables(uint32_t L, uint32_t C) {
-    const uint32_t cap = C <= 8 ? 64 : 32;
-    return L < cap ? L : cap;
-}
 static bool group_supported(uint32_t d, uint32_t Lg, uint32_t C) {
     if (!(d == 64 || d == 128 || d == 256) || C < 1 || C > 16) return false;
     if (!(Lg == 8 || Lg == 16 || Lg == 32 || (Lg == 64 && C <= 8))) return false;
     const uint32_t lt = mfma_tiles(Lg, C);  // 2, 4, 8 or 16
     return (size_t)lt * (d / 32) * 1024 <= 64 * 1024;
 }
+// Tables per launch: the largest group (at most 64 bytes of code row) whose re-ordered matrix fits 64 KB of LDS;
+// 0 if L is not a multiple of a supported group
+static uint32_t group_tables(uint32_t d, uint32_t L, uint32_t C) {
+    for (uint32_t Lg = 64; Lg >= 8; Lg /= 2)
+        if (Lg <= L && L % Lg == 0 && group_supported(d, Lg, C)) return Lg;
+    return 0;
+}
 static size_t group_proj_bytes(uint32_t d, uint32_t Lg, uint32_t C) { return (size_t)mfma_tiles(Lg, C) * (d / 32) * 64 * 16; }
 
 size_t mfma_proj_bytes(uint32_t d, uint32_t L, uint32_t C) {
     if (!hash_mfma_supported(d, L, C)) return 0;
-    const uint32_t Lg = group_tables(L, C);
+    const uint32_t Lg = group_tables(d, L, C);
     return (L / Lg) * group_proj_bytes(d, Lg, C);
 }
 
-// L in {8, 16, 32, 64}, and 128 with one-byte codes (two groups of 64 tables); the groups' matrices must fit LDS
+// L in {8, 16, 32, 64, 128}, hashed in groups of tables whose matrix fits LDS (one group up to 64 bytes of code row
+// at d <= 128)
 bool hash_mfma_supported(uint32_t d, uint32_t L, uint32_t C) {
     if (C < 1 || C > 16) return false;
-    if (!(L == 8 || L == 16 || L == 32 || L == 64 || (L == 128 && C <= 8))) return false;
-    return group_supported(d, group_tables(L, C), C);
+    if (!(L == 8 || L == 16 || L == 32 || L == 64 || L == 128)) return false;
+    return group_tables(d, L, C) != 0;
 }
 
 hipError_t launch_repack_proj_i8(const int8_t* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
     if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
-    const uint32_t Lg = group_tables(L, C);
+    const uint32_t Lg = group_tables(d, L, C);
     const uint32_t total = (uint32_t)group_proj_bytes(d, Lg, C);
     for (uint32_t grp = 0; grp < L / Lg; ++grp) {   // group grp = tables grp*Lg .. : rows grp*Lg*C .. of R
         hipLaunchKernelGGL(repack_proj_i8_kernel, dim3((total + 255) / 256), dim3(256), 0, stream,
@@ -348,7 +351,7 @@ static hipError_t launch_mfma_t(const int8_t* X, uint64_t n, uint32_t C, const v
 // ranges the fused grouping may use: the bins live in the LDS that holds R in the hashing workgroups
 uint32_t hash_mfma_fused_ranges(uint32_t d, uint32_t L, uint32_t C) {
     if (!hash_mfma_supported(d, L, C)) return 0;
-    const size_t words = group_proj_bytes(d, group_tables(L, C), C) / 4;
+    const size_t words = group_proj_bytes(d, group_tables(d, L, C), C) / 4;
     uint32_t r = 1;
     while ((size_t)r * 2 <= words && r < 4096) r *= 2;
     return r;
@@ -358,7 +361,7 @@ hipError_t launch_hash_mfma_i8(const int8_t* X, uint64_t n, uint32_t d, uint32_t
                                uint8_t* codes, const CandOrderArgs* fused, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!hash_mfma_supported(d, L, C)) return hipErrorInvalidValue;
-    const uint32_t Lg = group_tables(L, C), groups = L / Lg;
+    const uint32_t Lg = group_tables(d, L, C), groups = L / Lg;
     const uint32_t lt = mfma_tiles(Lg, C);
     const uint32_t code_bytes = C <= 8 ? 1 : 2;
     const uint32_t row_bytes = L * code_bytes;

@@ -55,7 +55,7 @@ def test_hash_i8_bit_exact_ragged_sizes(algo, n):
 
 @pytest.mark.parametrize("d,L,Cb", [(128, 16, 6), (64, 16, 1), (256, 32, 8), (128, 64, 5), (64, 64, 8), (256, 16, 4),
                                     # more than 64 bytes of code row: hashed in table groups, one launch per group
-                                    (128, 128, 5), (64, 128, 8), (128, 128, 1)])
+                                    (128, 128, 5), (64, 128, 8), (128, 128, 1), (256, 64, 8), (256, 128, 5)])
 def test_hash_mfma_shapes(d, L, Cb):
     say(f"hash mfma d={d} L={L} C={Cb}")
     rng = np.random.default_rng(d + L + Cb)

@@ -47,7 +47,7 @@ def test_hash_wide_and_l8_bit_exact(d, L, Cb, n):
 @pytest.mark.parametrize("d,L,Cb", [(128, 8, 11), (128, 8, 9), (64, 8, 16), (256, 8, 10), (128, 16, 12), (64, 32, 9),
                                     (128, 32, 16), (256, 16, 13), (128, 8, 1), (64, 8, 8), (256, 8, 5), (128, 8, 7),
                                     # 128 bytes of code row: two launches of 32 tables each
-                                    (128, 64, 9), (64, 64, 16)])
+                                    (128, 64, 9), (64, 64, 16), (256, 32, 12), (256, 64, 9), (128, 128, 9)])
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4099])
 def test_hash_mfma_wide_and_l8_shapes(algo, d, L, Cb, n):
     say(f"hash algo={algo} d={d} L={L} C={Cb} n={n}")
