@@ -271,10 +271,11 @@ __global__ void repack_proj_i8_kernel(const int8_t* __restrict__ R, uint32_t d, 
 // M-tiles of 32 projection rows: L/4 with one-byte codes, L/2 with 16-bit codes
 static uint32_t mfma_tiles(uint32_t L, uint32_t C) { return C <= 8 ? L / 4 : L / 2; }
 
-// shapes of the fp16 kernel (one-byte codes only)
+// shapes of the fp16 kernel (one-byte codes only); L = 128 is hashed as two groups of 64 tables, one launch each
 static bool mfma_shape(uint32_t d, uint32_t L) {
-    return (d == 64 || d == 128 || d == 256) && (L == 16 || L == 32 || L == 64);
+    return (d == 64 || d == 128 || d == 256) && (L == 8 || L == 16 || L == 32 || L == 64 || L == 128);
 }
+static uint32_t f16_group_tables(uint32_t L) { return L < 64 ? L : 64; }
 
 static bool group_supported(uint32_t d, uint32_t Lg, uint32_t C) {
     if (!(d == 64 || d == 128 || d == 256) || C < 1 || C > 16) return false;
@@ -408,7 +409,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 template <int KS, int LT, int NT, int WV>  // KS = d/16 k-steps, LT = L/4 M-tiles, NT n-tiles of 32 vectors per wave, WV waves per workgroup
 __global__ __launch_bounds__(WV * 64, 2) void hash_mfma_f16_kernel(const _Float16* __restrict__ X, uint64_t n,
                                                             const v8h* __restrict__ Rp, uint32_t cmask,
-                                                            uint8_t* __restrict__ codes) {
+                                                            uint8_t* __restrict__ codes, uint32_t row_bytes) {
     constexpr int D = KS * 16;
     constexpr int L = LT * 4;
     constexpr int OW = LT / 2;
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(WV * 64, 2) void hash_mfma_f16_kernel(const _Float1
         for (int nt = 0; nt < NT; ++nt) {
             uint64_t v = v0 + nt * 32 + col;
             if (v < n) {
-                uint32_t* dst = (uint32_t*)(codes + v * L + g * (L / 2));
+                uint32_t* dst = (uint32_t*)(codes + v * row_bytes + g * (L / 2));
 #pragma unroll
                 for (int w = 0; w < OW; ++w) dst[w] = outw[nt][w];
             }
@@ -549,22 +550,24 @@ __global__ void repack_proj_f16_kernel(const float* __restrict__ R, uint32_t d, 
 
 size_t mfma_f16_proj_bytes(uint32_t d, uint32_t L) {
     if (!mfma_shape(d, L)) return 0;
-    return (size_t)(L / 4) * 2 * (d / 16) * 64 * 16;
+    return (size_t)(L / 4) * 2 * (d / 16) * 64 * 16;  // the groups' matrices one after the other
 }
 
 bool hash_mfma_f16_supported(uint32_t d, uint32_t L, uint32_t C) { return mfma_shape(d, L) && C >= 1 && C <= 8; }
 
 hipError_t launch_repack_proj_f16(const float* R, uint32_t d, uint32_t L, uint32_t C, void* Rp, hipStream_t stream) {
-    uint32_t total = (uint32_t)(mfma_f16_proj_bytes(d, L) / 2);
-    if (!total) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(repack_proj_f16_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, R, d, L, C,
-                       (_Float16*)Rp, total);
+    if (!mfma_shape(d, L)) return hipErrorInvalidValue;
+    const uint32_t Lg = f16_group_tables(L);
+    const uint32_t total = (uint32_t)(mfma_f16_proj_bytes(d, Lg) / 2);  // halves per group
+    for (uint32_t grp = 0; grp < L / Lg; ++grp)
+        hipLaunchKernelGGL(repack_proj_f16_kernel, dim3((total + 255) / 256), dim3(256), 0, stream,
+                           R + (size_t)grp * Lg * C * d, d, Lg, C, (_Float16*)Rp + (size_t)grp * total, total);
     return hipGetLastError();
 }
 
 template <int KS, int LT>
 static hipError_t launch_mfma_f16_t(const void* X, uint64_t n, uint32_t C, const void* Rp, uint8_t* codes,
-                                    hipStream_t stream) {
+                                    uint32_t row_bytes, hipStream_t stream) {
     constexpr int NT = 2;
     // eight waves share each staged tile of R when a tile is large (d = 256: 32 KB), four otherwise
     constexpr int WV = KS >= 16 ? 8 : 4;
@@ -574,7 +577,7 @@ static hipError_t launch_mfma_f16_t(const void* X, uint64_t n, uint32_t C, const
     if (blocks > persistent) blocks = persistent;
     auto kern = hash_mfma_f16_kernel<KS, LT, NT, WV>;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WV * 64), 0, stream, (const _Float16*)X, n, (const v8h*)Rp,
-                       (1u << C) - 1u, codes);
+                       (1u << C) - 1u, codes, row_bytes);
     return hipGetLastError();
 }
 
@@ -582,19 +585,29 @@ hipError_t launch_hash_mfma_f16(const void* X, uint64_t n, uint32_t d, uint32_t 
                                 uint8_t* codes, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!hash_mfma_f16_supported(d, L, C)) return hipErrorInvalidValue;
+    const uint32_t Lg = f16_group_tables(L);
+    for (uint32_t grp = 0; grp < L / Lg; ++grp) {
+        const void* Rg = (const char*)Rp + (size_t)grp * mfma_f16_proj_bytes(d, Lg);
+        uint8_t* cg = codes + (size_t)grp * Lg;
+        hipError_t e = hipErrorInvalidValue;
 #define DESSERT_MFMA_F16_CASE(KS_, LT_) \
-    if (d == KS_ * 16 && L == LT_ * 4) return launch_mfma_f16_t<KS_, LT_>(X, n, C, Rp, codes, stream);
-    DESSERT_MFMA_F16_CASE(4, 4)
-    DESSERT_MFMA_F16_CASE(4, 8)
-    DESSERT_MFMA_F16_CASE(4, 16)
-    DESSERT_MFMA_F16_CASE(8, 4)
-    DESSERT_MFMA_F16_CASE(8, 8)
-    DESSERT_MFMA_F16_CASE(8, 16)
-    DESSERT_MFMA_F16_CASE(16, 4)
-    DESSERT_MFMA_F16_CASE(16, 8)
-    DESSERT_MFMA_F16_CASE(16, 16)
+    if (d == KS_ * 16 && Lg == LT_ * 4) e = launch_mfma_f16_t<KS_, LT_>(X, n, C, Rg, cg, L, stream);
+        DESSERT_MFMA_F16_CASE(4, 2)
+        DESSERT_MFMA_F16_CASE(4, 4)
+        DESSERT_MFMA_F16_CASE(4, 8)
+        DESSERT_MFMA_F16_CASE(4, 16)
+        DESSERT_MFMA_F16_CASE(8, 2)
+        DESSERT_MFMA_F16_CASE(8, 4)
+        DESSERT_MFMA_F16_CASE(8, 8)
+        DESSERT_MFMA_F16_CASE(8, 16)
+        DESSERT_MFMA_F16_CASE(16, 2)
+        DESSERT_MFMA_F16_CASE(16, 4)
+        DESSERT_MFMA_F16_CASE(16, 8)
+        DESSERT_MFMA_F16_CASE(16, 16)
 #undef DESSERT_MFMA_F16_CASE
-    return hipErrorInvalidValue;
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------

@@ -102,7 +102,9 @@ def test_hash_scalar_odd_shapes_and_seed_rule():
 
 
 @pytest.mark.parametrize("algo", [dz.HASH_SCALAR, dz.HASH_MFMA])
-@pytest.mark.parametrize("d,L,Cb,n", [(256, 64, 8, 5000), (128, 32, 7, 1000), (64, 16, 3, 333)])
+@pytest.mark.parametrize("d,L,Cb,n", [(256, 64, 8, 5000), (128, 32, 7, 1000), (64, 16, 3, 333),
+                                      # L = 128: two groups of 64 tables; L = 8: a single dword of codes per lane half
+                                      (128, 128, 8, 3000), (256, 128, 6, 2000), (64, 8, 5, 1000)])
 def test_hash_fp16_gaussian_within_tolerance(algo, d, L, Cb, n):
     say(f"hash f16 x gaussian f32 algo={algo} d={d} L={L} C={Cb} n={n}")
     rng = np.random.default_rng(d + L + Cb)
