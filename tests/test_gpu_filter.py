@@ -160,6 +160,7 @@ def test_filter_then_search_chain_with_empty_slots():
     (4, 16, 16, [32, 7], 1500, 12),            # k = filter_k
     (8, 4096, 100, [12, 7], 1500, 12),         # fewer hit documents than filter_k: empty slots reach the scoring
     (37, 2000, 20, [1800, 5], 150_000, 3),     # 64-bit list keys
+    (37, 2000, 2000, [1800, 5], 150_000, 3),   # the same with k = filter_k: the selected set itself is compared
     (3, 5000, 5000, [20, 32, 7], 100_000, 3)])
 def test_filter_search_equals_filter_then_search_and_the_oracle(probe, filter_k, k, q_lens, n_docs, max_len):
     """dessert_filter_search (one call, candidates unordered in between) against dessert_filter_query + dessert_search
