@@ -377,7 +377,9 @@ def main() -> int:
         # the kernel is bound by the vector ALU.  Algorithmic work = lane-operations of the bit-sliced count per
         # (document vector, chunk of 32 query vectors): one address per table (half when two query sets share the
         # lookups), two per full/half adder of the carry-save tree, two per plane of the running maximum.
-        ops_unit = masklut_lane_ops(p.L, paired=(B >= 2 and p.L * (1 << max(p.C, 6)) * 8 <= 32 * 1024))
+        # (whether two query sets shared the lookups is read off the instantiation the launch picked: its fifth parameter)
+        inst = score_kernel[score_kernel.find("<") + 1:score_kernel.rfind(">")].split(",") if "masklut" in score_kernel else []
+        ops_unit = masklut_lane_ops(p.L, paired=(len(inst) == 6 and inst[4].strip() == "2"))
         chunks = (p.q_len + 31) // 32
         lane_ops = w.n_vectors * B * chunks * ops_unit
         achieved = lane_ops / (score_ms * 1e-3) / 1e12

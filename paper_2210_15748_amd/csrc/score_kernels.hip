@@ -832,9 +832,11 @@ bool score_masklut_supported(uint32_t L, uint32_t C) {
 
 template <int L, int CB, int CW>
 static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char* desc, size_t desc_len) {
-    // two query sets per workgroup when every document is scored for every set and the paired
-    // table (8 bytes per entry) keeps eight workgroups per CU's worth of LDS and 16-bit offsets
-    constexpr bool PAIR_OK = (size_t)L * (1u << CB) * 8 <= 32 * 1024;
+    // two query sets per workgroup when every document is scored for every set and the paired table (8 bytes per entry)
+    // is at most 32 KB, or 64 KB with at most 32 tables (512 threads share it then; the offsets still fit the 16-bit
+    // immediate of an LDS read).  With one set per workgroup those shapes are bound by LDS: half the arithmetic per read.
+    constexpr size_t PAIR_BYTES = (size_t)L * (1u << CB) * 8;
+    constexpr bool PAIR_OK = PAIR_BYTES <= 32 * 1024 || (L <= 32 && PAIR_BYTES <= 64 * 1024);
     bool pair = PAIR_OK && a.cand_ids == nullptr && a.n_queries >= 2 && !a.sigma_mean;  // the mean form takes one set per workgroup
     // documents per workgroup: at most LUT_DOCS; fewer when that would leave the 256 CUs short of
     // workgroups, but at least 64 (32 = one run of 8 documents for each of the four waves when the

@@ -36,7 +36,8 @@ def clustered(rng, n, d, pool, spread):
 
 
 def pair_ok(L, Cb):
-    return L * (1 << max(Cb, 6)) * 8 <= 32 * 1024
+    size = L * (1 << max(Cb, 6)) * 8
+    return size <= 32 * 1024 or (L <= 32 and size <= 64 * 1024)
 
 
 def make_reference(form, dc, off, Cb):
