@@ -250,10 +250,22 @@ constexpr int ilog2_ceil(int x) { return x <= 1 ? 0 : 1 + ilog2_ceil((x + 1) / 2
 constexpr uint32_t LUT_DOCS = 256;  // documents per workgroup (upper bound)
 // Threads per workgroup: a mask table of 32 KB or more limits a CU to a few workgroups, so eight waves share
 // one table instead of four: from 32 KB where the register budget allows it (few tables), always from 64 KB.
-constexpr int masklut_threads(int L, int CB, int W) { return ((L << CB) * 4 * W >= 32 * 1024 && (L <= 16 || L >= 128 || (L << CB) * 4 * W >= 64 * 1024)) ? 512 : 256; }
+// The rotated table order (see below): one-byte codes, one query set per workgroup, 64 or 32 tables.
+// With 32 tables only from 128 entries per table on: the rows of the rotated order are twice the size of the plain table,
+// and the small tables (64 entries) measure faster plain.
+constexpr bool masklut_rotated(int L, int CB, int CW, int W) { return (L == 64 || (L == 32 && CB >= 7)) && CW == 1 && W == 1; }
+// Bytes of LDS the table takes: rows of the rotated order are 256 bytes (64 slots) also with 32 tables.
+constexpr int masklut_table_bytes(int L, int CB, int CW, int W) { return masklut_rotated(L, CB, CW, W) ? (64 << CB) * 4 : (L << CB) * 4 * W; }
+constexpr int masklut_threads(int L, int CB, int CW, int W) {
+    return (masklut_table_bytes(L, CB, CW, W) >= 32 * 1024 &&
+            (L <= 16 || L >= 128 || masklut_table_bytes(L, CB, CW, W) >= 64 * 1024)) ? 512 : 256;
+}
 // Waves per SIMD the register allocation must allow: the rotated form (L = 64) keeps 24 more per-lane
 // constants and would otherwise drop from 4 to 3.
-constexpr int masklut_min_waves(int L, int CW, int W, int REMAP) { return (L == 64 && CW == 1 && W == 1 && REMAP < 3) ? 4 : 1; }
+constexpr int masklut_min_waves(int L, int CB, int CW, int W, int REMAP) {
+    if (L == 64 && CW == 1 && W == 1 && REMAP < 3) return 4;
+    return 1;
+}
 constexpr uint32_t LUT_BINS = 64;   // length classes for the in-block ordering
 
 // Per-workgroup bookkeeping, in static LDS beside the mask table.
@@ -308,16 +320,26 @@ struct LutBlockMeta {
 // byte 0 from a per-lane constant.  (Measured on the fp16 stress preset: scoring 198 -> 102 ms.  The same
 // order for paired L = 32 tables, 8-byte slots, was 7 % slower than M[t][h]: that form is bound by the
 // vector ALU, not by LDS.)
+// With 32 tables (one set per workgroup, 128 or 256 entries per table) the order is used too: candidate scoring with
+// M[t][h] had LDS 95 % busy, 60 % of it conflicts, next to the memory reads it is bound by; rotated it is 2 % faster at
+// C = 7 and 8 % at C = 8, although the 256-byte rows double the table and the second exchange stage costs eight
+// more selects per vector (vector ALU 71 % -> 90 % busy).
 __device__ inline uint32_t rot_slot(uint32_t k, uint32_t b) {  // k = (k3 k2 k1 k0): slot (k1 k3 k2 k0 b1 b0)
     return ((k >> 1) & 1) * 32 + ((k >> 3) & 1) * 16 + ((k >> 2) & 1) * 8 + (k & 1) * 4 + b;
 }
+// L = 32: the eight registers of a code row are permuted by all three lane bits (the two 16-byte halves by the load
+// order, pairs of registers and neighbouring registers by one select each), so the 32 lanes of a half-wave ask for all
+// 32 tables in every read and table t simply sits at slot t of its row (the upper 32 slots of a row stay unused: a row
+// has to start on a multiple of 256 bytes for the one-v_perm address).
+template <int L>
+__device__ inline uint32_t rot_slot_of(uint32_t k, uint32_t b) { return L == 64 ? rot_slot(k, b) : 4 * k + b; }
 
 template <int L, int CB, int CW, int REMAP, int W, bool SPLIT>
-__global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW, W, REMAP)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
+__global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L, CB, CW, W, REMAP)) void score_masklut_kernel(ScoreArgs a, uint32_t docs_per_block, uint32_t gy_linear,
                                                             uint32_t gz_arg) {
-    constexpr bool ROT = (L == 64 && CW == 1 && W == 1);
+    constexpr bool ROT = masklut_rotated(L, CB, CW, W);
     const uint32_t gz = SPLIT ? gz_arg : 1u;
-    constexpr int T = masklut_threads(L, CB, W);
+    constexpr int T = masklut_threads(L, CB, CW, W);
     constexpr int LW = L * CW / 4;  // dwords per code row
     constexpr int STRIDE = 1 << CB;
     constexpr int P = ilog2_ceil(L + 1);  // planes needed for counts 0..L
@@ -329,7 +351,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     constexpr int P2 = P + 15;   // planes of the document's accumulator: S <= L * m < 2^(P-1) * 2^16
     // static LDS: the table sits at a link-time constant address, so t*STRIDE*4*W folds into the
     // immediate offset of each ds_read and the only per-read address arithmetic is one shift
-    constexpr int LUT_WORDS = L * STRIDE * W;
+    constexpr int LUT_WORDS = masklut_table_bytes(L, CB, CW, W) / 4;
     __shared__ __attribute__((aligned(256))) uint32_t lut[LUT_WORDS];  // [t][h][w]; ROT: [h][pos(t)]
     __shared__ LutBlockMeta meta;
 
@@ -376,11 +398,15 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
     };
     auto table_or = [&](int w, uint32_t i, uint32_t h) {
         const uint32_t q = i / L, t = i % L;
-        if constexpr (ROT) atomicOr(&lut[h * 64 + rot_slot(t >> 2, t & 3)], 1u << q);
+        if constexpr (ROT) atomicOr(&lut[h * 64 + rot_slot_of<L>(t >> 2, t & 3)], 1u << q);
         else atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
     };
     auto zero_table = [&]() {
-        for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
+        if constexpr (ROT && L == 32) {  // the used half of every row
+            for (uint32_t i = threadIdx.x; i < 32 * STRIDE; i += T) lut[(i >> 5) * 64 + (i & 31)] = 0;
+        } else {
+            for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
+        }
     };
     const bool have_doc = threadIdx.x < ndocs;
     uint64_t my_id = 0;
@@ -447,10 +473,16 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
 
     const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
     // ROT: lane-dependent table order (see above)
-    uint32_t rot_sel[4], rot_posc[ROT ? LW : 1], rot_quarter[ROT ? LW / 4 : 1], rot_swap = 0;
+    uint32_t rot_sel[4], rot_posc[ROT ? LW : 1], rot_quarter[ROT ? LW / 4 : 1], rot_swap = 0, rot_swap2 = 0;
     if constexpr (ROT) {
-        const uint32_t rb = lane & 3, aq = (lane >> 2) & 3, r0 = (lane >> 4) & 1;
+        // lane bits 0-1: byte rotation; then L = 64: bits 2-3 quarter order, bit 4 neighbour exchange;
+        // L = 32: bit 2 neighbour exchange, bit 3 exchange of register pairs, bit 4 order of the two halves
+        const uint32_t rb = lane & 3;
+        const uint32_t aq = L == 64 ? (lane >> 2) & 3 : (lane >> 4) & 1;
+        const uint32_t r0 = L == 64 ? (lane >> 4) & 1 : (lane >> 2) & 1;
+        const uint32_t r1 = L == 64 ? 0u : (lane >> 3) & 1;
         rot_swap = r0 ? ~0u : 0u;
+        rot_swap2 = r1 ? ~0u : 0u;
 #pragma unroll
         for (int b = 0; b < 4; ++b) rot_sel[b] = 0x0c0c0000u | ((4 + ((b + rb) & 3)) << 8) | b;
 #pragma unroll
@@ -460,7 +492,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
             rot_posc[k] = 0;
 #pragma unroll
             for (int b = 0; b < 4; ++b)
-                rot_posc[k] |= (rot_slot(k ^ r0 ^ (aq << 2), (b + rb) & 3) * 4) << (8 * b);
+                rot_posc[k] |= (rot_slot_of<L>(k ^ r0 ^ (r1 << 1) ^ (aq << 2), (b + rb) & 3) * 4) << (8 * b);
         }
         // keep the per-lane constants in registers (otherwise they are rebuilt inside the loop)
 #pragma unroll
@@ -470,6 +502,7 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
 #pragma unroll
         for (int k = 0; k < LW; ++k) asm volatile("" : "+v"(rot_posc[k]));
         asm volatile("" : "+v"(rot_swap));
+        asm volatile("" : "+v"(rot_swap2));
     }
     for (uint32_t c0 = c_first; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
         if (c0 != c_first) {  // the first chunk's table was built above
@@ -542,10 +575,15 @@ __global__ __launch_bounds__(masklut_threads(L, CB, W), masklut_min_waves(L, CW,
             auto process = [&](const uint32_t (&dw)[LW], int32_t row) {
                 const char* lut_bytes = reinterpret_cast<const char*>(lut);
                 uint32_t off[L];  // byte offset of x's entry within each table
+                uint32_t sw[ROT ? LW : 1];  // ROT: the registers after the exchange of neighbours
+                if constexpr (ROT) {
+#pragma unroll
+                    for (int w = 0; w < LW; ++w) sw[w] = select3(rot_swap, dw[w ^ 1], dw[w]);
+                }
 #pragma unroll
                 for (int w = 0; w < LW; ++w) {
                     if constexpr (ROT) {
-                        const uint32_t v = select3(rot_swap, dw[w ^ 1], dw[w]);
+                        const uint32_t v = L == 32 ? select3(rot_swap2, sw[w ^ 2], sw[w]) : sw[w];
 #pragma unroll
                         for (int b = 0; b < 4; ++b) off[4 * w + b] = __builtin_amdgcn_perm(v, rot_posc[w], rot_sel[b]);
                     } else if constexpr (CW == 1) {
@@ -843,7 +881,7 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
     // documents are long: about 4096 vectors per workgroup keep the table build amortised)
     uint32_t gy = pair ? (a.n_queries + 1) / 2 : a.n_queries;
     const uint64_t mean_len = a.n_docs ? (a.n_vectors + a.n_docs - 1) / a.n_docs : 1;
-    const uint32_t wave_docs = masklut_threads(L, CB, pair ? 2 : 1) / 64 * 8;  // one run of 8 documents per wave
+    const uint32_t wave_docs = masklut_threads(L, CB, CW, pair ? 2 : 1) / 64 * 8;  // one run of 8 documents per wave
     uint32_t dpb_min = wave_docs > 64 ? wave_docs : 64;
     while (dpb_min > wave_docs && (uint64_t)(dpb_min / 2) * mean_len >= 4096) dpb_min /= 2;
     // a single short list (one query set's candidates): even 64 documents per workgroup leave most CUs idle and the launch
@@ -895,7 +933,7 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
             const Kernel kern2 = remap == 2   ? score_masklut_kernel<L, CB, CW, 2, 2, false>
                                  : remap == 1 ? score_masklut_kernel<L, CB, CW, 1, 2, false>
                                               : score_masklut_kernel<L, CB, CW, 0, 2, false>;
-            hipLaunchKernelGGL(kern2, grid, dim3(masklut_threads(L, CB, 2)), 0, stream, a, dpb, gy_linear, 1u);
+            hipLaunchKernelGGL(kern2, grid, dim3(masklut_threads(L, CB, CW, 2)), 0, stream, a, dpb, gy_linear, 1u);
             return hipGetLastError();
         }
     }
@@ -912,7 +950,7 @@ static hipError_t launch_masklut_t(const ScoreArgs& a, hipStream_t stream, char*
                : remap == 2 ? score_masklut_kernel<L, CB, CW, 2, 1, false>
                : remap == 1 ? score_masklut_kernel<L, CB, CW, 1, 1, false>
                             : score_masklut_kernel<L, CB, CW, 0, 1, false>;
-    hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, 1)), 0, stream, a, dpb, gy_linear, gz);
+    hipLaunchKernelGGL(kern, grid, dim3(masklut_threads(L, CB, CW, 1)), 0, stream, a, dpb, gy_linear, gz);
     return hipGetLastError();
 }
 
