@@ -321,16 +321,17 @@ struct LutBlockMeta {
 // order for paired L = 32 tables, 8-byte slots, was 7 % slower than M[t][h]: that form is bound by the
 // vector ALU, not by LDS.)
 // With 32 tables (one set per workgroup, 128 or 256 entries per table) the order is used too: candidate scoring with
-// M[t][h] had LDS 95 % busy, 60 % of it conflicts, next to the memory reads it is bound by; rotated it is 2 % faster at
-// C = 7 and 8 % at C = 8, although the 256-byte rows double the table and the second exchange stage costs eight
-// more selects per vector (vector ALU 71 % -> 90 % busy).
+// M[t][h] had LDS 95 % busy, 60 % of it conflicts, next to the memory reads it is bound by; rotated it is 3 % faster at
+// C = 7 and 8 % at C = 8 (vector ALU 71 % -> 85 % busy: the selects and the permuted loads).
 __device__ inline uint32_t rot_slot(uint32_t k, uint32_t b) {  // k = (k3 k2 k1 k0): slot (k1 k3 k2 k0 b1 b0)
     return ((k >> 1) & 1) * 32 + ((k >> 3) & 1) * 16 + ((k >> 2) & 1) * 8 + (k & 1) * 4 + b;
 }
-// L = 32: the eight registers of a code row are permuted by all three lane bits (the two 16-byte halves by the load
-// order, pairs of registers and neighbouring registers by one select each), so the 32 lanes of a half-wave ask for all
-// 32 tables in every read and table t simply sits at slot t of its row (the upper 32 slots of a row stay unused: a row
-// has to start on a multiple of 256 bytes for the one-v_perm address).
+// L = 32: a row has room for the 32 masks twice, and a row has to start on a multiple of 256 bytes anyway for the
+// one-v_perm address.  Slots 0..31 hold table t at slot t, slots 32..63 hold table t at slot 32 + (t ^ 8).  The eight
+// registers of a code row are permuted by two lane bits (the two 16-byte halves by the load order, neighbouring
+// registers by one select), the bytes by two more, and the fifth bit of the lane picks the copy: in any read the 16
+// lanes that use the first copy ask for 16 different tables, the 16 lanes of the second copy for the same 16 tables,
+// whose slots there have bit 3 flipped, so the 32 lanes still address 32 different banks.
 template <int L>
 __device__ inline uint32_t rot_slot_of(uint32_t k, uint32_t b) { return L == 64 ? rot_slot(k, b) : 4 * k + b; }
 
@@ -398,15 +399,14 @@ __global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L,
     };
     auto table_or = [&](int w, uint32_t i, uint32_t h) {
         const uint32_t q = i / L, t = i % L;
-        if constexpr (ROT) atomicOr(&lut[h * 64 + rot_slot_of<L>(t >> 2, t & 3)], 1u << q);
+        if constexpr (ROT) {
+            atomicOr(&lut[h * 64 + rot_slot_of<L>(t >> 2, t & 3)], 1u << q);
+            if constexpr (L == 32) atomicOr(&lut[h * 64 + 32 + (t ^ 8)], 1u << q);  // the second copy
+        }
         else atomicOr(&lut[(t * STRIDE + h) * W + w], 1u << q);
     };
     auto zero_table = [&]() {
-        if constexpr (ROT && L == 32) {  // the used half of every row
-            for (uint32_t i = threadIdx.x; i < 32 * STRIDE; i += T) lut[(i >> 5) * 64 + (i & 31)] = 0;
-        } else {
-            for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
-        }
+        for (uint32_t i = threadIdx.x; i < LUT_WORDS; i += T) lut[i] = 0;
     };
     const bool have_doc = threadIdx.x < ndocs;
     uint64_t my_id = 0;
@@ -473,16 +473,15 @@ __global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L,
 
     const uint32_t entry_shift = W == 1 ? 2 : 3;  // log2 of the bytes per table entry
     // ROT: lane-dependent table order (see above)
-    uint32_t rot_sel[4], rot_posc[ROT ? LW : 1], rot_quarter[ROT ? LW / 4 : 1], rot_swap = 0, rot_swap2 = 0;
+    uint32_t rot_sel[4], rot_posc[ROT ? LW : 1], rot_quarter[ROT ? LW / 4 : 1], rot_swap = 0;
     if constexpr (ROT) {
         // lane bits 0-1: byte rotation; then L = 64: bits 2-3 quarter order, bit 4 neighbour exchange;
-        // L = 32: bit 2 neighbour exchange, bit 3 exchange of register pairs, bit 4 order of the two halves
+        // L = 32: bit 2 neighbour exchange, bit 3 which copy of the masks, bit 4 order of the two halves
         const uint32_t rb = lane & 3;
         const uint32_t aq = L == 64 ? (lane >> 2) & 3 : (lane >> 4) & 1;
         const uint32_t r0 = L == 64 ? (lane >> 4) & 1 : (lane >> 2) & 1;
-        const uint32_t r1 = L == 64 ? 0u : (lane >> 3) & 1;
+        const uint32_t copy = L == 64 ? 0u : (lane >> 3) & 1;
         rot_swap = r0 ? ~0u : 0u;
-        rot_swap2 = r1 ? ~0u : 0u;
 #pragma unroll
         for (int b = 0; b < 4; ++b) rot_sel[b] = 0x0c0c0000u | ((4 + ((b + rb) & 3)) << 8) | b;
 #pragma unroll
@@ -492,7 +491,10 @@ __global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L,
             rot_posc[k] = 0;
 #pragma unroll
             for (int b = 0; b < 4; ++b)
-                rot_posc[k] |= (rot_slot_of<L>(k ^ r0 ^ (r1 << 1) ^ (aq << 2), (b + rb) & 3) * 4) << (8 * b);
+            {
+                const uint32_t slot = rot_slot_of<L>(k ^ r0 ^ (aq << 2), (b + rb) & 3);
+                rot_posc[k] |= ((copy ? 32 + (slot ^ 8) : slot) * 4) << (8 * b);
+            }
         }
         // keep the per-lane constants in registers (otherwise they are rebuilt inside the loop)
 #pragma unroll
@@ -502,7 +504,6 @@ __global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L,
 #pragma unroll
         for (int k = 0; k < LW; ++k) asm volatile("" : "+v"(rot_posc[k]));
         asm volatile("" : "+v"(rot_swap));
-        asm volatile("" : "+v"(rot_swap2));
     }
     for (uint32_t c0 = c_first; c0 < max_len; c0 += gz * 32) {  // chunks of 32 query vectors
         if (c0 != c_first) {  // the first chunk's table was built above
@@ -575,15 +576,10 @@ __global__ __launch_bounds__(masklut_threads(L, CB, CW, W), masklut_min_waves(L,
             auto process = [&](const uint32_t (&dw)[LW], int32_t row) {
                 const char* lut_bytes = reinterpret_cast<const char*>(lut);
                 uint32_t off[L];  // byte offset of x's entry within each table
-                uint32_t sw[ROT ? LW : 1];  // ROT: the registers after the exchange of neighbours
-                if constexpr (ROT) {
-#pragma unroll
-                    for (int w = 0; w < LW; ++w) sw[w] = select3(rot_swap, dw[w ^ 1], dw[w]);
-                }
 #pragma unroll
                 for (int w = 0; w < LW; ++w) {
                     if constexpr (ROT) {
-                        const uint32_t v = L == 32 ? select3(rot_swap2, sw[w ^ 2], sw[w]) : sw[w];
+                        const uint32_t v = select3(rot_swap, dw[w ^ 1], dw[w]);
 #pragma unroll
                         for (int b = 0; b < 4; ++b) off[4 * w + b] = __builtin_amdgcn_perm(v, rot_posc[w], rot_sel[b]);
                     } else if constexpr (CW == 1) {
