@@ -262,7 +262,9 @@ dessert_status_t dessert_set_debug(dessert_index_t *index, int enable);
  *   bucket_docs_dev     dev, out, room for n_vectors u32 (upper bound of the total bucket size); a
  *                       document appears once per bucket, in unspecified order inside the bucket
  * The two bucket arrays must stay alive while dessert_filter_query is used.  This call waits for the
- * stream (it reads the bucket sizes back: the largest one sizes the query workspace).
+ * stream at its end (it reads the bucket sizes back: the largest one sizes the query workspace).  The
+ * library's own filter buffers are allocated by the first call and kept while n_centroids and the
+ * number of documents' id ranges stay the same: such a later call allocates and frees nothing.
  *
  * dessert_filter_query: for each query vector the filter_probe closest centroids; every document gets
  * one count per (query vector, probed centroid) pair whose bucket holds it; per query set the

@@ -99,6 +99,8 @@ struct dessert_index {
     const uint32_t* f_bucket_off = nullptr;   // caller's
     const uint32_t* f_bucket_docs = nullptr;  // caller's
     uint32_t f_max_bucket = 0;                // most documents in one bucket
+    uint32_t f_alloc_K = 0;                   // sizes the filter buffers above were allocated for
+    size_t f_alloc_sub = 0;
     bool f_built = false;
     int transform = DESSERT_SCORE_RAW_COUNTS;
     char last_score_kernel[128] = "";  // instantiation launched by the last scoring step (dessert_last_score_kernel)
@@ -871,20 +873,29 @@ dessert_status_t dessert_filter_build(dessert_index_t* ix, const int8_t* centroi
     DeviceGuard guard(ix->cfg.device);
     if (!guard.ok) return fail(DESSERT_EHIP, "hipSetDevice(%d) failed", ix->cfg.device);
     ix->f_built = false;
-    HIP_TRY(hipStreamSynchronize(ix->stream));  // earlier filter work may still read the buffers freed below
-    if (ix->f_cent) (void)hipFree(ix->f_cent);
-    if (ix->f_table) (void)hipFree(ix->f_table);
-    if (ix->f_cursor) (void)hipFree(ix->f_cursor);
-    if (ix->f_sub_off) (void)hipFree(ix->f_sub_off);
-    ix->f_cent = ix->f_table = nullptr;
-    ix->f_cursor = ix->f_sub_off = nullptr;
-    ix->f_sub = filter_sub_plan(ix->n_docs, n_centroids);
-    const size_t n_sub = (size_t)n_centroids * ix->f_sub.S;
-    hipError_t e = hipMalloc(&ix->f_cent, filter_centroid_bytes(n_centroids, ix->cfg.d));
-    if (e == hipSuccess) e = hipMalloc(&ix->f_table, filter_table_bytes(n_centroids));
-    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_cursor, n_sub * 4);
-    if (e == hipSuccess) e = hipMalloc((void**)&ix->f_sub_off, (n_sub + 1) * 4);
-    if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipMalloc(filter state): %s", hipGetErrorString(e));
+    const FilterSubPlan sub = filter_sub_plan(ix->n_docs, n_centroids);
+    const size_t n_sub = (size_t)n_centroids * sub.S;
+    // the filter's own buffers are kept from one build to the next while their sizes stay the same (same number of
+    // centroids and of sub-bucket ranges): such a rebuild frees and allocates nothing and runs in stream order
+    if (!ix->f_cent || ix->f_alloc_K != n_centroids || ix->f_alloc_sub != n_sub) {
+        HIP_TRY(hipStreamSynchronize(ix->stream));  // earlier filter work may still read the buffers freed below
+        if (ix->f_cent) (void)hipFree(ix->f_cent);
+        if (ix->f_table) (void)hipFree(ix->f_table);
+        if (ix->f_cursor) (void)hipFree(ix->f_cursor);
+        if (ix->f_sub_off) (void)hipFree(ix->f_sub_off);
+        ix->f_cent = ix->f_table = nullptr;
+        ix->f_cursor = ix->f_sub_off = nullptr;
+        ix->f_alloc_K = 0;
+        ix->f_alloc_sub = 0;
+        hipError_t e = hipMalloc(&ix->f_cent, filter_centroid_bytes(n_centroids, ix->cfg.d));
+        if (e == hipSuccess) e = hipMalloc(&ix->f_table, filter_table_bytes(n_centroids));
+        if (e == hipSuccess) e = hipMalloc((void**)&ix->f_cursor, n_sub * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&ix->f_sub_off, (n_sub + 1) * 4);
+        if (e != hipSuccess) return fail(DESSERT_ENOMEM, "hipMalloc(filter state): %s", hipGetErrorString(e));
+        ix->f_alloc_K = n_centroids;
+        ix->f_alloc_sub = n_sub;
+    }
+    ix->f_sub = sub;
     HIP_TRY(launch_filter_prep(centroids_dev, n_centroids, ix->cfg.d, ix->f_cent, ix->f_table, ix->stream));
     HIP_TRY(launch_filter_assign((const int8_t*)vectors_dev, ix->n_vectors, ix->cfg.d, n_centroids, ix->f_cent,
                                  ix->f_table, assign_dev, ix->stream));

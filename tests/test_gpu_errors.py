@@ -148,6 +148,16 @@ def test_rebuilding_the_index_drops_the_filter():
     for b, (q0, q1) in enumerate([(0, 8), (8, 40)]):
         w_ids, w_cnt = orc.filter_query(Q[q0:q1], Cn2, obo, obd, len(lens2), 2, 20)
         assert np.array_equal(ids.cpu().numpy()[b], w_ids) and np.array_equal(cnt.cpu().numpy()[b], w_cnt), b
+    # once more on the same collection: first with the same number of centroids (the library keeps its buffers), then
+    # with another number (it allocates them again)
+    for K3, first in ((K, 40), (20, 90)):
+        Cn3 = X2[first:first + K3].copy()
+        dz.filter_build(ix, torch.from_numpy(Cn3).to(DEV), X2d)
+        ids, cnt = dz.filter_query(ix, Qd, [8, 32], 2, 20)
+        obo, obd = orc.inverted_index(orc.assign_centroids(X2, Cn3), off2, K3)
+        for b, (q0, q1) in enumerate([(0, 8), (8, 40)]):
+            w_ids, w_cnt = orc.filter_query(Q[q0:q1], Cn3, obo, obd, len(lens2), 2, 20)
+            assert np.array_equal(ids.cpu().numpy()[b], w_ids) and np.array_equal(cnt.cpu().numpy()[b], w_cnt), (K3, b)
 
 
 def test_debug_mode_catches_a_candidate_id_out_of_range():
