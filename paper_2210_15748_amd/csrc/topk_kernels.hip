@@ -21,11 +21,14 @@ uint32_t topk_slices(uint64_t max_scored, uint32_t n_queries) {
 }
 
 // grid (slices, B).  slices == 1: final results; else per-slice keys to a.partial.
-// KT: the width the keys are computed in (uint32_t when keys_fit_32).  Eight loads in flight per thread; a slice of
-// at most 4096 scores stays in registers for all passes.
-template <typename KT>
-__global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, KeyPlan plan, uint32_t slices,
-                                                                   uint32_t kpad) {
+// KT: the width the keys are computed in (uint32_t when keys_fit_32).  T threads with U loads in flight each; a slice of
+// at most T * U = 4096 scores stays in registers for all passes.  T = 512, U = 8 in general; T = 1024, U = 4 when no
+// slice is longer than that (candidate lists): the phases of such a selection are short chains of LDS round trips and
+// barriers, which sixteen waves get through sooner than eight (17 -> 14 us for 256 lists of 4096); on long slices the
+// wider workgroup is slower (0.90 -> 1.20 ms on 8M documents).
+constexpr uint32_t TOPK_THREADS_SHORT = 1024;
+template <typename KT, int T, int U>
+__global__ __launch_bounds__(T) void topk_scores_kernel(TopkArgs a, KeyPlan plan, uint32_t slices, uint32_t kpad) {
     extern __shared__ uint64_t sorted[];
     __shared__ SelectShared sh;
     const uint32_t b = blockIdx.y, s = blockIdx.x;
@@ -41,13 +44,13 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_scores_kernel(TopkArgs a, K
     const uint64_t lo = (uint64_t)s * per < count ? (uint64_t)s * per : count;
     const uint64_t hi = lo + per < count ? lo + per : count;
     ScoreKeysT<KT> keys{a.scores + base + lo, a.cand_ids ? a.cand_ids + base + lo : nullptr, lo, plan.id_bits};
-    block_select<TOPK_THREADS, ScoreKeysT<KT>, 8, true>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
+    block_select<T, ScoreKeysT<KT>, U, true>(keys, hi - lo, a.k, kpad, sorted, sh, plan);
     if (slices == 1) {
-        for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS)
+        for (uint32_t i = threadIdx.x; i < a.k; i += T)
             write_result(sorted[i], plan.id_bits, a.out_ids + (size_t)b * a.k + i, a.out_scores + (size_t)b * a.k + i);
     } else {
         uint64_t* dst = a.partial + ((size_t)b * slices + s) * a.k;
-        for (uint32_t i = threadIdx.x; i < a.k; i += TOPK_THREADS) dst[i] = sorted[i];
+        for (uint32_t i = threadIdx.x; i < a.k; i += T) dst[i] = sorted[i];
     }
 }
 
@@ -211,10 +214,14 @@ __global__ __launch_bounds__(TOPK_EMIT_THREADS) void topk_lists_emit_kernel(cons
 }
 
 static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the selection state is another 8.3 KB)
-    static hipError_t a0 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint32_t>,
+    static hipError_t a0 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint32_t, TOPK_THREADS, 8>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
-    static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint64_t>,
+    static hipError_t a1 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint64_t, TOPK_THREADS, 8>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a9 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint32_t, TOPK_THREADS_SHORT, 4>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
+    static hipError_t a10 = hipFuncSetAttribute((const void*)topk_scores_kernel<uint64_t, TOPK_THREADS_SHORT, 4>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a2 = hipFuncSetAttribute((const void*)topk_merge_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     static hipError_t a3 = hipFuncSetAttribute((const void*)topk_lists_kernel<uint64_t, true>,
@@ -230,7 +237,7 @@ static hipError_t allow_large_k() {  // large k: opt in to more dynamic LDS (the
     static hipError_t a8 = hipFuncSetAttribute((const void*)topk_lists_plan_kernel<uint32_t>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TOPK_KMAX * 8);
     return a0 != hipSuccess ? a0 : a1 != hipSuccess ? a1 : a2 != hipSuccess ? a2 : a3 != hipSuccess ? a3 : a4 != hipSuccess ? a4
-           : a5 != hipSuccess ? a5 : a6 != hipSuccess ? a6 : a7 != hipSuccess ? a7 : a8;
+           : a5 != hipSuccess ? a5 : a6 != hipSuccess ? a6 : a7 != hipSuccess ? a7 : a8 != hipSuccess ? a8 : a9 != hipSuccess ? a9 : a10;
 }
 
 hipError_t launch_topk_lists(const uint64_t* lists, uint64_t list_stride, const uint32_t* counts, uint32_t n_queries,
@@ -295,12 +302,22 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t stream) {
         hipError_t e = allow_large_k();
         if (e != hipSuccess) return e;
     }
-    if (keys_fit_32(a.max_score, a.n_docs ? a.n_docs - 1 : 0))
-        hipLaunchKernelGGL(topk_scores_kernel<uint32_t>, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a,
-                           plan, slices, kpad);
-    else
-        hipLaunchKernelGGL(topk_scores_kernel<uint64_t>, dim3(slices, a.n_queries), dim3(TOPK_THREADS), lds, stream, a,
-                           plan, slices, kpad);
+    const bool fit32 = keys_fit_32(a.max_score, a.n_docs ? a.n_docs - 1 : 0);
+    const dim3 grid(slices, a.n_queries);
+    // every slice short enough to stay in the registers of the wider workgroup (see topk_scores_kernel)
+    if ((a.max_scored + slices - 1) / slices <= (uint64_t)TOPK_THREADS_SHORT * 4) {
+        if (fit32)
+            hipLaunchKernelGGL((topk_scores_kernel<uint32_t, TOPK_THREADS_SHORT, 4>), grid, dim3(TOPK_THREADS_SHORT), lds, stream, a, plan,
+                               slices, kpad);
+        else
+            hipLaunchKernelGGL((topk_scores_kernel<uint64_t, TOPK_THREADS_SHORT, 4>), grid, dim3(TOPK_THREADS_SHORT), lds, stream, a, plan,
+                               slices, kpad);
+    } else {
+        if (fit32)
+            hipLaunchKernelGGL((topk_scores_kernel<uint32_t, TOPK_THREADS, 8>), grid, dim3(TOPK_THREADS), lds, stream, a, plan, slices, kpad);
+        else
+            hipLaunchKernelGGL((topk_scores_kernel<uint64_t, TOPK_THREADS, 8>), grid, dim3(TOPK_THREADS), lds, stream, a, plan, slices, kpad);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
     hipLaunchKernelGGL(topk_merge_kernel, dim3(a.n_queries), dim3(TOPK_THREADS), lds, stream, a, plan, slices, kpad);
