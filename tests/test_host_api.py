@@ -79,3 +79,14 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no fallback", ""), (dirpath, f)
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    """Nothing here uses a second GPU: the benchmark says so instead of running a single-GPU job under another label."""
+    import pathlib
+    import subprocess
+    import sys
+    bench = pathlib.Path(__file__).resolve().parent.parent / "bench.py"
+    r = subprocess.run([sys.executable, str(bench), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
